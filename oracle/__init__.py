@@ -1,0 +1,159 @@
+"""fp64 CPU oracle for the RunLoRA layer (arxiv 2312.03415): TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the bench's cpu_baseline leg may import this package.  It
+shares nothing with the HIP path and never imports it.  The arithmetic lives in
+runlora_oracle.c (plain C, naive loops); this module only marshals numpy arrays into it.
+
+Shapes (paper's notation, Section 2): X [n,i], W [i,o], A [i,r], B [r,o], Y/dY [n,o],
+dX [n,i], dA [i,r], dB [r,o]; everything float64, C-contiguous.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+FWD_DEFAULT, FWD1, FWD2 = 0, 1, 2
+BWD_DEFAULT = 0  # 1..5 = Algorithms 1-5, 6..8 = remaining bracketings of Section 2
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if (not os.path.exists(path)) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
+            path = _build.build()
+        L = ctypes.CDLL(path)
+        i64, dp, ci = ctypes.c_int64, ctypes.POINTER(ctypes.c_double), ctypes.c_int
+        L.orc_flops_reset.restype = None
+        L.orc_flops_get.restype = ctypes.c_longlong
+        L.orc_num_threads.restype = ci
+        L.orc_matmul.argtypes = [ci, ci, i64, i64, i64, dp, i64, dp, i64, dp, i64, ci]
+        L.orc_matmul.restype = None
+        L.orc_reference_forward.argtypes = [i64] * 4 + [dp] * 5
+        L.orc_reference_forward.restype = None
+        L.orc_reference_backward.argtypes = [i64] * 4 + [dp] * 8
+        L.orc_reference_backward.restype = None
+        L.orc_forward.argtypes = [ci] + [i64] * 4 + [dp] * 6
+        L.orc_forward.restype = ci
+        L.orc_backward.argtypes = [ci] + [i64] * 4 + [dp] * 9
+        L.orc_backward.restype = ci
+        L.orc_dequant_int4.argtypes = [i64, i64, i64, ctypes.POINTER(ctypes.c_int8), dp, dp]
+        L.orc_dequant_int4.restype = None
+        L.orc_reference_rows.argtypes = [i64] * 4 + [dp] * 7
+        L.orc_reference_rows.restype = None
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    if a is None:
+        return None
+    assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _dims(X, W, A, B):
+    n, i = X.shape
+    i2, o = W.shape
+    i3, r = A.shape
+    r2, o2 = B.shape
+    assert i == i2 == i3 and o == o2 and r == r2, "shape mismatch"
+    return n, i, o, r
+
+
+def flops_reset():
+    lib().orc_flops_reset()
+
+
+def flops_get() -> int:
+    return int(lib().orc_flops_get())
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+def matmul(P, Q, ta=False, tb=False):
+    """op(P) @ op(Q) through the oracle's own naive routine."""
+    P, Q = _f64(P), _f64(Q)
+    m, k = (P.shape[1], P.shape[0]) if ta else P.shape
+    k2, n = (Q.shape[1], Q.shape[0]) if tb else Q.shape
+    assert k == k2
+    C = np.empty((m, n), dtype=np.float64)
+    lib().orc_matmul(int(ta), int(tb), m, n, k, _p(P), P.shape[1], _p(Q), Q.shape[1], _p(C), n, 0)
+    return C
+
+
+def reference_forward(X, W, A, B):
+    """Eq. 1 written out."""
+    X, W, A, B = map(_f64, (X, W, A, B))
+    n, i, o, r = _dims(X, W, A, B)
+    Y = np.empty((n, o))
+    lib().orc_reference_forward(n, i, o, r, _p(X), _p(W), _p(A), _p(B), _p(Y))
+    return Y
+
+
+def reference_backward(X, W, A, B, dY):
+    """Eq. 3 written out -> (dX, dA, dB)."""
+    X, W, A, B, dY = map(_f64, (X, W, A, B, dY))
+    n, i, o, r = _dims(X, W, A, B)
+    assert dY.shape == (n, o)
+    dX, dA, dB = np.empty((n, i)), np.empty((i, r)), np.empty((r, o))
+    lib().orc_reference_backward(n, i, o, r, _p(X), _p(W), _p(A), _p(B), _p(dY), _p(dX), _p(dA), _p(dB))
+    return dX, dA, dB
+
+
+def forward(variant, X, W, A, B):
+    """One forward graph -> (Y, T) with T = XA for the default chain (variant 0), else None."""
+    X, W, A, B = map(_f64, (X, W, A, B))
+    n, i, o, r = _dims(X, W, A, B)
+    Y = np.empty((n, o))
+    T = np.empty((n, r)) if variant == FWD_DEFAULT else None
+    rc = lib().orc_forward(variant, n, i, o, r, _p(X), _p(W), _p(A), _p(B), _p(Y), _p(T))
+    if rc != 0:
+        raise ValueError(f"oracle forward: bad variant {variant}")
+    return Y, T
+
+
+def backward(variant, X, W, A, B, dY, T=None):
+    """One backward graph -> (dX, dA, dB).  Variant 0 needs T = XA kept by forward variant 0."""
+    X, W, A, B, dY = map(_f64, (X, W, A, B, dY))
+    n, i, o, r = _dims(X, W, A, B)
+    assert dY.shape == (n, o)
+    if T is not None:
+        T = _f64(T)
+        assert T.shape == (n, r)
+    dX, dA, dB = np.empty((n, i)), np.empty((i, r)), np.empty((r, o))
+    rc = lib().orc_backward(variant, n, i, o, r, _p(X), _p(W), _p(A), _p(B), _p(dY), _p(T), _p(dX), _p(dA), _p(dB))
+    if rc != 0:
+        raise ValueError(f"oracle backward: bad variant {variant} (or missing T)")
+    return dX, dA, dB
+
+
+def dequant_int4(q, scale, group=64):
+    """W[k,j] = q[k,j] * scale[k // group, j]; q int8 in [-7,7] unpacked, scale float64."""
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    scale = _f64(scale)
+    i, o = q.shape
+    assert scale.shape == ((i + group - 1) // group, o)
+    W = np.empty((i, o))
+    lib().orc_dequant_int4(i, o, group, q.ctypes.data_as(ctypes.POINTER(ctypes.c_int8)), _p(scale), _p(W))
+    return W
+
+
+def reference_rows(Xrows, dYrows, W, A, B):
+    """Y and dX for a subset of token rows (rows are independent in Eq. 1 / Eq. 3's dX)."""
+    Xrows, dYrows, W, A, B = map(_f64, (Xrows, dYrows, W, A, B))
+    rows, i = Xrows.shape
+    o, r = W.shape[1], A.shape[1]
+    Y, dX = np.empty((rows, o)), np.empty((rows, i))
+    lib().orc_reference_rows(rows, i, o, r, _p(Xrows), _p(dYrows), _p(W), _p(A), _p(B), _p(Y), _p(dX))
+    return Y, dX
