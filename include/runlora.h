@@ -1,0 +1,218 @@
+/*
+ * runlora.h - C ABI of the MI355X (gfx950) LoRA-linear library.
+ *
+ * One layer of RunLoRA (arxiv 2312.03415, Section 2):
+ *     forward   Y  = X W + (X A) B                      (Eq. 1; W frozen)
+ *     backward  dA = X^T dY B^T,  dB = A^T X^T dY,
+ *               dX = dY W^T + dY B^T A^T                (Eq. 3; no dW)
+ * in each of the algebraically equivalent computation graphs the paper lists, plus the selector
+ * that picks a (forward, backward) pair per shape.
+ *
+ * Notation (Table 1 caption): n = b*s tokens, i = d_in, o = d_out, r = LoRA rank.
+ * All tensors are dense row-major DEVICE buffers described by rl_tensor_t:
+ *     X [n,i]  W [i,o]  A [i,r]  B [r,o]  Y,dY [n,o]  dX [n,i]  dA [i,r]  dB [r,o]
+ * (W is d_in x d_out because the paper writes Y = XW).
+ *
+ * Conventions shared by every entry point
+ *   - Pointers inside rl_tensor_t / rl_saved_t / rl_opts_t.workspace are device pointers; the
+ *     structs themselves and all int* outputs are host memory.
+ *   - The caller owns every buffer.  The library allocates no device memory, frees nothing and
+ *     keeps no pointer after a call returns, except those it writes into *saved.
+ *   - Work is enqueued on opts->stream (a hipStream_t; NULL = the default stream) and the call
+ *     returns without synchronising.  Buffers must stay alive until the stream has drained.
+ *   - Outputs are overwritten, never accumulated into.
+ *   - Return value: RL_OK (0) or a negative rl_status_t.  All argument checks happen before the
+ *     first HIP call, so they behave the same on a host without a GPU.  No exception crosses
+ *     the boundary.
+ *   - Element types: RL_F32, RL_F16, RL_BF16 for every tensor of a call (one type per call).
+ *     RL_INT4_G64 is allowed for W only (see rl_tensor_t).  Accumulation is fp32 throughout;
+ *     each result is rounded once (nearest even) to the storage type.
+ *   - Alignment: data pointers 16-byte aligned; ld (elements between rows) >= cols and a
+ *     multiple of 8 (16-bit types) or 4 (fp32); i, o and r multiples of 8 (16-bit) or 4 (fp32);
+ *     n is arbitrary (>= 1).  Anything else returns RL_ERR_ALIGN / RL_ERR_SHAPE.
+ */
+#ifndef RUNLORA_H
+#define RUNLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RL_F32 = 0,
+  RL_F16 = 1,
+  RL_BF16 = 2,
+  RL_INT4_G64 = 3 /* frozen W only: symmetric int4, one fp16 scale per 64 rows (d_in) per column */
+} rl_dtype_t;
+
+typedef enum {
+  RL_OK = 0,
+  RL_ERR_NULL = -1,           /* a required pointer is NULL                                   */
+  RL_ERR_SHAPE = -2,          /* dimensions of the tensors do not fit together, or are < 1    */
+  RL_ERR_DTYPE = -3,          /* unknown dtype, or tensors of one call differ in dtype        */
+  RL_ERR_VARIANT = -4,        /* unknown variant id                                           */
+  RL_ERR_SAVED_MISMATCH = -5, /* *saved does not come from a forward this backward can use    */
+  RL_ERR_ALIGN = -6,          /* pointer / ld / dimension alignment rule violated             */
+  RL_ERR_ALIAS = -7,          /* an output buffer overlaps an input buffer                    */
+  RL_ERR_WORKSPACE = -8,      /* workspace missing or smaller than runlora_workspace_bytes()  */
+  RL_ERR_UNSUPPORTED = -9,    /* legal request this build does not implement (e.g. merged-W   */
+                              /* graphs on an int4 W)                                         */
+  RL_ERR_HIP = -10            /* a HIP launch failed; runlora_last_hip_error() has the text   */
+} rl_status_t;
+
+/*
+ * Forward computation graphs (Section 2, "major forward variants", and the default chain that
+ * Section 2 contrasts them with).
+ */
+typedef enum {
+  RL_FWD_DEFAULT = 0, /* T = XA kept for the backward; Y = XW; Y += T B.  One kernel per product. */
+  RL_FWD1 = 1,        /* Y = (XW) + ((XA)B): T = XA, then one GEMM over the concatenated          */
+                      /* contraction [X|T] [W;B]; T is scratch, not kept.                         */
+  RL_FWD2 = 2         /* Y = X (W + AB): M = W + AB, then Y = X M  (Eq. 2).                       */
+} rl_fwd_variant_t;
+
+/*
+ * Backward computation graphs.  1..5 are Algorithms 1-5 of Section 2 (backward1..backward5).
+ * Where an algorithm ends with dX = dY W^T + Z1 A^T the two products run as one GEMM over the
+ * concatenated contraction [dY|Z1] [W^T;A^T].
+ */
+typedef enum {
+  RL_BWD_DEFAULT = 0, /* autograd's backward of the default chain; needs T from RL_FWD_DEFAULT:  */
+                      /* Z1 = dY B^T; dB = T^T dY; dA = X^T Z1; dX = dY W^T; dX += Z1 A^T.        */
+  RL_BWD1 = 1,
+  RL_BWD2 = 2,
+  RL_BWD3 = 3,
+  RL_BWD4 = 4,
+  RL_BWD5 = 5
+} rl_bwd_variant_t;
+
+/*
+ * A dense row-major matrix in device memory.
+ *   data   device pointer to element (0,0); for RL_INT4_G64: packed nibbles, two per byte, element
+ *          (k,j) in byte (k*ld + j)/2, low nibble for even j, value = nibble - 8 in [-7,7]
+ *   rows, cols, ld   in elements; ld = distance between consecutive rows
+ *   dtype  rl_dtype_t
+ *   scales RL_INT4_G64 only: device pointer to fp16 scales [ceil(rows/64), cols], row-major, dense
+ *   group  RL_INT4_G64 only: must be 64
+ */
+typedef struct {
+  void* data;
+  int64_t rows, cols, ld;
+  int32_t dtype;
+  void* scales;
+  int32_t group;
+} rl_tensor_t;
+
+/*
+ * What a forward leaves for its backward (Section 2: RunLoRA forwards keep X but not XA).
+ * Filled by runlora_forward; read by runlora_backward.  X is borrowed: the caller keeps the
+ * buffer alive and unchanged until the backward has run.
+ *   T  caller-provided [n,r] buffer (ldt elements per row, same dtype as X).  Set T/ldt BEFORE
+ *      calling runlora_forward(RL_FWD_DEFAULT, ...), which fills it with XA; other variants
+ *      ignore it and set it to NULL.
+ */
+typedef struct {
+  int32_t fwd_variant, dtype;
+  int64_t n, i, o, r;
+  const void* X;
+  int64_t ldx;
+  void* T;
+  int64_t ldt;
+} rl_saved_t;
+
+/*
+ * Per-call options.  workspace is device scratch of at least runlora_workspace_bytes() bytes for
+ * the variant and shape of the call, 256-byte aligned; its contents are undefined afterwards.
+ * Two calls that share a workspace must be ordered on one stream.
+ */
+typedef struct {
+  void* stream;
+  void* workspace;
+  size_t workspace_bytes;
+} rl_opts_t;
+
+/*
+ * Forward pass in computation graph `variant` (rl_fwd_variant_t): Y = XW + (XA)B  (Eq. 1).
+ * X, W, A, B are inputs (device), Y is overwritten, *saved (host struct) is filled.
+ * opts may be NULL only if the variant needs no workspace and the default stream is meant.
+ */
+int runlora_forward(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
+                    const rl_tensor_t* B, rl_tensor_t* Y, rl_saved_t* saved, const rl_opts_t* opts);
+
+/*
+ * Backward pass in computation graph `variant` (rl_bwd_variant_t): the gradients of Eq. 3.
+ * dY [n,o] and *saved (from the forward) are inputs together with W, A, B; dX, dA, dB are
+ * overwritten.  Any of dX / dA / dB may be NULL: that gradient is skipped.
+ * RL_BWD_DEFAULT requires saved->fwd_variant == RL_FWD_DEFAULT (it reads saved->T).
+ */
+int runlora_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved,
+                     const rl_tensor_t* W, const rl_tensor_t* A, const rl_tensor_t* B,
+                     rl_tensor_t* dX, rl_tensor_t* dA, rl_tensor_t* dB, const rl_opts_t* opts);
+
+/*
+ * Choose the (forward, backward) pair for one layer shape ("choosing best forward and backward
+ * computation graph based on FLOPs and time estimations", abstract).  Pure host function,
+ * thread-safe, no HIP call.  Uses the time model unless the environment variable
+ * RUNLORA_CRITERION=flops asks for the Table 1 FLOP criterion.  dtype is the activation dtype;
+ * pass RL_INT4_G64 to restrict the choice to the graphs an int4 W supports.
+ */
+int runlora_select(int64_t n_tokens, int64_t d_in, int64_t d_out, int64_t r, int dtype,
+                   int* fwd_variant, int* bwd_variant);
+
+/* Same, with the criterion explicit: 0 = Table 1 FLOPs (ties -> lower id), 1 = time model. */
+int runlora_select_by(int criterion, int64_t n_tokens, int64_t d_in, int64_t d_out, int64_t r,
+                      int dtype, int* fwd_variant, int* bwd_variant);
+
+/*
+ * Table 1 closed forms.  is_bwd = 0: variant 1,2 = forward1,2 (0 = default chain = forward1's
+ * products).  is_bwd = 1: variant 1..8 = backward1..8 (0 = default chain = backward1 minus the
+ * XA recompute).  Returns -1 for an unknown variant.
+ */
+int64_t runlora_flops(int is_bwd, int variant, int64_t n, int64_t i, int64_t o, int64_t r);
+
+/* Modelled time in microseconds of one variant on MI355X (what criterion 1 minimises);
+ * negative for an unknown variant. */
+double runlora_model_time_us(int is_bwd, int variant, int64_t n, int64_t i, int64_t o, int64_t r,
+                             int dtype);
+
+/* Scratch bytes needed by a forward variant (bwd < 0), a backward variant (fwd < 0), or the
+ * larger of the two.  w_dtype is W's dtype (RL_INT4_G64 or the same as dtype). */
+size_t runlora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r,
+                               int dtype);
+
+/*
+ * The building block every step above is made of, exposed for tests, tuning and calibration of
+ * the selector's time model:  C[M,N] = op(A)[M,K] op(B)[K,N] (+ op(A2)[M,K2] op(B2)[K2,N]) (+ D)
+ * on the matrix cores with fp32 accumulation.
+ *   a_strided  0: A (and A2) stored [M,K] row-major;  1: stored [K,M]   (X^T dY style)
+ *   b_kcontig  0: B (and B2) stored [K,N] row-major;  1: stored [N,K]   (dY W^T style)
+ *              (a_strided = 1 with b_kcontig = 1 is not provided)
+ *   K2 = 0     no second segment.   D = NULL: no addend (D may alias C).
+ *   tile_cfg   -1 = library heuristic, else 0..5 = 256x256, 128x128, 128x32, 128x64, 32x128,
+ *              64x128 output tile per workgroup
+ *   splits     0 = heuristic, n > 0 = split the contraction n ways (fp32 partials in the
+ *              workspace, summed in a fixed order; needs K2 = 0)
+ * Same dtype / alignment rules as the layer calls (M arbitrary when A is [M,K]; every other
+ * dimension a multiple of 8, or 4 for fp32).  Workspace: runlora_gemm_workspace_bytes().
+ */
+typedef struct {
+  int32_t dtype, a_strided, b_kcontig, tile_cfg, splits;
+  int64_t M, N, K, K2;
+  const void *A, *B, *A2, *B2, *D;
+  void* C;
+  int64_t lda, ldb, lda2, ldb2, ldc, ldd;
+} rl_gemm_t;
+int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts);
+size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g);
+
+const char* runlora_strerror(int code);
+const char* runlora_last_hip_error(void); /* text of the last RL_ERR_HIP on this thread */
+int runlora_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RUNLORA_H */

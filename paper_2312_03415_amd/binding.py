@@ -1,0 +1,231 @@
+"""ctypes binding of librunlora.so (include/runlora.h): argument marshalling only.
+
+Every step of the layer runs inside the HIP library; torch is used for device memory and for the
+current stream.  There is no fallback: if the library is missing, loading raises.
+
+    runlora_forward(variant, X, W, A, B, Y, saved, workspace=None, stream=None)
+    runlora_backward(variant, dY, saved, W, A, B, dX, dA, dB, workspace=None, stream=None)
+    runlora_select(n_tokens, d_in, d_out, r, dtype) -> (fwd, bwd)
+
+Tensors are 2-D torch tensors on the GPU (row-major, last dimension contiguous):
+X [n,i], W [i,o], A [i,r], B [r,o], Y/dY [n,o], dX [n,i], dA [i,r], dB [r,o]  (Section 2 of
+arxiv 2312.03415: Y = XW + (XA)B, W frozen).
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librunlora.so")
+
+RL_F32, RL_F16, RL_BF16, RL_INT4_G64 = 0, 1, 2, 3
+FWD_DEFAULT, FWD1, FWD2 = 0, 1, 2
+BWD_DEFAULT, BWD1, BWD2, BWD3, BWD4, BWD5 = 0, 1, 2, 3, 4, 5
+FWD_VARIANTS = (FWD_DEFAULT, FWD1, FWD2)
+BWD_VARIANTS = (BWD_DEFAULT, BWD1, BWD2, BWD3, BWD4, BWD5)
+
+RL_OK = 0
+RL_ERR_NULL, RL_ERR_SHAPE, RL_ERR_DTYPE, RL_ERR_VARIANT, RL_ERR_SAVED_MISMATCH = -1, -2, -3, -4, -5
+RL_ERR_ALIGN, RL_ERR_ALIAS, RL_ERR_WORKSPACE, RL_ERR_UNSUPPORTED, RL_ERR_HIP = -6, -7, -8, -9, -10
+
+EXPORTS = (
+    "runlora_forward", "runlora_backward", "runlora_select", "runlora_select_by", "runlora_flops",
+    "runlora_model_time_us", "runlora_workspace_bytes", "runlora_strerror", "runlora_last_hip_error",
+    "runlora_version", "runlora_gemm", "runlora_gemm_workspace_bytes",
+)
+
+
+class rl_tensor_t(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("ld", ctypes.c_int64), ("dtype", ctypes.c_int32), ("scales", ctypes.c_void_p),
+                ("group", ctypes.c_int32)]
+
+
+class rl_saved_t(ctypes.Structure):
+    _fields_ = [("fwd_variant", ctypes.c_int32), ("dtype", ctypes.c_int32), ("n", ctypes.c_int64),
+                ("i", ctypes.c_int64), ("o", ctypes.c_int64), ("r", ctypes.c_int64),
+                ("X", ctypes.c_void_p), ("ldx", ctypes.c_int64), ("T", ctypes.c_void_p),
+                ("ldt", ctypes.c_int64)]
+
+
+class rl_opts_t(ctypes.Structure):
+    _fields_ = [("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+class rl_gemm_t(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("a_strided", ctypes.c_int32), ("b_kcontig", ctypes.c_int32),
+                ("tile_cfg", ctypes.c_int32), ("splits", ctypes.c_int32),
+                ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("K2", ctypes.c_int64),
+                ("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("A2", ctypes.c_void_p), ("B2", ctypes.c_void_p),
+                ("D", ctypes.c_void_p), ("C", ctypes.c_void_p),
+                ("lda", ctypes.c_int64), ("ldb", ctypes.c_int64), ("lda2", ctypes.c_int64), ("ldb2", ctypes.c_int64),
+                ("ldc", ctypes.c_int64), ("ldd", ctypes.c_int64)]
+
+
+class RunLoRAError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"runlora error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load librunlora.so (built by `python -m paper_2312_03415_amd.build`).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2312_03415_amd.build` (no CPU fallback exists)")
+    L = ctypes.CDLL(LIB_PATH)
+    tp, sp, op = ctypes.POINTER(rl_tensor_t), ctypes.POINTER(rl_saved_t), ctypes.POINTER(rl_opts_t)
+    i64, ci, ip = ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_int)
+    L.runlora_forward.argtypes = [ci, tp, tp, tp, tp, tp, sp, op]
+    L.runlora_forward.restype = ci
+    L.runlora_backward.argtypes = [ci, tp, sp, tp, tp, tp, tp, tp, tp, op]
+    L.runlora_backward.restype = ci
+    L.runlora_select.argtypes = [i64, i64, i64, i64, ci, ip, ip]
+    L.runlora_select.restype = ci
+    L.runlora_select_by.argtypes = [ci, i64, i64, i64, i64, ci, ip, ip]
+    L.runlora_select_by.restype = ci
+    L.runlora_flops.argtypes = [ci, ci, i64, i64, i64, i64]
+    L.runlora_flops.restype = i64
+    L.runlora_model_time_us.argtypes = [ci, ci, i64, i64, i64, i64, ci]
+    L.runlora_model_time_us.restype = ctypes.c_double
+    L.runlora_workspace_bytes.argtypes = [ci, ci, i64, i64, i64, i64, ci]
+    L.runlora_workspace_bytes.restype = ctypes.c_size_t
+    L.runlora_strerror.argtypes = [ci]
+    L.runlora_strerror.restype = ctypes.c_char_p
+    L.runlora_last_hip_error.argtypes = []
+    L.runlora_last_hip_error.restype = ctypes.c_char_p
+    L.runlora_version.argtypes = []
+    L.runlora_version.restype = ci
+    L.runlora_gemm.argtypes = [ctypes.POINTER(rl_gemm_t), op]
+    L.runlora_gemm.restype = ci
+    L.runlora_gemm_workspace_bytes.argtypes = [ctypes.POINTER(rl_gemm_t)]
+    L.runlora_gemm_workspace_bytes.restype = ctypes.c_size_t
+    _lib = L
+    return L
+
+
+def _check(code):
+    if code != RL_OK:
+        L = lib()
+        text = L.runlora_strerror(code).decode()
+        if code == RL_ERR_HIP:
+            text += " (" + L.runlora_last_hip_error().decode() + ")"
+        raise RunLoRAError(code, text)
+
+
+def dtype_code(torch_dtype):
+    import torch
+    return {torch.float32: RL_F32, torch.float16: RL_F16, torch.bfloat16: RL_BF16}[torch_dtype]
+
+
+def dtype_from_name(name):
+    return {"f32": RL_F32, "f16": RL_F16, "bf16": RL_BF16, "int4": RL_INT4_G64}[name]
+
+
+def tensor_desc(t):
+    """rl_tensor_t view of a 2-D torch tensor (None -> NULL pointer argument)."""
+    if t is None:
+        return None
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("expected a 2-D tensor with contiguous rows")
+    return rl_tensor_t(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), dtype_code(t.dtype), None, 0)
+
+
+def _opts(workspace, stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    return rl_opts_t(stream, ws_ptr, ws_bytes)
+
+
+def _ref(desc):
+    return ctypes.byref(desc) if desc is not None else None
+
+
+def runlora_forward(variant, X, W, A, B, Y, saved, workspace=None, stream=None):
+    """Y = XW + (XA)B in forward graph `variant`; fills `saved` (rl_saved_t).  For FWD_DEFAULT set
+    saved.T / saved.ldt to an [n,r] buffer first (see new_saved)."""
+    dx, dw, da, db, dy = (tensor_desc(t) for t in (X, W, A, B, Y))
+    o = _opts(workspace, stream)
+    _check(lib().runlora_forward(variant, _ref(dx), _ref(dw), _ref(da), _ref(db), _ref(dy), ctypes.byref(saved),
+                                 ctypes.byref(o)))
+    return Y
+
+
+def runlora_backward(variant, dY, saved, W, A, B, dX, dA, dB, workspace=None, stream=None):
+    """Gradients of Eq. 3 in backward graph `variant`; any of dX/dA/dB may be None (skipped)."""
+    ddy, dw, da, db = (tensor_desc(t) for t in (dY, W, A, B))
+    gx, ga, gb = tensor_desc(dX), tensor_desc(dA), tensor_desc(dB)
+    o = _opts(workspace, stream)
+    _check(lib().runlora_backward(variant, _ref(ddy), ctypes.byref(saved), _ref(dw), _ref(da), _ref(db), _ref(gx),
+                                  _ref(ga), _ref(gb), ctypes.byref(o)))
+    return dX, dA, dB
+
+
+def runlora_select(n_tokens, d_in, d_out, r, dtype, criterion=None):
+    """(fwd, bwd) for a layer shape.  criterion None = library default (time model unless
+    RUNLORA_CRITERION=flops), 0 = Table 1 FLOPs, 1 = time model."""
+    f, b = ctypes.c_int(-1), ctypes.c_int(-1)
+    if criterion is None:
+        _check(lib().runlora_select(n_tokens, d_in, d_out, r, dtype, ctypes.byref(f), ctypes.byref(b)))
+    else:
+        _check(lib().runlora_select_by(criterion, n_tokens, d_in, d_out, r, dtype, ctypes.byref(f), ctypes.byref(b)))
+    return f.value, b.value
+
+
+def runlora_flops(is_bwd, variant, n, i, o, r):
+    return int(lib().runlora_flops(int(is_bwd), variant, n, i, o, r))
+
+
+def runlora_model_time_us(is_bwd, variant, n, i, o, r, dtype):
+    return float(lib().runlora_model_time_us(int(is_bwd), variant, n, i, o, r, dtype))
+
+
+def runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype):
+    return int(lib().runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype))
+
+
+def runlora_gemm(A, B, C, a_strided=False, b_kcontig=False, A2=None, B2=None, D=None, tile_cfg=-1, splits=0,
+                 workspace=None, stream=None):
+    """C = op(A) op(B) (+ op(A2) op(B2)) (+ D) through the library's tile GEMM (see runlora.h)."""
+    import torch
+    M = A.shape[1] if a_strided else A.shape[0]
+    K = A.shape[0] if a_strided else A.shape[1]
+    N = B.shape[0] if b_kcontig else B.shape[1]
+    K2 = 0
+    if A2 is not None:
+        K2 = A2.shape[0] if a_strided else A2.shape[1]
+    g = rl_gemm_t(dtype_code(A.dtype), int(a_strided), int(b_kcontig), tile_cfg, splits, M, N, K, K2,
+                  A.data_ptr(), B.data_ptr(), A2.data_ptr() if A2 is not None else None,
+                  B2.data_ptr() if B2 is not None else None, D.data_ptr() if D is not None else None, C.data_ptr(),
+                  A.stride(0), B.stride(0), A2.stride(0) if A2 is not None else 0,
+                  B2.stride(0) if B2 is not None else 0, C.stride(0), D.stride(0) if D is not None else 0)
+    need = int(lib().runlora_gemm_workspace_bytes(ctypes.byref(g)))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=C.device)
+    o = _opts(workspace, stream)
+    _check(lib().runlora_gemm(ctypes.byref(g), ctypes.byref(o)))
+    return C
+
+
+# ---- conveniences on top of the ABI (device memory only) --------------------------------------
+
+def new_saved(T=None):
+    s = rl_saved_t()
+    if T is not None:
+        s.T = T.data_ptr()
+        s.ldt = T.stride(0)
+    return s
+
+
+def new_workspace(fwd, bwd, n, i, o, r, dtype, device="cuda"):
+    import torch
+    nbytes = runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)

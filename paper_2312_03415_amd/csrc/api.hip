@@ -1,0 +1,294 @@
+// C ABI of the library (include/runlora.h): argument checks, variant schedules -> launches.
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/runlora.h"
+#include "schedule.hpp"
+
+using namespace rl;
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int set_hip_error(hipError_t e, const char* what) {
+  std::snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+  return RL_ERR_HIP;
+}
+
+int internal_dtype(int dtype) {
+  switch (dtype) {
+    case RL_F32: return DT_F32;
+    case RL_F16: return DT_F16;
+    case RL_BF16: return DT_BF16;
+    default: return -1;
+  }
+}
+
+// shape / dtype / alignment rules of one dense tensor
+int check_tensor(const rl_tensor_t* t, int64_t rows, int64_t cols, int dtype) {
+  if (!t || !t->data) return RL_ERR_NULL;
+  if (t->dtype != dtype) return RL_ERR_DTYPE;
+  if (t->rows != rows || t->cols != cols || t->ld < t->cols) return RL_ERR_SHAPE;
+  const int64_t q = dtype == RL_F32 ? 4 : 8;
+  if ((reinterpret_cast<uintptr_t>(t->data) & 15) != 0 || t->ld % q != 0) return RL_ERR_ALIGN;
+  return RL_OK;
+}
+
+int check_dims(int64_t n, int64_t i, int64_t o, int64_t r, int dtype) {
+  if (n < 1 || i < 1 || o < 1 || r < 1) return RL_ERR_SHAPE;
+  if (n > (1LL << 30) || i > (1LL << 30) || o > (1LL << 30) || r > (1LL << 30)) return RL_ERR_SHAPE;
+  const int64_t q = dtype == RL_F32 ? 4 : 8;
+  if (i % q || o % q || r % q) return RL_ERR_ALIGN;
+  return RL_OK;
+}
+
+struct Range {
+  const char* lo;
+  const char* hi;
+};
+Range range_of(const void* p, int64_t rows, int64_t ld, int64_t cols, size_t esz) {
+  const char* lo = static_cast<const char*>(p);
+  return {lo, lo + ((size_t)(rows - 1) * (size_t)ld + (size_t)cols) * esz};
+}
+bool overlap(Range a, Range b) { return a.lo < b.hi && b.lo < a.hi; }
+
+Mat mat(const rl_tensor_t* t) {
+  Mat m;
+  m.ptr = t->data;
+  m.ld = t->ld;
+  return m;
+}
+
+int run_schedule(const Schedule& sch, char* ws, hipStream_t stream) {
+  float* partial = ws ? reinterpret_cast<float*>(ws + sch.partial_offset) : nullptr;
+  for (const Step& s : sch.steps) {
+    hipError_t e = gemm_run(s.d, s.plan, partial, stream);
+    if (e != hipSuccess) return set_hip_error(e, s.what);
+  }
+  return RL_OK;
+}
+
+int check_workspace(const Schedule& sch, const rl_opts_t* opts) {
+  if (sch.workspace_bytes == 0) return RL_OK;
+  if (!opts || !opts->workspace || opts->workspace_bytes < sch.workspace_bytes) return RL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(opts->workspace) & 255) != 0) return RL_ERR_ALIGN;
+  return RL_OK;
+}
+
+}  // namespace
+
+extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
+                               const rl_tensor_t* B, rl_tensor_t* Y, rl_saved_t* saved, const rl_opts_t* opts) {
+  if (!X || !W || !A || !B || !Y || !saved) return RL_ERR_NULL;
+  if (variant < RL_FWD_DEFAULT || variant > RL_FWD2) return RL_ERR_VARIANT;
+  const int dtype = X->dtype;
+  const int dt = internal_dtype(dtype);
+  if (dt < 0) return RL_ERR_DTYPE;
+  if (W->dtype == RL_INT4_G64) return RL_ERR_UNSUPPORTED;
+  const int64_t n = X->rows, i = X->cols, o = W->cols, r = A->cols;
+  int rc;
+  if ((rc = check_dims(n, i, o, r, dtype)) != RL_OK) return rc;
+  if ((rc = check_tensor(X, n, i, dtype)) != RL_OK) return rc;
+  if ((rc = check_tensor(W, i, o, dtype)) != RL_OK) return rc;
+  if ((rc = check_tensor(A, i, r, dtype)) != RL_OK) return rc;
+  if ((rc = check_tensor(B, r, o, dtype)) != RL_OK) return rc;
+  if ((rc = check_tensor(Y, n, o, dtype)) != RL_OK) return rc;
+  const size_t esz = dtype_size(dt);
+  Range ry = range_of(Y->data, n, Y->ld, o, esz);
+  if (overlap(ry, range_of(X->data, n, X->ld, i, esz)) || overlap(ry, range_of(W->data, i, W->ld, o, esz)) ||
+      overlap(ry, range_of(A->data, i, A->ld, r, esz)) || overlap(ry, range_of(B->data, r, B->ld, o, esz)))
+    return RL_ERR_ALIAS;
+
+  LayerDims L{n, i, o, r, dt};
+  FwdOperands op;
+  op.X = mat(X); op.W = mat(W); op.A = mat(A); op.B = mat(B); op.Y = mat(Y);
+  if (variant == RL_FWD_DEFAULT) {
+    if (!saved->T) return RL_ERR_NULL;
+    const int64_t q = dtype == RL_F32 ? 4 : 8;
+    if (saved->ldt < r) return RL_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(saved->T) & 15) != 0 || saved->ldt % q != 0) return RL_ERR_ALIGN;
+    Range rt = range_of(saved->T, n, saved->ldt, r, esz);
+    if (overlap(rt, ry) || overlap(rt, range_of(X->data, n, X->ld, i, esz))) return RL_ERR_ALIAS;
+    op.T.ptr = saved->T;
+    op.T.ld = saved->ldt;
+  }
+  Schedule sch;
+  char* ws = opts ? static_cast<char*>(opts->workspace) : nullptr;
+  if (!build_forward(variant, L, op, ws, &sch)) return RL_ERR_VARIANT;
+  if ((rc = check_workspace(sch, opts)) != RL_OK) return rc;
+
+  hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
+  rc = run_schedule(sch, ws, stream);
+  if (rc != RL_OK) return rc;
+
+  saved->fwd_variant = variant;
+  saved->dtype = dtype;
+  saved->n = n; saved->i = i; saved->o = o; saved->r = r;
+  saved->X = X->data;
+  saved->ldx = X->ld;
+  if (variant != RL_FWD_DEFAULT) { saved->T = nullptr; saved->ldt = 0; }
+  return RL_OK;
+}
+
+extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved, const rl_tensor_t* W,
+                                const rl_tensor_t* A, const rl_tensor_t* B, rl_tensor_t* dX, rl_tensor_t* dA,
+                                rl_tensor_t* dB, const rl_opts_t* opts) {
+  if (!dY || !saved || !W || !A || !B) return RL_ERR_NULL;
+  if (variant < RL_BWD_DEFAULT || variant > RL_BWD5) return RL_ERR_VARIANT;
+  const int dtype = dY->dtype;
+  const int dt = internal_dtype(dtype);
+  if (dt < 0) return RL_ERR_DTYPE;
+  if (W->dtype == RL_INT4_G64) return RL_ERR_UNSUPPORTED;
+  const int64_t n = dY->rows, o = dY->cols, i = W->rows, r = A->cols;
+  int rc;
+  if ((rc = check_dims(n, i, o, r, dtype)) != RL_OK) return rc;
+  if ((rc = check_tensor(dY, n, o, dtype)) != RL_OK) return rc;
+  if ((rc = check_tensor(W, i, o, dtype)) != RL_OK) return rc;
+  if ((rc = check_tensor(A, i, r, dtype)) != RL_OK) return rc;
+  if ((rc = check_tensor(B, r, o, dtype)) != RL_OK) return rc;
+  if (dX && (rc = check_tensor(dX, n, i, dtype)) != RL_OK) return rc;
+  if (dA && (rc = check_tensor(dA, i, r, dtype)) != RL_OK) return rc;
+  if (dB && (rc = check_tensor(dB, r, o, dtype)) != RL_OK) return rc;
+  // the forward's record must describe this very layer
+  if (saved->fwd_variant < RL_FWD_DEFAULT || saved->fwd_variant > RL_FWD2) return RL_ERR_SAVED_MISMATCH;
+  if (saved->dtype != dtype || saved->n != n || saved->i != i || saved->o != o || saved->r != r)
+    return RL_ERR_SAVED_MISMATCH;
+  if (!saved->X) return RL_ERR_NULL;
+  const int64_t q = dtype == RL_F32 ? 4 : 8;
+  if (saved->ldx < i) return RL_ERR_SAVED_MISMATCH;
+  if ((reinterpret_cast<uintptr_t>(saved->X) & 15) != 0 || saved->ldx % q != 0) return RL_ERR_ALIGN;
+  if (variant == RL_BWD_DEFAULT) {
+    if (saved->fwd_variant != RL_FWD_DEFAULT || !saved->T || saved->ldt < r) return RL_ERR_SAVED_MISMATCH;
+    if ((reinterpret_cast<uintptr_t>(saved->T) & 15) != 0 || saved->ldt % q != 0) return RL_ERR_ALIGN;
+  }
+  const size_t esz = dtype_size(dt);
+  Range in[6] = {range_of(dY->data, n, dY->ld, o, esz), range_of(saved->X, n, saved->ldx, i, esz),
+                 range_of(W->data, i, W->ld, o, esz), range_of(A->data, i, A->ld, r, esz),
+                 range_of(B->data, r, B->ld, o, esz),
+                 (variant == RL_BWD_DEFAULT) ? range_of(saved->T, n, saved->ldt, r, esz) : Range{nullptr, nullptr}};
+  Range outr[3];
+  int nout = 0;
+  if (dX) outr[nout++] = range_of(dX->data, n, dX->ld, i, esz);
+  if (dA) outr[nout++] = range_of(dA->data, i, dA->ld, r, esz);
+  if (dB) outr[nout++] = range_of(dB->data, r, dB->ld, o, esz);
+  for (int a = 0; a < nout; ++a) {
+    for (int b = 0; b < 6; ++b)
+      if (in[b].lo && overlap(outr[a], in[b])) return RL_ERR_ALIAS;
+    for (int b = a + 1; b < nout; ++b)
+      if (overlap(outr[a], outr[b])) return RL_ERR_ALIAS;
+  }
+
+  LayerDims L{n, i, o, r, dt};
+  BwdOperands op;
+  op.dY = mat(dY); op.W = mat(W); op.A = mat(A); op.B = mat(B);
+  op.X.ptr = saved->X; op.X.ld = saved->ldx;
+  op.T.ptr = saved->T; op.T.ld = saved->ldt;
+  op.want_dX = dX != nullptr; op.want_dA = dA != nullptr; op.want_dB = dB != nullptr;
+  if (dX) op.dX = mat(dX);
+  if (dA) op.dA = mat(dA);
+  if (dB) op.dB = mat(dB);
+  Schedule sch;
+  char* ws = opts ? static_cast<char*>(opts->workspace) : nullptr;
+  if (!build_backward(variant, L, op, ws, &sch)) return RL_ERR_VARIANT;
+  if ((rc = check_workspace(sch, opts)) != RL_OK) return rc;
+  hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
+  return run_schedule(sch, ws, stream);
+}
+
+extern "C" size_t runlora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype) {
+  const int dt = internal_dtype(dtype);
+  if (dt < 0 || n < 1 || i < 1 || o < 1 || r < 1) return 0;
+  LayerDims L{n, i, o, r, dt};
+  size_t need = 0;
+  Schedule sch;
+  if (fwd >= 0) {
+    FwdOperands op;
+    if (build_forward(fwd, L, op, nullptr, &sch) && sch.workspace_bytes > need) need = sch.workspace_bytes;
+  }
+  if (bwd >= 0) {
+    BwdOperands op;
+    if (build_backward(bwd, L, op, nullptr, &sch) && sch.workspace_bytes > need) need = sch.workspace_bytes;
+  }
+  return need;
+}
+
+extern "C" const char* runlora_strerror(int code) {
+  switch (code) {
+    case RL_OK: return "ok";
+    case RL_ERR_NULL: return "a required pointer is NULL";
+    case RL_ERR_SHAPE: return "tensor dimensions do not fit together";
+    case RL_ERR_DTYPE: return "unknown dtype or mixed dtypes in one call";
+    case RL_ERR_VARIANT: return "unknown variant id";
+    case RL_ERR_SAVED_MISMATCH: return "saved context does not match this backward";
+    case RL_ERR_ALIGN: return "pointer, leading dimension or dimension violates the alignment rules";
+    case RL_ERR_ALIAS: return "an output buffer overlaps an input buffer";
+    case RL_ERR_WORKSPACE: return "workspace missing or too small";
+    case RL_ERR_UNSUPPORTED: return "request not supported by this build";
+    case RL_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+extern "C" const char* runlora_last_hip_error(void) { return g_hip_error; }
+extern "C" int runlora_version(void) { return 100; }
+
+// ---- the tile GEMM as a call of its own ---------------------------------------------------------
+
+static int check_gemm(const rl_gemm_t* g, GemmDesc* d, GemmPlan* plan) {
+  if (!g || !g->A || !g->B || !g->C) return RL_ERR_NULL;
+  const int dt = internal_dtype(g->dtype);
+  if (dt < 0) return RL_ERR_DTYPE;
+  if (g->a_strided && g->b_kcontig) return RL_ERR_UNSUPPORTED;
+  if (g->M < 1 || g->N < 1 || g->K < 1 || g->K2 < 0) return RL_ERR_SHAPE;
+  if (g->M > (1LL << 30) || g->N > (1LL << 30) || g->K > (1LL << 30) || g->K2 > (1LL << 30)) return RL_ERR_SHAPE;
+  if (g->K2 > 0 && (!g->A2 || !g->B2)) return RL_ERR_NULL;
+  if (g->tile_cfg < -1 || g->tile_cfg >= CFG_COUNT || g->splits < 0) return RL_ERR_VARIANT;
+  if (g->splits > 1 && g->K2 > 0) return RL_ERR_UNSUPPORTED;
+  const int64_t q = dt == DT_F32 ? 4 : 8;
+  if (g->N % q || g->K % q || g->K2 % q || (g->a_strided && g->M % q)) return RL_ERR_ALIGN;
+  const int64_t a_cols = g->a_strided ? g->M : g->K, a2_cols = g->a_strided ? g->M : g->K2;
+  const int64_t b_cols = g->b_kcontig ? g->K : g->N, b2_cols = g->b_kcontig ? g->K2 : g->N;
+  if (g->lda < a_cols || g->ldb < b_cols || g->ldc < g->N) return RL_ERR_SHAPE;
+  if (g->K2 > 0 && (g->lda2 < a2_cols || g->ldb2 < b2_cols)) return RL_ERR_SHAPE;
+  if (g->D && g->ldd < g->N) return RL_ERR_SHAPE;
+  const void* ptrs[6] = {g->A, g->B, g->A2, g->B2, g->D, g->C};
+  for (const void* p : ptrs)
+    if (p && (reinterpret_cast<uintptr_t>(p) & 15) != 0) return RL_ERR_ALIGN;
+  if (g->lda % q || g->ldb % q || g->ldc % q || (g->K2 > 0 && (g->lda2 % q || g->ldb2 % q)) || (g->D && g->ldd % q))
+    return RL_ERR_ALIGN;
+  d->dtype = dt;
+  d->a_strided = g->a_strided;
+  d->b_kcontig = g->b_kcontig;
+  d->M = g->M; d->N = g->N;
+  d->nseg = g->K2 > 0 ? 2 : 1;
+  d->A[0] = g->A; d->B[0] = g->B; d->lda[0] = g->lda; d->ldb[0] = g->ldb; d->K[0] = g->K;
+  d->A[1] = g->A2; d->B[1] = g->B2; d->lda[1] = g->lda2; d->ldb[1] = g->ldb2; d->K[1] = g->K2;
+  d->C = g->C; d->ldc = g->ldc; d->D = g->D; d->ldd = g->ldd;
+  *plan = gemm_plan(dt, g->M, g->N, g->K, g->K2, g->tile_cfg, g->K2 > 0 ? 1 : g->splits);
+  return RL_OK;
+}
+
+extern "C" size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g) {
+  GemmDesc d;
+  GemmPlan plan;
+  if (check_gemm(g, &d, &plan) != RL_OK) return 0;
+  return plan.partial_bytes;
+}
+
+extern "C" int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts) {
+  GemmDesc d;
+  GemmPlan plan;
+  int rc = check_gemm(g, &d, &plan);
+  if (rc != RL_OK) return rc;
+  float* scratch = nullptr;
+  if (plan.partial_bytes > 0) {
+    if (!opts || !opts->workspace || opts->workspace_bytes < plan.partial_bytes) return RL_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(opts->workspace) & 255) != 0) return RL_ERR_ALIGN;
+    scratch = static_cast<float*>(opts->workspace);
+  }
+  hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
+  hipError_t e = gemm_run(d, plan, scratch, stream);
+  if (e != hipSuccess) return set_hip_error(e, "runlora_gemm");
+  return RL_OK;
+}

@@ -1,0 +1,56 @@
+// Host-side interface of the tile GEMM engine (gemm_engine.hpp): problem description, launch plan
+// (tile shape + split of the contraction) and launch.  Internal to the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace rl {
+
+enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
+
+// C[M,N] (dtype) = sum_s op(A_s) op(B_s) (+ D).
+struct GemmDesc {
+  int dtype = DT_BF16;
+  int a_strided = 0;  // 0: A_s stored [M,K_s] row-major; 1: A_s stored [K_s,M]
+  int b_kcontig = 0;  // 0: B_s stored [K_s,N] row-major; 1: B_s stored [N,K_s]
+  int64_t M = 0, N = 0;
+  int nseg = 1;
+  const void* A[2] = {nullptr, nullptr};
+  const void* B[2] = {nullptr, nullptr};
+  int64_t lda[2] = {0, 0}, ldb[2] = {0, 0}, K[2] = {0, 0};
+  void* C = nullptr;
+  int64_t ldc = 0;
+  const void* D = nullptr;  // optional addend, same dtype as C (may alias C)
+  int64_t ldd = 0;
+};
+
+enum TileCfg { CFG_BIG = 0, CFG_MID, CFG_TALL32, CFG_TALL64, CFG_WIDE32, CFG_WIDE64, CFG_COUNT };
+
+struct GemmPlan {
+  int cfg = CFG_MID;
+  int bm = 128, bn = 128, bk = 64;
+  int nbm = 1, nbn = 1;
+  int splits = 1;            // > 1: fp32 partials + fixed-order reduce
+  int tiles_per_split = 1;
+  size_t partial_bytes = 0;  // scratch needed when splits > 1
+};
+
+// Tile shape and K split for a problem; depends on shapes and dtype only (never on pointers), so
+// the same plan sizes the workspace and drives the launch.  force_cfg / force_splits (>= 0 / > 0)
+// override the heuristics (used by the tuning sweeps and tests).
+GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg = -1,
+                   int force_splits = 0);
+
+// Enqueue the product.  `scratch` must hold plan.partial_bytes when plan.splits > 1.
+hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream);
+
+// per-dtype launchers (one translation unit each)
+struct GemmArgs;
+hipError_t gemm_launch_bf16(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);
+hipError_t gemm_launch_f16(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);
+hipError_t gemm_launch_f32(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);
+hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int M, int N, void* C,
+                                int64_t ldc, const void* D, int64_t ldd, hipStream_t s);
+
+}  // namespace rl

@@ -1,0 +1,4 @@
+#define RL_T __bf16
+#define RL_BK 64
+#define RL_FN gemm_launch_bf16
+#include "gemm_launch.inc"

@@ -1,0 +1,331 @@
+// Tile GEMM engine for gfx950 (CDNA4): C[M,N] = sum over segments of op(A_s)[M,K_s] * op(B_s)[K_s,N]
+// (+ D), fp32 accumulation on the matrix cores, one rounding to the output type.
+//
+// Every product of the LoRA layer (Eq. 1 and Eq. 3 of arxiv 2312.03415, and the intermediates of
+// Algorithms 1-5) is an instance of this kernel: operand layouts select X W (row x row), dY W^T
+// (row x col) and X^T dY (col x row); a second K segment gives [X|T][W;B] and [dY|Z1][W^T;A^T];
+// the addend D gives W + AB and the "+=" steps of the default chain; gridDim.y > 1 splits the
+// contraction over workgroups, each writing an fp32 partial that a second kernel sums in a fixed
+// order (no atomics, run-to-run identical).
+//
+// Execution model: one workgroup owns a BM x BN output tile; WM x WN wavefronts (64 lanes) each own
+// a (BM/WM) x (BN/WN) sub-tile made of 32x32 MFMA blocks.  Global memory -> registers -> LDS with
+// the next K tile in flight while the current one is multiplied (two LDS stages, one barrier per
+// K tile).  LDS keeps each operand in its global orientation; rows are padded so that the
+// fragment reads are bank-conflict free.  K-contiguous operands are read with 16-byte LDS loads,
+// K-strided 16-bit operands with the transposing 64-bit LDS load.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rl {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(_Float16)))) _Float16 f16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i32x2;
+
+struct GemmArgs {
+  const void* A[2];   // segment s: A stored [M,K_s] (AL=0) or [K_s,M] (AL=1)
+  const void* B[2];   // segment s: B stored [K_s,N] (BL=0) or [N,K_s] (BL=1)
+  int64_t lda[2], ldb[2];
+  int K[2];           // K[1] = 0 when there is one segment
+  void* C;            // [M,N] output in T (or unused when partial != nullptr)
+  int64_t ldc;
+  const void* D;      // optional addend [M,N] in T
+  int64_t ldd;
+  float* partial;     // split-K: fp32 [gridDim.y][M][N], dense
+  int M, N;
+  int tiles_per_split;  // K tiles per gridDim.y slice
+  int nbm, nbn;         // tile grid
+};
+
+// ---- per-type pieces --------------------------------------------------------------------------
+
+template <typename T> struct Elem;
+template <> struct Elem<__bf16> {
+  static __device__ __forceinline__ void mma(f32x16& acc, i32x4 rowop, i32x4 colop) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, rowop),
+                                                  __builtin_bit_cast(bf16x8, colop), acc, 0, 0, 0);
+  }
+};
+template <> struct Elem<_Float16> {
+  static __device__ __forceinline__ void mma(f32x16& acc, i32x4 rowop, i32x4 colop) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, rowop),
+                                                 __builtin_bit_cast(f16x8, colop), acc, 0, 0, 0);
+  }
+};
+template <> struct Elem<float> {
+  // a lane carries 4 consecutive k; four K=2 MFMAs each take one of them (same k order on both
+  // operands, so the pairing is consistent)
+  static __device__ __forceinline__ void mma(f32x16& acc, i32x4 rowop, i32x4 colop) {
+    f32x4 a = __builtin_bit_cast(f32x4, rowop), b = __builtin_bit_cast(f32x4, colop);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b[j], acc, 0, 0, 0);
+  }
+};
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ __bf16 from_f32<__bf16>(float v) { return (__bf16)v; }
+template <> __device__ __forceinline__ _Float16 from_f32<_Float16>(float v) { return (_Float16)v; }
+
+// LDS row length (elements) for a tile whose rows hold `cols` elements.
+//  K-contiguous tile: +16 bytes, so 16 consecutive rows read by 16-byte loads hit distinct banks.
+//  K-strided tile   : row stride = 64 bytes mod 128 (16-bit, transposing loads) / +8 floats (fp32).
+template <typename T, bool STRIDED, int COLS> struct LdsLd {
+  static constexpr int VE = 16 / sizeof(T);
+  static constexpr int value =
+      !STRIDED ? COLS + VE
+               : (sizeof(T) == 2 ? (((COLS * 2) % 128 == 64) ? COLS : COLS + 32) : COLS + 8);
+};
+
+// One 32-wide operand fragment for K step `ks` out of an LDS tile.
+// Returns 16 bytes: the VE consecutive k values this lane feeds to the MFMA(s).
+template <typename T, bool STRIDED, int LD>
+__device__ __forceinline__ i32x4 read_frag(const T* tile, int idx0, int ks, int lane) {
+  constexpr int VE = 16 / sizeof(T);
+  if constexpr (!STRIDED) {
+    const T* p = tile + (idx0 + (lane & 31)) * LD + ks * (2 * VE) + VE * (lane >> 5);
+    return *reinterpret_cast<const i32x4*>(p);
+  } else if constexpr (sizeof(T) == 2) {
+    // transposing load: within a 16-lane block, lane s points at [k0 + s/4][c0 + 4*(s%4) .. +3]
+    // and receives column c0 + s for k0..k0+3.
+    const int s = lane & 15;
+    const int c0 = idx0 + 16 * ((lane >> 4) & 1);
+    const int k0 = ks * 16 + 8 * (lane >> 5);
+    const T* p = tile + (k0 + (s >> 2)) * LD + c0 + 4 * (s & 3);
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * LD));
+    i32x2 l2 = __builtin_bit_cast(i32x2, lo), h2 = __builtin_bit_cast(i32x2, hi);
+    i32x4 out = {l2[0], l2[1], h2[0], h2[1]};
+    return out;
+  } else {
+    const T* p = tile + (ks * 8 + 4 * (lane >> 5)) * LD + idx0 + (lane & 31);
+    f32x4 v = {p[0], p[LD], p[2 * LD], p[3 * LD]};
+    return __builtin_bit_cast(i32x4, v);
+  }
+}
+
+// ---- the kernel ---------------------------------------------------------------------------------
+// AL: 0 = A stored [M,K] (K contiguous), 1 = A stored [K,M].   BL: 0 = B stored [K,N], 1 = [N,K].
+template <typename T, int AL, int BL, int BM, int BN, int BK, int WM, int WN>
+struct GemmTile {
+  static constexpr int NT = WM * WN * 64;
+  static constexpr int VE = 16 / sizeof(T);
+  static constexpr int KS = 2 * VE;
+  static constexpr int WTM = BM / WM, WTN = BN / WN, TM = WTM / 32, TN = WTN / 32;
+  static constexpr bool A_STR = (AL == 1), B_STR = (BL == 0);
+  static constexpr int A_ROWS = A_STR ? BK : BM, A_COLS = A_STR ? BM : BK;
+  static constexpr int B_ROWS = B_STR ? BK : BN, B_COLS = B_STR ? BN : BK;
+  static constexpr int A_LD = LdsLd<T, A_STR, A_COLS>::value;
+  static constexpr int B_LD = LdsLd<T, B_STR, B_COLS>::value;
+  static constexpr int A_ELEMS = A_ROWS * A_LD, B_ELEMS = B_ROWS * B_LD;
+  static constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
+  static constexpr int LDS_BYTES = 2 * STAGE_ELEMS * (int)sizeof(T);
+  static constexpr int A_CPR = A_COLS / VE, B_CPR = B_COLS / VE;  // 16-byte chunks per tile row
+  static constexpr int A_CHUNKS = A_ROWS * A_CPR, B_CHUNKS = B_ROWS * B_CPR;
+  static constexpr int A_PER = (A_CHUNKS + NT - 1) / NT, B_PER = (B_CHUNKS + NT - 1) / NT;
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % KS == 0, "tile shape");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+
+template <typename T, int AL, int BL, int BM, int BN, int BK, int WM, int WN>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
+  using G = GemmTile<T, AL, BL, BM, BN, BK, WM, WN>;
+  constexpr int NT = G::NT, VE = G::VE;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* smem = reinterpret_cast<T*>(smem_raw);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+
+  // ---- workgroup -> tile.  Consecutive workgroup ids go to different XCDs (8 of them, each with
+  // its own L2), so first renumber such that each XCD gets a contiguous run of tiles, then walk
+  // the tile grid in bands of 8 tile rows so that a run shares B columns and A rows in its L2.
+  const int total = g.nbm * g.nbn;
+  int id = blockIdx.x;
+  {
+    const int x = id & 7, slot = id >> 3, q = total >> 3, rem = total & 7;
+    id = x * q + (x < rem ? x : rem) + slot;
+  }
+  constexpr int BAND = 8;
+  const int per_band = BAND * g.nbn;
+  const int band = id / per_band, first_m = band * BAND;
+  const int band_rows = (g.nbm - first_m) < BAND ? (g.nbm - first_m) : BAND;
+  const int in_band = id - band * per_band;
+  const int tile_m = first_m + in_band % band_rows, tile_n = in_band / band_rows;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // ---- K tiles of this workgroup (over both segments; gridDim.y slices them)
+  const int nt0 = (g.K[0] + BK - 1) / BK, nt1 = (g.K[1] + BK - 1) / BK;
+  const int t_begin = blockIdx.y * g.tiles_per_split;
+  int t_end = t_begin + g.tiles_per_split;
+  if (t_end > nt0 + nt1) t_end = nt0 + nt1;
+
+  f32x16 acc[G::TM][G::TN];
+#pragma unroll
+  for (int a = 0; a < G::TM; ++a)
+#pragma unroll
+    for (int b = 0; b < G::TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  i32x4 ra[G::A_PER], rb[G::B_PER];
+
+  auto load_global = [&](int t) {
+    const int s = t < nt0 ? 0 : 1;
+    const int k0 = (t - (s ? nt0 : 0)) * BK;
+    const int Ks = g.K[s];
+    const T* Ap = static_cast<const T*>(g.A[s]);
+    const T* Bp = static_cast<const T*>(g.B[s]);
+    const int64_t lda = g.lda[s], ldb = g.ldb[s];
+#pragma unroll
+    for (int j = 0; j < G::A_PER; ++j) {
+      const int c = tid + j * NT;
+      const int row = c / G::A_CPR, col = (c % G::A_CPR) * VE;
+      i32x4 v = {0, 0, 0, 0};
+      if (G::A_CHUNKS % NT == 0 || c < G::A_CHUNKS) {
+        if constexpr (!G::A_STR) {  // row = m, col = k
+          if (m0 + row < g.M && k0 + col < Ks)
+            v = *reinterpret_cast<const i32x4*>(Ap + (int64_t)(m0 + row) * lda + k0 + col);
+        } else {  // row = k, col = m
+          if (k0 + row < Ks && m0 + col < g.M)
+            v = *reinterpret_cast<const i32x4*>(Ap + (int64_t)(k0 + row) * lda + m0 + col);
+        }
+      }
+      ra[j] = v;
+    }
+#pragma unroll
+    for (int j = 0; j < G::B_PER; ++j) {
+      const int c = tid + j * NT;
+      const int row = c / G::B_CPR, col = (c % G::B_CPR) * VE;
+      i32x4 v = {0, 0, 0, 0};
+      if (G::B_CHUNKS % NT == 0 || c < G::B_CHUNKS) {
+        if constexpr (G::B_STR) {  // row = k, col = n
+          if (k0 + row < Ks && n0 + col < g.N)
+            v = *reinterpret_cast<const i32x4*>(Bp + (int64_t)(k0 + row) * ldb + n0 + col);
+        } else {  // row = n, col = k
+          if (n0 + row < g.N && k0 + col < Ks)
+            v = *reinterpret_cast<const i32x4*>(Bp + (int64_t)(n0 + row) * ldb + k0 + col);
+        }
+      }
+      rb[j] = v;
+    }
+  };
+
+  auto store_lds = [&](int stage) {
+    T* sA = smem + stage * G::STAGE_ELEMS;
+    T* sB = sA + G::A_ELEMS;
+#pragma unroll
+    for (int j = 0; j < G::A_PER; ++j) {
+      const int c = tid + j * NT;
+      if (G::A_CHUNKS % NT == 0 || c < G::A_CHUNKS)
+        *reinterpret_cast<i32x4*>(sA + (c / G::A_CPR) * G::A_LD + (c % G::A_CPR) * VE) = ra[j];
+    }
+#pragma unroll
+    for (int j = 0; j < G::B_PER; ++j) {
+      const int c = tid + j * NT;
+      if (G::B_CHUNKS % NT == 0 || c < G::B_CHUNKS)
+        *reinterpret_cast<i32x4*>(sB + (c / G::B_CPR) * G::B_LD + (c % G::B_CPR) * VE) = rb[j];
+    }
+  };
+
+  if (t_begin < t_end) {
+    load_global(t_begin);
+    store_lds(0);
+  }
+  __syncthreads();
+
+  int stage = 0;
+  for (int t = t_begin; t < t_end; ++t) {
+    const bool more = (t + 1 < t_end);
+    if (more) load_global(t + 1);
+    const T* sA = smem + stage * G::STAGE_ELEMS;
+    const T* sB = sA + G::A_ELEMS;
+#pragma unroll
+    for (int ks = 0; ks < BK / G::KS; ++ks) {
+      i32x4 fa[G::TM], fb[G::TN];
+#pragma unroll
+      for (int a = 0; a < G::TM; ++a)
+        fa[a] = read_frag<T, G::A_STR, G::A_LD>(sA, wm * G::WTM + a * 32, ks, lane);
+#pragma unroll
+      for (int b = 0; b < G::TN; ++b)
+        fb[b] = read_frag<T, G::B_STR, G::B_LD>(sB, wn * G::WTN + b * 32, ks, lane);
+#pragma unroll
+      for (int a = 0; a < G::TM; ++a)
+#pragma unroll
+        for (int b = 0; b < G::TN; ++b) Elem<T>::mma(acc[a][b], fb[b], fa[a]);  // rows of the MFMA = n
+    }
+    if (more) store_lds(stage ^ 1);
+    __syncthreads();
+    stage ^= 1;
+  }
+
+  // ---- epilogue.  With the operands swapped, lane l of a 32x32 block holds row m = l%32 and the
+  // four consecutive columns n = 8*(v/4) + 4*(l/32) + (v%4): one 8- or 16-byte store per group.
+  const int mrow = lane & 31, nsub = 4 * (lane >> 5);
+#pragma unroll
+  for (int a = 0; a < G::TM; ++a) {
+    const int m = m0 + wm * G::WTM + a * 32 + mrow;
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int b = 0; b < G::TN; ++b) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * G::WTN + b * 32 + 8 * q + nsub;
+        if (n >= g.N) continue;  // N is a multiple of 4, so n..n+3 are valid together
+        f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+        if (g.partial) {
+          float* p = g.partial + ((int64_t)blockIdx.y * g.M + m) * g.N + n;
+          *reinterpret_cast<f32x4*>(p) = v;
+        } else {
+          if (g.D) {
+            const T* d = static_cast<const T*>(g.D) + (int64_t)m * g.ldd + n;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += (float)d[e];
+          }
+          T* c = static_cast<T*>(g.C) + (int64_t)m * g.ldc + n;
+          if constexpr (sizeof(T) == 4) {
+            *reinterpret_cast<f32x4*>(c) = v;
+          } else {
+            T o4[4] = {from_f32<T>(v[0]), from_f32<T>(v[1]), from_f32<T>(v[2]), from_f32<T>(v[3])};
+            *reinterpret_cast<i32x2*>(c) = *reinterpret_cast<i32x2*>(o4);
+          }
+        }
+      }
+    }
+  }
+}
+
+// Sum the split-K partials in slice order and round once: C = sum_z partial[z] (+ D).
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits,
+                                                            int M, int N, T* __restrict__ C, int64_t ldc,
+                                                            const T* __restrict__ D, int64_t ldd) {
+  const int64_t quads = (int64_t)M * N / 4;  // N is a multiple of 4
+  for (int64_t qd = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; qd < quads;
+       qd += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t e = qd * 4;
+    const int m = (int)(e / N), n = (int)(e % N);
+    f32x4 s = *reinterpret_cast<const f32x4*>(partial + e);
+    for (int z = 1; z < splits; ++z) {
+      f32x4 p = *reinterpret_cast<const f32x4*>(partial + (int64_t)z * M * N + e);
+      s += p;
+    }
+    if (D) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) s[k] += (float)D[(int64_t)m * ldd + n + k];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) C[(int64_t)m * ldc + n + k] = from_f32<T>(s[k]);
+  }
+}
+
+}  // namespace rl

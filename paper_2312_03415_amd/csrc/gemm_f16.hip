@@ -1,0 +1,4 @@
+#define RL_T _Float16
+#define RL_BK 64
+#define RL_FN gemm_launch_f16
+#include "gemm_launch.inc"

@@ -1,0 +1,4 @@
+#define RL_T float
+#define RL_BK 32
+#define RL_FN gemm_launch_f32
+#include "gemm_launch.inc"

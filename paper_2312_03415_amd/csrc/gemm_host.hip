@@ -1,0 +1,118 @@
+// Launch planning and dispatch for the tile GEMM engine.
+#include "gemm.hpp"
+#include "gemm_engine.hpp"
+
+namespace rl {
+
+static const int kTileBM[CFG_COUNT] = {256, 128, 128, 128, 32, 64};
+static const int kTileBN[CFG_COUNT] = {256, 128, 32, 64, 128, 128};
+
+GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg,
+                   int force_splits) {
+  GemmPlan p;
+  p.bk = (dtype == DT_F32) ? 32 : 64;
+  int cfg;
+  if (force_cfg >= 0 && force_cfg < CFG_COUNT) {
+    cfg = force_cfg;
+  } else if (M <= 32) {
+    cfg = CFG_WIDE32;
+  } else if (M <= 64) {
+    cfg = CFG_WIDE64;
+  } else if (N <= 32) {
+    cfg = CFG_TALL32;
+  } else if (N <= 64) {
+    cfg = CFG_TALL64;
+  } else {
+    // the 256x256 tile needs enough tiles to occupy the 256 compute units
+    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    cfg = big_tiles >= 192 ? CFG_BIG : CFG_MID;
+  }
+  p.cfg = cfg;
+  p.bm = kTileBM[cfg];
+  p.bn = kTileBN[cfg];
+  p.nbm = (int)((M + p.bm - 1) / p.bm);
+  p.nbn = (int)((N + p.bn - 1) / p.bn);
+  const int64_t tiles = (int64_t)p.nbm * p.nbn;
+  const int ktiles = (int)((K0 + p.bk - 1) / p.bk + (K1 + p.bk - 1) / p.bk);
+  int splits = 1;
+  if (force_splits > 0) {
+    splits = force_splits;
+  } else if (tiles < 256 && ktiles >= 8) {
+    // fill the chip (aim at ~512 workgroups) but keep >= 4 K tiles per slice
+    int64_t want = (512 + tiles - 1) / tiles;
+    int64_t cap = ktiles / 4;
+    splits = (int)(want < cap ? want : cap);
+    if (splits > 64) splits = 64;
+    if (splits < 1) splits = 1;
+  }
+  if (splits > ktiles) splits = ktiles > 0 ? ktiles : 1;
+  p.tiles_per_split = (ktiles + splits - 1) / splits;
+  if (p.tiles_per_split < 1) p.tiles_per_split = 1;
+  p.splits = (ktiles + p.tiles_per_split - 1) / p.tiles_per_split;  // no empty slice
+  if (p.splits < 1) p.splits = 1;
+  p.partial_bytes = p.splits > 1 ? (size_t)p.splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+  return p;
+}
+
+hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream) {
+  if (d.M <= 0 || d.N <= 0) return hipErrorInvalidValue;
+  if (plan.splits > 1 && scratch == nullptr) return hipErrorInvalidValue;
+  GemmArgs a{};
+  for (int s = 0; s < 2; ++s) {
+    const bool on = s < d.nseg;
+    a.A[s] = on ? d.A[s] : nullptr;
+    a.B[s] = on ? d.B[s] : nullptr;
+    a.lda[s] = on ? d.lda[s] : 0;
+    a.ldb[s] = on ? d.ldb[s] : 0;
+    a.K[s] = on ? (int)d.K[s] : 0;
+  }
+  a.C = d.C;
+  a.ldc = d.ldc;
+  a.D = plan.splits > 1 ? nullptr : d.D;
+  a.ldd = d.ldd;
+  a.partial = plan.splits > 1 ? scratch : nullptr;
+  a.M = (int)d.M;
+  a.N = (int)d.N;
+  a.tiles_per_split = plan.splits > 1 ? plan.tiles_per_split : (1 << 30);
+  a.nbm = plan.nbm;
+  a.nbn = plan.nbn;
+  dim3 grid((unsigned)(plan.nbm * plan.nbn), (unsigned)plan.splits, 1);
+  const int al = d.a_strided ? 1 : 0, bl = d.b_kcontig ? 1 : 0;
+  hipError_t e;
+  switch (d.dtype) {
+    case DT_BF16: e = gemm_launch_bf16(plan.cfg, al, bl, a, grid, stream); break;
+    case DT_F16: e = gemm_launch_f16(plan.cfg, al, bl, a, grid, stream); break;
+    case DT_F32: e = gemm_launch_f32(plan.cfg, al, bl, a, grid, stream); break;
+    default: return hipErrorInvalidValue;
+  }
+  if (e != hipSuccess) return e;
+  if (plan.splits > 1)
+    e = splitk_reduce_launch(d.dtype, scratch, plan.splits, (int)d.M, (int)d.N, d.C, d.ldc, d.D, d.ldd, stream);
+  return e;
+}
+
+hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int M, int N, void* C,
+                                int64_t ldc, const void* D, int64_t ldd, hipStream_t s) {
+  const int64_t quads = (int64_t)M * N / 4;
+  int blocks = (int)((quads + 255) / 256);
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  switch (dtype) {
+    case DT_BF16:
+      hipLaunchKernelGGL(splitk_reduce_kernel<__bf16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
+                         static_cast<__bf16*>(C), ldc, static_cast<const __bf16*>(D), ldd);
+      break;
+    case DT_F16:
+      hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
+                         static_cast<_Float16*>(C), ldc, static_cast<const _Float16*>(D), ldd);
+      break;
+    case DT_F32:
+      hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
+                         static_cast<float*>(C), ldc, static_cast<const float*>(D), ldd);
+      break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace rl

@@ -1,0 +1,49 @@
+// Variant schedules: each computation graph of the LoRA layer (Section 2 of arxiv 2312.03415:
+// forward variants 1-2, Algorithms 1-5, and the default chain) written as the ordered list of
+// GEMM launches that realises it, together with its scratch layout.  The same list drives the
+// launches (api.hip), the workspace size and the selector's time model (select.cpp), so the three
+// cannot drift apart.  Internal to the library.
+#pragma once
+#include <vector>
+
+#include "gemm.hpp"
+
+namespace rl {
+
+struct Mat {  // device matrix view; ptr may be null when only shapes are needed
+  const void* ptr = nullptr;
+  int64_t ld = 0;
+};
+
+struct LayerDims {
+  int64_t n = 0, i = 0, o = 0, r = 0;
+  int dtype = DT_BF16;
+};
+
+struct Step {
+  GemmDesc d;
+  GemmPlan plan;
+  const char* what = "";  // the product in the paper's notation, e.g. "Z1 = dY B^T"
+};
+
+struct Schedule {
+  std::vector<Step> steps;
+  size_t workspace_bytes = 0;  // intermediates + split-K partials
+  size_t partial_offset = 0;   // where the shared split-K scratch starts
+};
+
+struct FwdOperands {
+  Mat X, W, A, B, Y, T;  // T: caller's buffer for the default chain (kept for the backward)
+};
+struct BwdOperands {
+  Mat dY, X, W, A, B, T, dX, dA, dB;
+  bool want_dX = true, want_dA = true, want_dB = true;
+};
+
+// ws_base may be null (sizing / modelling).  Returns false for an unknown variant.
+bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void* ws_base, Schedule* out);
+bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void* ws_base, Schedule* out);
+
+inline size_t dtype_size(int dtype) { return dtype == DT_F32 ? 4 : 2; }
+
+}  // namespace rl

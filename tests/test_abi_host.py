@@ -1,0 +1,192 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what the header
+declares, its Table 1 closed forms and FLOP-criterion selector agree with the paper, and every
+argument error is reported before any HIP call."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2312_03415_amd import binding as rl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "runlora.h")).read()
+    declared = set(re.findall(r"\b(runlora_\w+)\s*\(", header))
+    assert declared, "no declarations found"
+    L = rl.lib()
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in runlora.h but not exported"
+    assert declared == set(rl.EXPORTS)
+    assert L.runlora_version() >= 100
+    assert L.runlora_strerror(rl.RL_ERR_ALIGN).decode()
+
+
+def test_flops_match_table1(table1):
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        n, i, o, r = (int(v) for v in rng.integers(1, 20000, size=4))
+        assert rl.runlora_flops(0, 1, n, i, o, r) == table1["forward1"](n, i, o, r)
+        assert rl.runlora_flops(0, 2, n, i, o, r) == table1["forward2"](n, i, o, r)
+        for v in range(1, 9):
+            assert rl.runlora_flops(1, v, n, i, o, r) == table1[f"backward{v}"](n, i, o, r)
+        assert rl.runlora_flops(0, 0, n, i, o, r) == table1["forward1"](n, i, o, r)
+        assert rl.runlora_flops(1, 0, n, i, o, r) == table1["backward1"](n, i, o, r) - 2 * n * i * r
+    assert rl.runlora_flops(0, 3, 1, 1, 1, 1) == -1 and rl.runlora_flops(1, 9, 1, 1, 1, 1) == -1
+
+
+def test_flop_criterion_closed_forms(table1):
+    """Consequences of Table 1: forward2 wins iff n > io/(i+o) (independent of r); backward5 beats
+    backward1 iff n > o; backward2/3 never win under r(i+o) < io (Section 2)."""
+    rng = np.random.default_rng(1)
+    for _ in range(400):
+        n, i, o, r = (int(v) for v in rng.integers(1, 6000, size=4))
+        f, b = rl.runlora_select(n, i, o, r, rl.RL_BF16, criterion=0)
+        ff = {v: table1[f"forward{v}"](n, i, o, r) for v in (1, 2)}
+        bf = {v: table1[f"backward{v}"](n, i, o, r) for v in range(1, 6)}
+        assert ff[f] == min(ff.values()) and bf[b] == min(bf.values())
+        assert f == (2 if n * (i + o) > i * o else 1)
+        if r * (i + o) < i * o:
+            assert b in (1, 4, 5)
+            if b != 4:
+                assert b == (5 if n > o else 1)
+
+
+def test_flop_criterion_on_llama_mlp_setting():
+    """The setting of the paper's batch/sequence figure: i=4096, o=11008, r=128 satisfies Eq. 5;
+    forward2 from n = 2986 tokens on, backward5 beyond n = 11008, backward1 below."""
+    i, o, r = 4096, 11008, 128
+    assert r * (i + o) < i * o
+    assert rl.runlora_select(2985, i, o, r, rl.RL_BF16, 0)[0] == 1
+    assert rl.runlora_select(2986, i, o, r, rl.RL_BF16, 0)[0] == 2
+    assert rl.runlora_select(11008, i, o, r, rl.RL_BF16, 0)[1] == 1
+    assert rl.runlora_select(11009, i, o, r, rl.RL_BF16, 0)[1] == 5
+    # int4 W: merged graphs are unavailable
+    assert rl.runlora_select(4096, 5120, 13824, 64, rl.RL_INT4_G64, 0) == (1, 1)
+
+
+def test_select_time_model_returns_legal_pairs():
+    for n in (128, 1024, 8192, 16384):
+        for r in (8, 64, 256):
+            f, b = rl.runlora_select(n, 4096, 4096, r, rl.RL_F16)
+            assert f in (1, 2) and b in (1, 2, 3, 4, 5)
+            assert rl.runlora_model_time_us(0, f, n, 4096, 4096, r, rl.RL_F16) > 0
+    assert rl.runlora_model_time_us(0, 7, 128, 64, 64, 8, rl.RL_F16) < 0
+    f, b = ctypes.c_int(), ctypes.c_int()
+    assert rl.lib().runlora_select(0, 8, 8, 8, rl.RL_F16, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_SHAPE
+    assert rl.lib().runlora_select(8, 8, 8, 8, 77, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_DTYPE
+    assert rl.lib().runlora_select(8, 8, 8, 8, rl.RL_F16, None, ctypes.byref(b)) == rl.RL_ERR_NULL
+
+
+def test_workspace_bytes_cover_intermediates():
+    n, i, o, r = 8192, 4096, 4096, 32
+    e = 2
+    assert rl.runlora_workspace_bytes(1, -1, n, i, o, r, rl.RL_BF16) >= n * r * e              # T
+    assert rl.runlora_workspace_bytes(2, -1, n, i, o, r, rl.RL_BF16) >= i * o * e              # M
+    assert rl.runlora_workspace_bytes(-1, 4, n, i, o, r, rl.RL_BF16) >= 2 * i * o * e          # M, Z2
+    assert rl.runlora_workspace_bytes(-1, 5, n, i, o, r, rl.RL_BF16) >= 2 * n * r * e + i * o * e
+    both = rl.runlora_workspace_bytes(2, 5, n, i, o, r, rl.RL_BF16)
+    assert both == max(rl.runlora_workspace_bytes(2, -1, n, i, o, r, rl.RL_BF16),
+                       rl.runlora_workspace_bytes(-1, 5, n, i, o, r, rl.RL_BF16))
+
+
+# ---- argument validation: fake (never dereferenced) device addresses ----------------------------
+
+def T(ptr, rows, cols, dtype=rl.RL_BF16, ld=None):
+    return rl.rl_tensor_t(ptr, rows, cols, cols if ld is None else ld, dtype, None, 0)
+
+
+def fwd_args(n=64, i=32, o=48, r=8, dtype=rl.RL_BF16):
+    base = 0x10000000
+    step = 0x1000000
+    return dict(X=T(base, n, i, dtype), W=T(base + step, i, o, dtype), A=T(base + 2 * step, i, r, dtype),
+                B=T(base + 3 * step, r, o, dtype), Y=T(base + 4 * step, n, o, dtype))
+
+
+def call_fwd(variant, a, saved=None, opts=None):
+    saved = saved if saved is not None else rl.rl_saved_t()
+    ref = lambda x: ctypes.byref(x) if x is not None else None
+    return rl.lib().runlora_forward(variant, ref(a["X"]), ref(a["W"]), ref(a["A"]), ref(a["B"]), ref(a["Y"]),
+                                    ctypes.byref(saved), ref(opts))
+
+
+def test_forward_rejects_bad_arguments_before_touching_the_gpu():
+    a = fwd_args()
+    assert call_fwd(9, a) == rl.RL_ERR_VARIANT
+    assert call_fwd(-1, a) == rl.RL_ERR_VARIANT
+    b = fwd_args(); b["W"] = None
+    assert call_fwd(1, b) == rl.RL_ERR_NULL
+    b = fwd_args(); b["W"].data = None
+    assert call_fwd(1, b) == rl.RL_ERR_NULL
+    b = fwd_args(); b["W"].rows = 40
+    assert call_fwd(1, b) == rl.RL_ERR_SHAPE
+    b = fwd_args(); b["B"].cols = 56
+    assert call_fwd(1, b) == rl.RL_ERR_SHAPE
+    b = fwd_args(); b["A"].dtype = rl.RL_F16
+    assert call_fwd(1, b) == rl.RL_ERR_DTYPE
+    b = fwd_args(); b["X"].dtype = 42
+    assert call_fwd(1, b) == rl.RL_ERR_DTYPE
+    b = fwd_args(); b["X"].data += 2
+    assert call_fwd(1, b) == rl.RL_ERR_ALIGN
+    b = fwd_args(); b["X"].ld = 36
+    assert call_fwd(1, b) == rl.RL_ERR_ALIGN
+    b = fwd_args(r=4)
+    assert call_fwd(1, b) == rl.RL_ERR_ALIGN          # r must be a multiple of 8 for 16-bit types
+    b = fwd_args(); b["Y"].data = b["X"].data
+    assert call_fwd(1, b) == rl.RL_ERR_ALIAS
+    # needs workspace, none given / too small / misaligned
+    assert call_fwd(1, a) == rl.RL_ERR_WORKSPACE
+    assert call_fwd(1, a, opts=rl.rl_opts_t(None, 0x70000000, 16)) == rl.RL_ERR_WORKSPACE
+    need = rl.runlora_workspace_bytes(1, -1, 64, 32, 48, 8, rl.RL_BF16)
+    assert call_fwd(1, a, opts=rl.rl_opts_t(None, 0x70000010, need)) == rl.RL_ERR_ALIGN
+    # default chain needs the caller's T buffer
+    assert call_fwd(0, a) == rl.RL_ERR_NULL
+    # int4 W is declared but not built yet
+    b = fwd_args(); b["W"].dtype = rl.RL_INT4_G64
+    assert call_fwd(1, b) == rl.RL_ERR_UNSUPPORTED
+
+
+def test_backward_rejects_bad_arguments_before_touching_the_gpu():
+    n, i, o, r = 64, 32, 48, 8
+    base, step = 0x10000000, 0x1000000
+    dt = rl.RL_BF16
+    dY, W, A, B = T(base, n, o), T(base + step, i, o), T(base + 2 * step, i, r), T(base + 3 * step, r, o)
+    dX, dA, dB = T(base + 4 * step, n, i), T(base + 5 * step, i, r), T(base + 6 * step, r, o)
+    saved = rl.rl_saved_t(1, dt, n, i, o, r, base + 7 * step, i, None, 0)
+    L = rl.lib()
+    br = ctypes.byref
+
+    def call(variant, saved=saved, dY=dY, dX=dX, opts=None):
+        return L.runlora_backward(variant, br(dY), br(saved), br(W), br(A), br(B), br(dX) if dX else None, br(dA),
+                                  br(dB), br(opts) if opts else None)
+
+    assert call(6) == rl.RL_ERR_VARIANT
+    assert call(0) == rl.RL_ERR_SAVED_MISMATCH            # default backward needs the default forward's T
+    s2 = rl.rl_saved_t(1, dt, n + 1, i, o, r, base + 7 * step, i, None, 0)
+    assert call(1, saved=s2) == rl.RL_ERR_SAVED_MISMATCH
+    s3 = rl.rl_saved_t(1, rl.RL_F16, n, i, o, r, base + 7 * step, i, None, 0)
+    assert call(1, saved=s3) == rl.RL_ERR_SAVED_MISMATCH
+    s4 = rl.rl_saved_t(1, dt, n, i, o, r, None, i, None, 0)
+    assert call(1, saved=s4) == rl.RL_ERR_NULL
+    assert call(1, dY=T(base, n, o + 8)) == rl.RL_ERR_SHAPE
+    assert call(1, dX=T(base, n, i)) == rl.RL_ERR_ALIAS    # dX on top of dY
+    assert call(1) == rl.RL_ERR_WORKSPACE
+    assert call(1, dX=None) == rl.RL_ERR_WORKSPACE          # skipping dX is legal; still needs scratch
+
+
+def test_gemm_call_rejects_bad_arguments():
+    g = rl.rl_gemm_t(rl.RL_BF16, 1, 1, -1, 0, 64, 64, 64, 0, 0x1000, 0x2000, None, None, None, 0x3000, 64, 64, 0, 0, 64, 0)
+    L = rl.lib()
+    assert L.runlora_gemm(ctypes.byref(g), None) == rl.RL_ERR_UNSUPPORTED
+    g.b_kcontig = 0
+    g.N = 60
+    assert L.runlora_gemm(ctypes.byref(g), None) == rl.RL_ERR_ALIGN
+    g.N = 64
+    g.tile_cfg = 17
+    assert L.runlora_gemm(ctypes.byref(g), None) == rl.RL_ERR_VARIANT
+    g.tile_cfg = -1
+    g.C = None
+    assert L.runlora_gemm(ctypes.byref(g), None) == rl.RL_ERR_NULL

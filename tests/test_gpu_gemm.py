@@ -1,0 +1,107 @@
+"""GPU: the tile GEMM behind every step, each tile shape x operand layout x dtype, on ragged shapes
+that span several tiles, against the oracle's naive fp64 matmul (through the C ABI)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL, relerr, to_device, to_f64, torch_dtype
+from paper_2312_03415_amd import binding as rl
+from paper_2312_03415_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = {"NN": (False, False), "NT": (False, True), "TN": (True, False)}
+# (M, N, K) per tile config: more than one tile each way, ragged last tile, ragged last K tile
+SHAPES = {
+    0: (600, 520, 328),   # 256x256
+    1: (300, 264, 200),   # 128x128
+    2: (300, 24, 200),    # 128x32
+    3: (300, 56, 200),    # 128x64
+    4: (24, 264, 456),    # 32x128
+    5: (56, 264, 456),    # 64x128
+}
+
+
+def make(seed, stream, shape, dtype, var=1.0):
+    st = synth.store(synth.normal(seed, stream, shape, var), dtype)
+    return to_device(st, dtype), synth.widen(st, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("layout", list(LAYOUTS))
+@pytest.mark.parametrize("cfg", list(SHAPES))
+def test_gemm_tile_configs(cfg, layout, dtype):
+    import torch
+    a_str, b_kc = LAYOUTS[layout]
+    M, N, K = SHAPES[cfg]
+    if a_str:
+        M = (M + 7) // 8 * 8   # a [K,M] operand needs M to be a multiple of 8
+    print(f"case cfg={cfg} layout={layout} dtype={dtype} M={M} N={N} K={K}", flush=True)
+    A, Ah = make(3, 1, (K, M) if a_str else (M, K), dtype)
+    B, Bh = make(3, 2, (N, K) if b_kc else (K, N), dtype, 1.0 / K)
+    want = oracle.matmul(Ah, Bh, ta=a_str, tb=b_kc)
+    C = torch.full((M, N), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, tile_cfg=cfg, splits=1)
+    torch.cuda.synchronize()
+    assert relerr(to_f64(C), want) < TOL[dtype]
+    # split contraction (fp32 partials + ordered reduce) and an addend
+    D, Dh = make(3, 3, (M, N), dtype)
+    C2 = torch.full((M, N), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    rl.runlora_gemm(A, B, C2, a_strided=a_str, b_kcontig=b_kc, D=D, tile_cfg=cfg, splits=3)
+    torch.cuda.synchronize()
+    assert relerr(to_f64(C2), want + Dh) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("layout", ["NN", "NT"])
+def test_gemm_two_segments_and_heuristic_plan(layout, dtype):
+    """[A|A2][B;B2] with a short second segment (the K-concatenated LoRA term), plan left to the library."""
+    import torch
+    a_str, b_kc = LAYOUTS[layout]
+    M, N, K, K2 = 333, 264, 200, 24
+    print(f"case two-seg layout={layout} dtype={dtype}", flush=True)
+    A, Ah = make(5, 1, (M, K), dtype)
+    A2, A2h = make(5, 2, (M, K2), dtype)
+    B, Bh = make(5, 3, (N, K) if b_kc else (K, N), dtype, 1.0 / K)
+    B2, B2h = make(5, 4, (N, K2) if b_kc else (K2, N), dtype, 1.0 / K2)
+    want = oracle.matmul(Ah, Bh, tb=b_kc) + oracle.matmul(A2h, B2h, tb=b_kc)
+    for cfg in (-1, 0, 1):
+        C = torch.full((M, N), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+        rl.runlora_gemm(A, B, C, b_kcontig=b_kc, A2=A2, B2=B2, tile_cfg=cfg)
+        torch.cuda.synchronize()
+        assert relerr(to_f64(C), want) < TOL[dtype], cfg
+
+
+def test_gemm_exact_on_small_integers():
+    """Integer-valued inputs are exact in every dtype and every accumulation order: bit-exact result."""
+    import torch
+    rng = np.random.default_rng(0)
+    M, N, K = 130, 72, 96
+    for dtype in ("bf16", "f16", "f32"):
+        Ah = rng.integers(-3, 4, size=(M, K)).astype(np.float64)
+        Bh = rng.integers(-3, 4, size=(K, N)).astype(np.float64)
+        A = to_device(synth.store(Ah, dtype), dtype)
+        B = to_device(synth.store(Bh, dtype), dtype)
+        want = oracle.matmul(Ah, Bh)
+        assert np.abs(want).max() < 256          # representable in bf16's 8-bit significand
+        for cfg in (0, 1, 2, 3):
+            C = torch.empty((M, N), dtype=torch_dtype(dtype), device="cuda")
+            rl.runlora_gemm(A, B, C, tile_cfg=cfg, splits=2)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_f64(C), want), (dtype, cfg)
+
+
+def test_gemm_strided_rows_and_aliased_addend():
+    """Leading dimensions larger than the row length; D aliasing C (the '+=' of the default chain)."""
+    import torch
+    dtype = "bf16"
+    M, N, K = 200, 136, 72
+    Abuf, Abh = make(9, 1, (M, K + 24), dtype)
+    Bbuf, Bbh = make(9, 2, (K, N + 8), dtype, 1.0 / K)
+    Cbuf, Cbh = make(9, 3, (M, N + 16), dtype)
+    A, B, C = Abuf[:, :K], Bbuf[:, :N], Cbuf[:, :N]
+    want = oracle.matmul(Abh[:, :K].copy(), Bbh[:, :N].copy()) + Cbh[:, :N]
+    rl.runlora_gemm(A, B, C, D=C)
+    torch.cuda.synchronize()
+    assert relerr(to_f64(C), want) < TOL[dtype]
+    assert np.array_equal(to_f64(Cbuf[:, N:]), Cbh[:, N:])      # padding columns untouched
