@@ -192,9 +192,10 @@ size_t runlora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o
  *              (a_strided = 1 with b_kcontig = 1 is not provided)
  *   K2 = 0     no second segment.   D = NULL: no addend (D may alias C).
  *   tile_cfg   -1 = library heuristic, else 0..5 = 256x256, 128x128, 128x32, 128x64, 32x128,
- *              64x128 output tile per workgroup
+ *              64x128 output tile per workgroup (generic engine), 6 / 7 = 256x256 with 4 / 8
+ *              wavefronts in the hand-pipelined kernel (16-bit types; fp32 falls back to 0)
  *   splits     0 = heuristic, n > 0 = split the contraction n ways (fp32 partials in the
- *              workspace, summed in a fixed order; needs K2 = 0)
+ *              workspace, summed in a fixed order)
  * Same dtype / alignment rules as the layer calls (M arbitrary when A is [M,K]; every other
  * dimension a multiple of 8, or 4 for fp32).  Workspace: runlora_gemm_workspace_bytes().
  */
@@ -207,6 +208,27 @@ typedef struct {
 } rl_gemm_t;
 int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts);
 size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g);
+
+/*
+ * Per-kernel timing, for measurement runs (the bench's roofline figures, calibration of the time
+ * model).  While enabled, every layer call made from this thread records a pair of HIP events
+ * around each step it enqueues (at most max_steps per collect; further steps go untimed).
+ * runlora_profile_collect waits for the recorded events, writes one rl_step_time_t per step in
+ * launch order (up to cap), forgets them, and returns how many it wrote (or a negative status).
+ * `what` points to a static string naming the product in the paper's notation; flops = 2*M*N*K of
+ * that product; bytes = one read of each operand plus the output (and addend) in the storage
+ * dtype.  Events are host objects created at enable and destroyed at disable; no device memory.
+ */
+typedef struct {
+  const char* what;
+  double us;
+  double flops, bytes;
+  int64_t M, N, K;
+  int32_t tile_cfg, splits, a_strided, b_kcontig;
+} rl_step_time_t;
+int runlora_profile_enable(int max_steps);
+int runlora_profile_collect(rl_step_time_t* out, int cap);
+int runlora_profile_disable(void);
 
 const char* runlora_strerror(int code);
 const char* runlora_last_hip_error(void); /* text of the last RL_ERR_HIP on this thread */

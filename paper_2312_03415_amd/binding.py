@@ -31,6 +31,7 @@ EXPORTS = (
     "runlora_forward", "runlora_backward", "runlora_select", "runlora_select_by", "runlora_flops",
     "runlora_model_time_us", "runlora_workspace_bytes", "runlora_strerror", "runlora_last_hip_error",
     "runlora_version", "runlora_gemm", "runlora_gemm_workspace_bytes",
+    "runlora_profile_enable", "runlora_profile_collect", "runlora_profile_disable",
 )
 
 
@@ -59,6 +60,13 @@ class rl_gemm_t(ctypes.Structure):
                 ("D", ctypes.c_void_p), ("C", ctypes.c_void_p),
                 ("lda", ctypes.c_int64), ("ldb", ctypes.c_int64), ("lda2", ctypes.c_int64), ("ldb2", ctypes.c_int64),
                 ("ldc", ctypes.c_int64), ("ldd", ctypes.c_int64)]
+
+
+class rl_step_time_t(ctypes.Structure):
+    _fields_ = [("what", ctypes.c_char_p), ("us", ctypes.c_double), ("flops", ctypes.c_double),
+                ("bytes", ctypes.c_double), ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("tile_cfg", ctypes.c_int32), ("splits", ctypes.c_int32), ("a_strided", ctypes.c_int32),
+                ("b_kcontig", ctypes.c_int32)]
 
 
 class RunLoRAError(RuntimeError):
@@ -105,6 +113,12 @@ def lib():
     L.runlora_gemm.restype = ci
     L.runlora_gemm_workspace_bytes.argtypes = [ctypes.POINTER(rl_gemm_t)]
     L.runlora_gemm_workspace_bytes.restype = ctypes.c_size_t
+    L.runlora_profile_enable.argtypes = [ci]
+    L.runlora_profile_enable.restype = ci
+    L.runlora_profile_collect.argtypes = [ctypes.POINTER(rl_step_time_t), ci]
+    L.runlora_profile_collect.restype = ci
+    L.runlora_profile_disable.argtypes = []
+    L.runlora_profile_disable.restype = ci
     _lib = L
     return L
 
@@ -213,6 +227,24 @@ def runlora_gemm(A, B, C, a_strided=False, b_kcontig=False, A2=None, B2=None, D=
     o = _opts(workspace, stream)
     _check(lib().runlora_gemm(ctypes.byref(g), ctypes.byref(o)))
     return C
+
+
+def runlora_profile_enable(max_steps):
+    _check(lib().runlora_profile_enable(max_steps))
+
+
+def runlora_profile_collect(cap=4096):
+    """Per-step timings of the layer calls since enable / the last collect, as a list of dicts."""
+    buf = (rl_step_time_t * cap)()
+    k = lib().runlora_profile_collect(buf, cap)
+    if k < 0:
+        _check(k)
+    keys = ("us", "flops", "bytes", "M", "N", "K", "tile_cfg", "splits", "a_strided", "b_kcontig")
+    return [dict(what=buf[j].what.decode(), **{f: getattr(buf[j], f) for f in keys}) for j in range(k)]
+
+
+def runlora_profile_disable():
+    _check(lib().runlora_profile_disable())
 
 
 # ---- conveniences on top of the ABI (device memory only) --------------------------------------

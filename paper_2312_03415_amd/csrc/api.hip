@@ -1,6 +1,7 @@
 // C ABI of the library (include/runlora.h): argument checks, variant schedules -> launches.
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "../../include/runlora.h"
 #include "schedule.hpp"
@@ -60,11 +61,44 @@ Mat mat(const rl_tensor_t* t) {
   return m;
 }
 
+// optional per-step event timing (runlora_profile_*), one recorder per host thread
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> start, stop;
+  std::vector<rl_step_time_t> rec;
+  size_t used = 0;
+};
+thread_local Profiler g_prof;
+
+void describe_step(const Step& s, rl_step_time_t* r) {
+  const GemmDesc& d = s.d;
+  const double K = (double)(d.K[0] + (d.nseg > 1 ? d.K[1] : 0));
+  const double e = (double)dtype_size(d.dtype);
+  r->what = s.what;
+  r->us = 0.0;
+  r->flops = 2.0 * (double)d.M * (double)d.N * K;
+  r->bytes = e * ((double)d.M * K + K * (double)d.N + (double)d.M * (double)d.N * (d.D ? 2.0 : 1.0));
+  r->M = d.M; r->N = d.N; r->K = (int64_t)K;
+  r->tile_cfg = s.plan.cfg; r->splits = s.plan.splits;
+  r->a_strided = d.a_strided; r->b_kcontig = d.b_kcontig;
+}
+
 int run_schedule(const Schedule& sch, char* ws, hipStream_t stream) {
   float* partial = ws ? reinterpret_cast<float*>(ws + sch.partial_offset) : nullptr;
   for (const Step& s : sch.steps) {
+    const bool timed = g_prof.on && g_prof.used < g_prof.start.size();
+    if (timed) {
+      hipError_t e = hipEventRecord(g_prof.start[g_prof.used], stream);
+      if (e != hipSuccess) return set_hip_error(e, "profile event");
+    }
     hipError_t e = gemm_run(s.d, s.plan, partial, stream);
     if (e != hipSuccess) return set_hip_error(e, s.what);
+    if (timed) {
+      e = hipEventRecord(g_prof.stop[g_prof.used], stream);
+      if (e != hipSuccess) return set_hip_error(e, "profile event");
+      describe_step(s, &g_prof.rec[g_prof.used]);
+      ++g_prof.used;
+    }
   }
   return RL_OK;
 }
@@ -244,7 +278,6 @@ static int check_gemm(const rl_gemm_t* g, GemmDesc* d, GemmPlan* plan) {
   if (g->M > (1LL << 30) || g->N > (1LL << 30) || g->K > (1LL << 30) || g->K2 > (1LL << 30)) return RL_ERR_SHAPE;
   if (g->K2 > 0 && (!g->A2 || !g->B2)) return RL_ERR_NULL;
   if (g->tile_cfg < -1 || g->tile_cfg >= CFG_COUNT || g->splits < 0) return RL_ERR_VARIANT;
-  if (g->splits > 1 && g->K2 > 0) return RL_ERR_UNSUPPORTED;
   const int64_t q = dt == DT_F32 ? 4 : 8;
   if (g->N % q || g->K % q || g->K2 % q || (g->a_strided && g->M % q)) return RL_ERR_ALIGN;
   const int64_t a_cols = g->a_strided ? g->M : g->K, a2_cols = g->a_strided ? g->M : g->K2;
@@ -265,7 +298,7 @@ static int check_gemm(const rl_gemm_t* g, GemmDesc* d, GemmPlan* plan) {
   d->A[0] = g->A; d->B[0] = g->B; d->lda[0] = g->lda; d->ldb[0] = g->ldb; d->K[0] = g->K;
   d->A[1] = g->A2; d->B[1] = g->B2; d->lda[1] = g->lda2; d->ldb[1] = g->ldb2; d->K[1] = g->K2;
   d->C = g->C; d->ldc = g->ldc; d->D = g->D; d->ldd = g->ldd;
-  *plan = gemm_plan(dt, g->M, g->N, g->K, g->K2, g->tile_cfg, g->K2 > 0 ? 1 : g->splits);
+  *plan = gemm_plan(dt, g->M, g->N, g->K, g->K2, g->tile_cfg, g->splits);
   return RL_OK;
 }
 
@@ -291,4 +324,59 @@ extern "C" int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts) {
   hipError_t e = gemm_run(d, plan, scratch, stream);
   if (e != hipSuccess) return set_hip_error(e, "runlora_gemm");
   return RL_OK;
+}
+
+// ---- per-step timing ------------------------------------------------------------------------------
+
+extern "C" int runlora_profile_disable(void) {
+  for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
+  for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
+  g_prof.start.clear();
+  g_prof.stop.clear();
+  g_prof.rec.clear();
+  g_prof.used = 0;
+  g_prof.on = false;
+  return RL_OK;
+}
+
+extern "C" int runlora_profile_enable(int max_steps) {
+  if (max_steps < 1 || max_steps > (1 << 20)) return RL_ERR_SHAPE;
+  runlora_profile_disable();
+  g_prof.start.resize(max_steps);
+  g_prof.stop.resize(max_steps);
+  g_prof.rec.resize(max_steps);
+  for (int k = 0; k < max_steps; ++k) {
+    hipError_t e = hipEventCreate(&g_prof.start[k]);
+    if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[k]);
+    if (e != hipSuccess) {
+      g_prof.start.resize(k);
+      g_prof.stop.resize(k);
+      runlora_profile_disable();
+      return set_hip_error(e, "hipEventCreate");
+    }
+  }
+  g_prof.on = true;
+  return RL_OK;
+}
+
+extern "C" int runlora_profile_collect(rl_step_time_t* out, int cap) {
+  if (!out && cap > 0) return RL_ERR_NULL;
+  if (!g_prof.on) return 0;
+  int written = 0;
+  for (size_t k = 0; k < g_prof.used; ++k) {
+    hipError_t e = hipEventSynchronize(g_prof.stop[k]);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.start[k], g_prof.stop[k]);
+    if (e != hipSuccess) {
+      g_prof.used = 0;
+      return set_hip_error(e, "profile collect");
+    }
+    if (written < cap) {
+      out[written] = g_prof.rec[k];
+      out[written].us = (double)ms * 1e3;
+      ++written;
+    }
+  }
+  g_prof.used = 0;
+  return written;
 }

@@ -1,4 +1,5 @@
 #define RL_T float
 #define RL_BK 32
 #define RL_FN gemm_launch_f32
+#define RL_PIPE 0
 #include "gemm_launch.inc"

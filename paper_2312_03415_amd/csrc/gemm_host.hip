@@ -4,16 +4,17 @@
 
 namespace rl {
 
-static const int kTileBM[CFG_COUNT] = {256, 128, 128, 128, 32, 64};
-static const int kTileBN[CFG_COUNT] = {256, 128, 32, 64, 128, 128};
+static const int kTileBM[CFG_COUNT] = {256, 128, 128, 128, 32, 64, 256, 256};
+static const int kTileBN[CFG_COUNT] = {256, 128, 32, 64, 128, 128, 128, 256};
+static const int kTileBK16[CFG_COUNT] = {64, 64, 64, 64, 64, 64, 32, 64};  // K tile, 16-bit types
 
 GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg,
                    int force_splits) {
   GemmPlan p;
-  p.bk = (dtype == DT_F32) ? 32 : 64;
   int cfg;
   if (force_cfg >= 0 && force_cfg < CFG_COUNT) {
     cfg = force_cfg;
+    if ((cfg == CFG_P256x128 || cfg == CFG_P256x256) && dtype == DT_F32) cfg = CFG_BIG;  // 16-bit only
   } else if (M <= 32) {
     cfg = CFG_WIDE32;
   } else if (M <= 64) {
@@ -23,11 +24,17 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   } else if (N <= 64) {
     cfg = CFG_TALL64;
   } else {
-    // the 256x256 tile needs enough tiles to occupy the 256 compute units
+    // the 256x256 tile needs enough tiles to occupy the 256 compute units; a grid between half
+    // and full is filled by splitting the contraction in two
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-    cfg = big_tiles >= 192 ? CFG_BIG : CFG_MID;
+    const bool pipe_ok = dtype != DT_F32;
+    if (big_tiles >= 160 || (big_tiles >= 80 && K0 + K1 >= 2048))
+      cfg = pipe_ok ? CFG_P256x256 : CFG_BIG;
+    else
+      cfg = CFG_MID;
   }
   p.cfg = cfg;
+  p.bk = (dtype == DT_F32) ? 32 : kTileBK16[cfg];
   p.bm = kTileBM[cfg];
   p.bn = kTileBN[cfg];
   p.nbm = (int)((M + p.bm - 1) / p.bm);
@@ -37,6 +44,8 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   int splits = 1;
   if (force_splits > 0) {
     splits = force_splits;
+  } else if (cfg == CFG_P256x256 || cfg == CFG_BIG) {
+    if (tiles < 160 && ktiles >= 16) splits = (int)((256 + tiles - 1) / tiles);
   } else if (tiles < 256 && ktiles >= 8) {
     // fill the chip (aim at ~512 workgroups) but keep >= 4 K tiles per slice
     int64_t want = (512 + tiles - 1) / tiles;
@@ -57,6 +66,12 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
 hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream) {
   if (d.M <= 0 || d.N <= 0) return hipErrorInvalidValue;
   if (plan.splits > 1 && scratch == nullptr) return hipErrorInvalidValue;
+  int cfg = plan.cfg;
+  if (cfg == CFG_P256x128 || cfg == CFG_P256x256) {
+    // the pipelined kernel addresses segment 0 with 32-bit element offsets
+    const int64_t a_rows = d.a_strided ? d.K[0] : d.M, b_rows = d.b_kcontig ? d.N : d.K[0];
+    if (a_rows * d.lda[0] >= (1LL << 32) || b_rows * d.ldb[0] >= (1LL << 32) || d.dtype == DT_F32) cfg = CFG_BIG;
+  }
   GemmArgs a{};
   for (int s = 0; s < 2; ++s) {
     const bool on = s < d.nseg;
@@ -80,9 +95,9 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   const int al = d.a_strided ? 1 : 0, bl = d.b_kcontig ? 1 : 0;
   hipError_t e;
   switch (d.dtype) {
-    case DT_BF16: e = gemm_launch_bf16(plan.cfg, al, bl, a, grid, stream); break;
-    case DT_F16: e = gemm_launch_f16(plan.cfg, al, bl, a, grid, stream); break;
-    case DT_F32: e = gemm_launch_f32(plan.cfg, al, bl, a, grid, stream); break;
+    case DT_BF16: e = gemm_launch_bf16(cfg, al, bl, a, grid, stream); break;
+    case DT_F16: e = gemm_launch_f16(cfg, al, bl, a, grid, stream); break;
+    case DT_F32: e = gemm_launch_f32(cfg, al, bl, a, grid, stream); break;
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;

@@ -19,6 +19,8 @@ SHAPES = {
     3: (300, 56, 200),    # 128x64
     4: (24, 264, 456),    # 32x128
     5: (56, 264, 456),    # 64x128
+    6: (600, 520, 328),   # 256x256, pipelined kernel, 4 wavefronts (fp32 falls back to config 0)
+    7: (600, 520, 328),   # 256x256, pipelined kernel, 8 wavefronts
 }
 
 
@@ -65,11 +67,16 @@ def test_gemm_two_segments_and_heuristic_plan(layout, dtype):
     B, Bh = make(5, 3, (N, K) if b_kc else (K, N), dtype, 1.0 / K)
     B2, B2h = make(5, 4, (N, K2) if b_kc else (K2, N), dtype, 1.0 / K2)
     want = oracle.matmul(Ah, Bh, tb=b_kc) + oracle.matmul(A2h, B2h, tb=b_kc)
-    for cfg in (-1, 0, 1):
+    for cfg in (-1, 0, 1, 6, 7):
         C = torch.full((M, N), float("nan"), dtype=torch_dtype(dtype), device="cuda")
         rl.runlora_gemm(A, B, C, b_kcontig=b_kc, A2=A2, B2=B2, tile_cfg=cfg)
         torch.cuda.synchronize()
         assert relerr(to_f64(C), want) < TOL[dtype], cfg
+        # contraction split across both segments
+        C = torch.full((M, N), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+        rl.runlora_gemm(A, B, C, b_kcontig=b_kc, A2=A2, B2=B2, tile_cfg=cfg, splits=2)
+        torch.cuda.synchronize()
+        assert relerr(to_f64(C), want) < TOL[dtype], (cfg, "split")
 
 
 def test_gemm_exact_on_small_integers():
@@ -84,7 +91,7 @@ def test_gemm_exact_on_small_integers():
         B = to_device(synth.store(Bh, dtype), dtype)
         want = oracle.matmul(Ah, Bh)
         assert np.abs(want).max() < 256          # representable in bf16's 8-bit significand
-        for cfg in (0, 1, 2, 3):
+        for cfg in (0, 1, 2, 3, 6, 7):
             C = torch.empty((M, N), dtype=torch_dtype(dtype), device="cuda")
             rl.runlora_gemm(A, B, C, tile_cfg=cfg, splits=2)
             torch.cuda.synchronize()
