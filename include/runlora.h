@@ -191,9 +191,12 @@ size_t runlora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o
  *   b_kcontig  0: B (and B2) stored [K,N] row-major;  1: stored [N,K]   (dY W^T style)
  *              (a_strided = 1 with b_kcontig = 1 is not provided)
  *   K2 = 0     no second segment.   D = NULL: no addend (D may alias C).
- *   tile_cfg   -1 = library heuristic, else 0..5 = 256x256, 128x128, 128x32, 128x64, 32x128,
- *              64x128 output tile per workgroup (generic engine), 6 / 7 = 256x256 with 4 / 8
- *              wavefronts in the hand-pipelined kernel (16-bit types; fp32 falls back to 0)
+ *   tile_cfg   -1 = library heuristic; 0..5 = 256x256, 128x128, 128x32, 128x64, 32x128, 64x128
+ *              output tile per workgroup in the generic engine; 6 / 7 = 256x128x32 (4 wavefronts)
+ *              / 256x256x64 (8 wavefronts) in the hand-pipelined kernel (16-bit types; fp32 falls
+ *              back to 0); 8 = the streaming kernel for rank-r products (N <= 128, no second
+ *              segment, no addend: 4 wavefronts per 32 output rows split the contraction)
+ *   trans_out  1 = store C transposed, as [N,M] with ldc >= M (streaming kernel only); else 0
  *   splits     0 = heuristic, n > 0 = split the contraction n ways (fp32 partials in the
  *              workspace, summed in a fixed order)
  * Same dtype / alignment rules as the layer calls (M arbitrary when A is [M,K]; every other
@@ -205,6 +208,7 @@ typedef struct {
   const void *A, *B, *A2, *B2, *D;
   void* C;
   int64_t lda, ldb, lda2, ldb2, ldc, ldd;
+  int32_t trans_out;
 } rl_gemm_t;
 int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts);
 size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g);

@@ -59,7 +59,7 @@ class rl_gemm_t(ctypes.Structure):
                 ("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("A2", ctypes.c_void_p), ("B2", ctypes.c_void_p),
                 ("D", ctypes.c_void_p), ("C", ctypes.c_void_p),
                 ("lda", ctypes.c_int64), ("ldb", ctypes.c_int64), ("lda2", ctypes.c_int64), ("ldb2", ctypes.c_int64),
-                ("ldc", ctypes.c_int64), ("ldd", ctypes.c_int64)]
+                ("ldc", ctypes.c_int64), ("ldd", ctypes.c_int64), ("trans_out", ctypes.c_int32)]
 
 
 class rl_step_time_t(ctypes.Structure):
@@ -207,7 +207,7 @@ def runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype):
 
 
 def runlora_gemm(A, B, C, a_strided=False, b_kcontig=False, A2=None, B2=None, D=None, tile_cfg=-1, splits=0,
-                 workspace=None, stream=None):
+                 workspace=None, stream=None, trans_out=False):
     """C = op(A) op(B) (+ op(A2) op(B2)) (+ D) through the library's tile GEMM (see runlora.h)."""
     import torch
     M = A.shape[1] if a_strided else A.shape[0]
@@ -220,7 +220,7 @@ def runlora_gemm(A, B, C, a_strided=False, b_kcontig=False, A2=None, B2=None, D=
                   A.data_ptr(), B.data_ptr(), A2.data_ptr() if A2 is not None else None,
                   B2.data_ptr() if B2 is not None else None, D.data_ptr() if D is not None else None, C.data_ptr(),
                   A.stride(0), B.stride(0), A2.stride(0) if A2 is not None else 0,
-                  B2.stride(0) if B2 is not None else 0, C.stride(0), D.stride(0) if D is not None else 0)
+                  B2.stride(0) if B2 is not None else 0, C.stride(0), D.stride(0) if D is not None else 0, int(trans_out))
     need = int(lib().runlora_gemm_workspace_bytes(ctypes.byref(g)))
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=C.device)

@@ -71,6 +71,23 @@ struct Profiler {
 thread_local Profiler g_prof;
 
 void describe_step(const Step& s, rl_step_time_t* r) {
+  if (s.nsk > 0) {
+    const double e = (double)dtype_size(s.d.dtype);
+    r->what = s.what;
+    r->us = 0.0;
+    r->flops = 0.0;
+    r->bytes = 0.0;
+    for (int w = 0; w < s.nsk; ++w) {
+      const SkinnyDesc& k = s.sk[w];
+      r->flops += 2.0 * (double)k.M * (double)k.N * (double)k.K;
+      r->bytes += e * ((double)k.M * k.K + (double)k.K * k.N + (double)k.M * k.N);
+    }
+    r->M = s.sk[0].M; r->N = s.sk[0].N; r->K = s.sk[0].K;
+    r->tile_cfg = CFG_COUNT + (s.skplan.rt == 1 ? 0 : (s.skplan.rt == 2 ? 1 : 2));
+    r->splits = s.skplan.splits;
+    r->a_strided = s.sk[0].a_strided; r->b_kcontig = s.sk[0].b_kcontig;
+    return;
+  }
   const GemmDesc& d = s.d;
   const double K = (double)(d.K[0] + (d.nseg > 1 ? d.K[1] : 0));
   const double e = (double)dtype_size(d.dtype);
@@ -91,7 +108,8 @@ int run_schedule(const Schedule& sch, char* ws, hipStream_t stream) {
       hipError_t e = hipEventRecord(g_prof.start[g_prof.used], stream);
       if (e != hipSuccess) return set_hip_error(e, "profile event");
     }
-    hipError_t e = gemm_run(s.d, s.plan, partial, stream);
+    hipError_t e = s.nsk > 0 ? skinny_run(s.d.dtype, s.nsk, s.sk, s.skplan, partial, stream)
+                             : gemm_run(s.d, s.plan, partial, stream);
     if (e != hipSuccess) return set_hip_error(e, s.what);
     if (timed) {
       e = hipEventRecord(g_prof.stop[g_prof.used], stream);
@@ -277,12 +295,21 @@ static int check_gemm(const rl_gemm_t* g, GemmDesc* d, GemmPlan* plan) {
   if (g->M < 1 || g->N < 1 || g->K < 1 || g->K2 < 0) return RL_ERR_SHAPE;
   if (g->M > (1LL << 30) || g->N > (1LL << 30) || g->K > (1LL << 30) || g->K2 > (1LL << 30)) return RL_ERR_SHAPE;
   if (g->K2 > 0 && (!g->A2 || !g->B2)) return RL_ERR_NULL;
-  if (g->tile_cfg < -1 || g->tile_cfg >= CFG_COUNT || g->splits < 0) return RL_ERR_VARIANT;
+  if (g->tile_cfg < -1 || g->tile_cfg > CFG_COUNT || g->splits < 0) return RL_ERR_VARIANT;
+  if (g->trans_out != 0 && g->trans_out != 1) return RL_ERR_VARIANT;
+  if (g->tile_cfg == CFG_COUNT) {  // the streaming kernel
+    if (g->N > 128 || g->K2 > 0 || g->D) return RL_ERR_UNSUPPORTED;
+    const int64_t esz = g->dtype == RL_F32 ? 4 : 2;
+    const int64_t a_rows = g->a_strided ? g->K : g->M, b_rows = g->b_kcontig ? g->N : g->K;
+    if (a_rows * g->lda * esz >= (1LL << 31) || b_rows * g->ldb * esz >= (1LL << 31)) return RL_ERR_UNSUPPORTED;
+  } else if (g->trans_out) {
+    return RL_ERR_UNSUPPORTED;
+  }
   const int64_t q = dt == DT_F32 ? 4 : 8;
   if (g->N % q || g->K % q || g->K2 % q || (g->a_strided && g->M % q)) return RL_ERR_ALIGN;
   const int64_t a_cols = g->a_strided ? g->M : g->K, a2_cols = g->a_strided ? g->M : g->K2;
   const int64_t b_cols = g->b_kcontig ? g->K : g->N, b2_cols = g->b_kcontig ? g->K2 : g->N;
-  if (g->lda < a_cols || g->ldb < b_cols || g->ldc < g->N) return RL_ERR_SHAPE;
+  if (g->lda < a_cols || g->ldb < b_cols || g->ldc < (g->trans_out ? g->M : g->N)) return RL_ERR_SHAPE;
   if (g->K2 > 0 && (g->lda2 < a2_cols || g->ldb2 < b2_cols)) return RL_ERR_SHAPE;
   if (g->D && g->ldd < g->N) return RL_ERR_SHAPE;
   const void* ptrs[6] = {g->A, g->B, g->A2, g->B2, g->D, g->C};
@@ -298,14 +325,32 @@ static int check_gemm(const rl_gemm_t* g, GemmDesc* d, GemmPlan* plan) {
   d->A[0] = g->A; d->B[0] = g->B; d->lda[0] = g->lda; d->ldb[0] = g->ldb; d->K[0] = g->K;
   d->A[1] = g->A2; d->B[1] = g->B2; d->lda[1] = g->lda2; d->ldb[1] = g->ldb2; d->K[1] = g->K2;
   d->C = g->C; d->ldc = g->ldc; d->D = g->D; d->ldd = g->ldd;
-  *plan = gemm_plan(dt, g->M, g->N, g->K, g->K2, g->tile_cfg, g->splits);
+  if (g->tile_cfg != CFG_COUNT) *plan = gemm_plan(dt, g->M, g->N, g->K, g->K2, g->tile_cfg, g->splits);
   return RL_OK;
+}
+
+static void gemm_as_skinny(const rl_gemm_t* g, SkinnyDesc* k, SkinnyPlan* plan) {
+  k->A = g->A; k->B = g->B; k->C = g->C;
+  k->lda = g->lda; k->ldb = g->ldb; k->ldc = g->ldc;
+  k->M = g->M; k->N = g->N; k->K = g->K;
+  k->a_strided = g->a_strided; k->b_kcontig = g->b_kcontig; k->trans_out = g->trans_out;
+  *plan = skinny_plan(internal_dtype(g->dtype), 1, k);
+  if (g->splits > 0) {
+    plan->splits = g->splits;
+    plan->partial_bytes = g->splits > 1 ? (size_t)g->splits * (size_t)g->M * (size_t)g->N * sizeof(float) : 0;
+  }
 }
 
 extern "C" size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g) {
   GemmDesc d;
   GemmPlan plan;
   if (check_gemm(g, &d, &plan) != RL_OK) return 0;
+  if (g->tile_cfg == CFG_COUNT) {
+    SkinnyDesc k;
+    SkinnyPlan sp;
+    gemm_as_skinny(g, &k, &sp);
+    return sp.partial_bytes;
+  }
   return plan.partial_bytes;
 }
 
@@ -314,6 +359,13 @@ extern "C" int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts) {
   GemmPlan plan;
   int rc = check_gemm(g, &d, &plan);
   if (rc != RL_OK) return rc;
+  SkinnyDesc k;
+  SkinnyPlan sp;
+  const bool streaming = g->tile_cfg == CFG_COUNT;
+  if (streaming) {
+    gemm_as_skinny(g, &k, &sp);
+    plan.partial_bytes = sp.partial_bytes;
+  }
   float* scratch = nullptr;
   if (plan.partial_bytes > 0) {
     if (!opts || !opts->workspace || opts->workspace_bytes < plan.partial_bytes) return RL_ERR_WORKSPACE;
@@ -321,7 +373,7 @@ extern "C" int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts) {
     scratch = static_cast<float*>(opts->workspace);
   }
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
-  hipError_t e = gemm_run(d, plan, scratch, stream);
+  hipError_t e = streaming ? skinny_run(d.dtype, 1, &k, sp, scratch, stream) : gemm_run(d, plan, scratch, stream);
   if (e != hipSuccess) return set_hip_error(e, "runlora_gemm");
   return RL_OK;
 }

@@ -50,6 +50,30 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
 // Enqueue the product.  `scratch` must hold plan.partial_bytes when plan.splits > 1.
 hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream);
 
+// ---- streaming kernel for the rank-r products (skinny.hpp) --------------------------------------
+// C[M,N<=128] = op(A)[M,K] op(B)[K,N], optionally stored transposed; up to two problems per launch.
+struct SkinnyDesc {
+  const void* A = nullptr;
+  const void* B = nullptr;
+  void* C = nullptr;
+  int64_t lda = 0, ldb = 0, ldc = 0;
+  int64_t M = 0, N = 0, K = 0;
+  int a_strided = 0, b_kcontig = 0, trans_out = 0;
+};
+struct SkinnyPlan {
+  int rt = 1;      // 32-column blocks per row block: N <= 32*rt
+  int splits = 1;  // K split over workgroups (fp32 partials + ordered reduce)
+  size_t partial_bytes = 0;
+};
+inline bool skinny_ok(int64_t N) { return N <= 128; }
+SkinnyPlan skinny_plan(int dtype, int nprob, const SkinnyDesc* d);
+hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPlan& plan, float* scratch,
+                      hipStream_t stream);
+struct SkinnyArgs;
+hipError_t skinny_launch_bf16(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
+hipError_t skinny_launch_f16(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
+hipError_t skinny_launch_f32(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
+
 // per-dtype launchers (one translation unit each)
 struct GemmArgs;
 hipError_t gemm_launch_bf16(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);

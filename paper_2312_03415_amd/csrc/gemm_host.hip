@@ -1,6 +1,7 @@
 // Launch planning and dispatch for the tile GEMM engine.
 #include "gemm.hpp"
 #include "gemm_engine.hpp"
+#include "skinny.hpp"
 
 namespace rl {
 
@@ -128,6 +129,80 @@ hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+// ---- streaming kernel for the rank-r products -----------------------------------------------------
+
+SkinnyPlan skinny_plan(int dtype, int nprob, const SkinnyDesc* d) {
+  SkinnyPlan p;
+  const int bk = dtype == DT_F32 ? 32 : 64;
+  int64_t blocks = 0, min_ktiles = 1 << 30, outs = 0, maxn = 0;
+  for (int w = 0; w < nprob; ++w) {
+    blocks += (d[w].M + 31) / 32;
+    const int64_t kt = (d[w].K + bk - 1) / bk;
+    if (kt < min_ktiles) min_ktiles = kt;
+    outs += d[w].M * d[w].N;
+    if (d[w].N > maxn) maxn = d[w].N;
+  }
+  p.rt = maxn <= 32 ? 1 : (maxn <= 64 ? 2 : 4);
+  // one workgroup of 8 waves per compute unit already keeps enough loads in flight; split K over
+  // workgroups only when there are fewer row blocks than compute units, and keep >= 4 K tiles
+  // per wave and slice
+  int64_t splits = 1;
+  if (blocks < 224) {
+    splits = (256 + blocks - 1) / blocks;
+    int64_t cap = min_ktiles / 32;
+    if (cap < 1) cap = 1;
+    if (splits > cap) splits = cap;
+    if (splits > 16) splits = 16;
+  }
+  p.splits = (int)splits;
+  p.partial_bytes = splits > 1 ? (size_t)splits * (size_t)outs * sizeof(float) : 0;
+  return p;
+}
+
+hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPlan& plan, float* scratch,
+                      hipStream_t stream) {
+  if (nprob < 1 || nprob > 2) return hipErrorInvalidValue;
+  if (plan.splits > 1 && scratch == nullptr) return hipErrorInvalidValue;
+  const int bk = dtype == DT_F32 ? 32 : 64;
+  SkinnyArgs a{};
+  a.nprob = nprob;
+  int64_t blocks = 0;
+  float* part = scratch;
+  for (int w = 0; w < nprob; ++w) {
+    SkinnyProblem& P = a.p[w];
+    if (d[w].N > 32 * plan.rt || d[w].M < 1 || d[w].K < 1) return hipErrorInvalidValue;
+    P.A = d[w].A; P.B = d[w].B; P.C = d[w].C;
+    P.lda = d[w].lda; P.ldb = d[w].ldb; P.ldc = d[w].ldc;
+    P.M = (int)d[w].M; P.N = (int)d[w].N; P.K = (int)d[w].K;
+    P.a_strided = d[w].a_strided; P.b_kcontig = d[w].b_kcontig; P.trans_out = d[w].trans_out;
+    P.row_blocks = (int)((d[w].M + 31) / 32);
+    {
+      const int64_t esz = dtype == DT_F32 ? 4 : 2;
+      const int64_t a_rows = d[w].a_strided ? d[w].K : d[w].M, a_cols = d[w].a_strided ? d[w].M : d[w].K;
+      const int64_t b_rows = d[w].b_kcontig ? d[w].N : d[w].K, b_cols = d[w].b_kcontig ? d[w].K : d[w].N;
+      const int64_t ab = ((a_rows - 1) * d[w].lda + a_cols) * esz, bb = ((b_rows - 1) * d[w].ldb + b_cols) * esz;
+      if (ab >= (1LL << 31) || bb >= (1LL << 31)) return hipErrorInvalidValue;  // callers check skinny_fits()
+      P.a_bytes = (int)ab;
+      P.b_bytes = (int)bb;
+    }
+    const int64_t kt = (d[w].K + bk - 1) / bk;
+    P.tiles_per_split = (int)((kt + plan.splits - 1) / plan.splits);
+    P.partial = nullptr;
+    if (plan.splits > 1) {
+      P.partial = part;
+      part += (size_t)plan.splits * (size_t)d[w].M * (size_t)d[w].N;
+    }
+    blocks += P.row_blocks;
+  }
+  dim3 grid((unsigned)blocks, (unsigned)plan.splits, 1);
+  switch (dtype) {
+    case DT_BF16: return skinny_launch_bf16(plan.rt, a, grid, plan.splits, stream);
+    case DT_F16: return skinny_launch_f16(plan.rt, a, grid, plan.splits, stream);
+    case DT_F32: return skinny_launch_f32(plan.rt, a, grid, plan.splits, stream);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace rl

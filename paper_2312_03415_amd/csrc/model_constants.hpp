@@ -14,7 +14,7 @@ struct ModelConstants {
 
 inline const ModelConstants& model_constants() {
   static const ModelConstants c = {
-      {{900.0, 600.0, 150.0, 250.0, 150.0, 250.0}, {60.0, 45.0, 20.0, 30.0, 20.0, 30.0}},
+      {{850.0, 700.0, 150.0, 250.0, 150.0, 250.0, 900.0, 1000.0}, {125.0, 110.0, 20.0, 30.0, 20.0, 30.0, 125.0, 125.0}},
       3.0,
       3.0,
   };

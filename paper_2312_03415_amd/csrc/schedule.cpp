@@ -47,11 +47,107 @@ struct Builder {
     out->steps.push_back(s);
   }
 
+  // Rank-r product C[M,N] = op(A) op(B) (N = r, or M = r with the output stored transposed) on the
+  // streaming kernel; falls back to the tile GEMM when r is too large for it.
+  struct Sk {
+    int a_strided, b_kcontig;
+    int64_t M, N, K;
+    Mat A, B, C;
+  };
+  static SkinnyDesc to_skinny(const Sk& g) {
+    SkinnyDesc d;
+    if (g.N <= g.M || g.a_strided == 0) {
+      d.A = g.A.ptr; d.lda = g.A.ld; d.B = g.B.ptr; d.ldb = g.B.ld; d.C = const_cast<void*>(g.C.ptr); d.ldc = g.C.ld;
+      d.M = g.M; d.N = g.N; d.K = g.K; d.a_strided = g.a_strided; d.b_kcontig = g.b_kcontig; d.trans_out = 0;
+    } else {
+      // short M (= r), long N, both operands stored [K, .]: compute C^T = op(B)^T op(A)
+      d.A = g.B.ptr; d.lda = g.B.ld; d.B = g.A.ptr; d.ldb = g.A.ld; d.C = const_cast<void*>(g.C.ptr); d.ldc = g.C.ld;
+      d.M = g.N; d.N = g.M; d.K = g.K; d.a_strided = 1; d.b_kcontig = 0; d.trans_out = 1;
+    }
+    return d;
+  }
+  bool sk_ok(const Sk& g) const {
+    // operands are addressed with 31-bit byte offsets
+    const int64_t esz = (int64_t)dtype_size(L.dtype);
+    const int64_t a_rows = g.a_strided ? g.K : g.M, b_rows = g.b_kcontig ? g.N : g.K;
+    if (a_rows * g.A.ld * esz >= (1LL << 31) || b_rows * g.B.ld * esz >= (1LL << 31)) return false;
+    return sk_shape_ok(g);
+  }
+  static bool sk_shape_ok(const Sk& g) {
+    const int64_t shortdim = (g.N <= g.M || g.a_strided == 0) ? g.N : g.M;
+    // the transposed form needs both operands stored [K, .]
+    if (!(g.N <= g.M || g.a_strided == 0) && g.b_kcontig) return false;
+    return skinny_ok(shortdim);
+  }
+  void skinny(const char* what, const Sk& g) {
+    if (!sk_ok(g)) {
+      gemm(what, g.a_strided, g.b_kcontig, g.M, g.N, g.K, g.A, g.B, g.C);
+      return;
+    }
+    Step s;
+    s.what = what;
+    s.nsk = 1;
+    s.d.dtype = L.dtype;
+    s.sk[0] = to_skinny(g);
+    s.skplan = skinny_plan(L.dtype, 1, s.sk);
+    if (s.skplan.partial_bytes > max_partial) max_partial = s.skplan.partial_bytes;
+    out->steps.push_back(s);
+  }
+  void skinny2(const char* what, const char* what1, const Sk& g1, const char* what2, const Sk& g2) {
+    bool pair = sk_ok(g1) && sk_ok(g2);
+    SkinnyDesc d1, d2;
+    if (pair) {
+      d1 = to_skinny(g1);
+      d2 = to_skinny(g2);
+      // one launch serves both only if they stream the same way: same A layout, and the B layouts
+      // in an order the kernel is built for ([N,K] first when they differ)
+      if (d1.a_strided != d2.a_strided) pair = false;
+      else if (d1.b_kcontig == 0 && d2.b_kcontig == 1) { SkinnyDesc t = d1; d1 = d2; d2 = t; }
+      if (pair && d1.a_strided == 1 && (d1.b_kcontig || d2.b_kcontig)) pair = false;
+    }
+    if (!pair) {
+      skinny(what1, g1);
+      skinny(what2, g2);
+      return;
+    }
+    Step s;
+    s.what = what;
+    s.nsk = 2;
+    s.d.dtype = L.dtype;
+    s.sk[0] = d1;
+    s.sk[1] = d2;
+    s.skplan = skinny_plan(L.dtype, 2, s.sk);
+    if (s.skplan.partial_bytes > max_partial) max_partial = s.skplan.partial_bytes;
+    out->steps.push_back(s);
+  }
+
   void finish() {
     out->partial_offset = used;
     out->workspace_bytes = used + (max_partial + kAlign - 1) / kAlign * kAlign;
   }
 };
+
+// Z1 = dY B^T and Z2 = X A in one launch, then dA = X^T Z1 and dB = Z2^T dY in one launch
+// (Algorithms 1 and 5 share these four statements).
+void rank_r_pass(Builder& b, const BwdOperands& op, int64_t n, int64_t i, int64_t o, int64_t r, Mat Z1, Mat Z2,
+                 bool need_Z1, bool need_Z2, bool dA, bool dB) {
+  const Builder::Sk z1{0, 1, n, r, o, op.dY, op.B, Z1}, z2{0, 0, n, r, i, op.X, op.A, Z2};
+  if (need_Z1 && need_Z2) b.skinny2("Z1 = dY B^T ; Z2 = X A", "Z1 = dY B^T", z1, "Z2 = X A", z2);
+  else if (need_Z1) b.skinny("Z1 = dY B^T", z1);
+  else if (need_Z2) b.skinny("Z2 = X A", z2);
+  const Builder::Sk ga{1, 0, i, r, n, op.X, Z1, op.dA}, gb{1, 0, r, o, n, Z2, op.dY, op.dB};
+  if (dA && dB) b.skinny2("dA = X^T Z1 ; dB = Z2^T dY", "dA = X^T Z1", ga, "dB = Z2^T dY", gb);
+  else if (dA) b.skinny("dA = X^T Z1", ga);
+  else if (dB) b.skinny("dB = Z2^T dY", gb);
+}
+
+// dA = Z2 B^T and dB = A^T Z2 (Algorithms 3 and 4), one launch when both are wanted
+void z2_grads(Builder& b, const BwdOperands& op, int64_t i, int64_t o, int64_t r, Mat Z2, bool dA, bool dB) {
+  const Builder::Sk ga{0, 1, i, r, o, Z2, op.B, op.dA}, gb{1, 0, r, o, i, op.A, Z2, op.dB};
+  if (dA && dB) b.skinny2("dA = Z2 B^T ; dB = A^T Z2", "dA = Z2 B^T", ga, "dB = A^T Z2", gb);
+  else if (dA) b.skinny("dA = Z2 B^T", ga);
+  else if (dB) b.skinny("dB = A^T Z2", gb);
+}
 
 }  // namespace
 
@@ -61,14 +157,14 @@ bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void*
   const int64_t n = L.n, i = L.i, o = L.o, r = L.r;
   switch (variant) {
     case 0: {  // default chain: T kept, one kernel per product
-      b.gemm("T = X A", 0, 0, n, r, i, op.X, op.A, op.T);
+      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, op.T});
       b.gemm("Y = X W", 0, 0, n, o, i, op.X, op.W, op.Y);
       b.gemm("Y += T B", 0, 0, n, o, r, op.T, op.B, op.Y, &op.Y);
       break;
     }
     case 1: {  // forward1: (XW) + ((XA)B), the sum folded into one contraction over [X|T]
       Mat T = b.scratch(n, r);
-      b.gemm("T = X A", 0, 0, n, r, i, op.X, op.A, T);
+      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T});
       b.gemm("Y = [X|T] [W;B]", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, r, &T, &op.B);
       break;
     }
@@ -93,9 +189,10 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
   switch (variant) {
     case 0: {  // backward of the default chain (uses the kept T = XA)
       Mat Z1 = b.scratch(n, r);
-      if (dA || dX) b.gemm("Z1 = dY B^T", 0, 1, n, r, o, op.dY, op.B, Z1);
-      if (dB) b.gemm("dB = T^T dY", 1, 0, r, o, n, op.T, op.dY, op.dB);
-      if (dA) b.gemm("dA = X^T Z1", 1, 0, i, r, n, op.X, Z1, op.dA);
+      // one kernel per product, as autograd would run them
+      if (dA || dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1});
+      if (dB) b.skinny("dB = T^T dY", {1, 0, r, o, n, op.T, op.dY, op.dB});
+      if (dA) b.skinny("dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA});
       if (dX) {
         b.gemm("dX = dY W^T", 0, 1, n, i, o, op.dY, op.W, op.dX);
         b.gemm("dX += Z1 A^T", 0, 1, n, i, r, Z1, op.A, op.dX, &op.dX);
@@ -104,28 +201,27 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     }
     case 1: {  // Algorithm 1
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r);
-      if (dA || dX) b.gemm("Z1 = dY B^T", 0, 1, n, r, o, op.dY, op.B, Z1);
-      if (dB) b.gemm("Z2 = X A", 0, 0, n, r, i, op.X, op.A, Z2);
-      if (dA) b.gemm("dA = X^T Z1", 1, 0, i, r, n, op.X, Z1, op.dA);
-      if (dB) b.gemm("dB = Z2^T dY", 1, 0, r, o, n, Z2, op.dY, op.dB);
+      rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA || dX, dB, dA, dB);
       if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A);
       break;
     }
     case 2: {  // Algorithm 2
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(i, o);
-      if (dA || dX) b.gemm("Z1 = dY B^T", 0, 1, n, r, o, op.dY, op.B, Z1);
+      if (dA || dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1});
       if (dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
-      if (dA) b.gemm("dA = X^T Z1", 1, 0, i, r, n, op.X, Z1, op.dA);
-      if (dB) b.gemm("dB = A^T Z2", 1, 0, r, o, i, op.A, Z2, op.dB);
+      if (dA && dB)
+        b.skinny2("dA = X^T Z1 ; dB = A^T Z2", "dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA}, "dB = A^T Z2",
+                  {1, 0, r, o, i, op.A, Z2, op.dB});
+      else if (dA) b.skinny("dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA});
+      else if (dB) b.skinny("dB = A^T Z2", {1, 0, r, o, i, op.A, Z2, op.dB});
       if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A);
       break;
     }
     case 3: {  // Algorithm 3
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(i, o);
-      if (dX) b.gemm("Z1 = dY B^T", 0, 1, n, r, o, op.dY, op.B, Z1);
+      if (dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1});
       if (dA || dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
-      if (dA) b.gemm("dA = Z2 B^T", 0, 1, i, r, o, Z2, op.B, op.dA);
-      if (dB) b.gemm("dB = A^T Z2", 1, 0, r, o, i, op.A, Z2, op.dB);
+      z2_grads(b, op, i, o, r, Z2, dA, dB);
       if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A);
       break;
     }
@@ -133,18 +229,14 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
       Mat Z1 = b.scratch(i, o), Z2 = b.scratch(i, o);
       if (dX) b.gemm("Z1 = W + A B", 0, 0, i, o, r, op.A, op.B, Z1, &op.W);
       if (dA || dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
-      if (dA) b.gemm("dA = Z2 B^T", 0, 1, i, r, o, Z2, op.B, op.dA);
-      if (dB) b.gemm("dB = A^T Z2", 1, 0, r, o, i, op.A, Z2, op.dB);
+      z2_grads(b, op, i, o, r, Z2, dA, dB);
       if (dX) b.gemm("dX = dY Z1^T", 0, 1, n, i, o, op.dY, Z1, op.dX);
       break;
     }
     case 5: {  // Algorithm 5
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r), Z3 = b.scratch(i, o);
-      if (dA) b.gemm("Z1 = dY B^T", 0, 1, n, r, o, op.dY, op.B, Z1);
-      if (dB) b.gemm("Z2 = X A", 0, 0, n, r, i, op.X, op.A, Z2);
       if (dX) b.gemm("Z3 = W + A B", 0, 0, i, o, r, op.A, op.B, Z3, &op.W);
-      if (dA) b.gemm("dA = X^T Z1", 1, 0, i, r, n, op.X, Z1, op.dA);
-      if (dB) b.gemm("dB = Z2^T dY", 1, 0, r, o, n, Z2, op.dY, op.dB);
+      rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA, dB, dA, dB);
       if (dX) b.gemm("dX = dY Z3^T", 0, 1, n, i, o, op.dY, Z3, op.dX);
       break;
     }

@@ -21,9 +21,12 @@ struct LayerDims {
 };
 
 struct Step {
+  int nsk = 0;  // 0: one tile-GEMM launch (d, plan); 1 or 2: streaming-kernel launch of sk[0..nsk-1]
   GemmDesc d;
   GemmPlan plan;
-  const char* what = "";  // the product in the paper's notation, e.g. "Z1 = dY B^T"
+  SkinnyDesc sk[2];
+  SkinnyPlan skplan;
+  const char* what = "";  // the product(s) in the paper's notation, e.g. "Z1 = dY B^T"
 };
 
 struct Schedule {

@@ -39,6 +39,20 @@ int64_t table1_flops(int is_bwd, int v, int64_t n, int64_t i, int64_t o, int64_t
 // memory traffic at the measured streaming rate, plus a fixed launch cost; a split contraction
 // adds the write and re-read of the fp32 partials and the reduce launch.
 static double step_time_us(const Step& s) {
+  const ModelConstants& mc = model_constants();
+  if (s.nsk > 0) {
+    // streaming kernel: one read of each operand, one write of the (small) output
+    const double e = (double)dtype_size(s.d.dtype);
+    double bytes = 0, outs = 0;
+    for (int w = 0; w < s.nsk; ++w) {
+      const SkinnyDesc& k = s.sk[w];
+      bytes += e * ((double)k.M * k.K + (double)k.K * k.N + (double)k.M * k.N);
+      outs += (double)k.M * k.N;
+    }
+    double us = bytes / (mc.stream_tbps * 1e12) * 1e6 + mc.launch_us;
+    if (s.skplan.splits > 1) us += 2.0 * 4.0 * outs * s.skplan.splits / (mc.stream_tbps * 1e12) * 1e6 + mc.launch_us;
+    return us;
+  }
   const GemmDesc& d = s.d;
   const GemmPlan& p = s.plan;
   const double e = (double)dtype_size(d.dtype);
@@ -46,7 +60,7 @@ static double step_time_us(const Step& s) {
   // the engine multiplies whole tiles: count the padded problem
   const double Mp = (double)p.nbm * p.bm, Np = (double)p.nbn * p.bn;
   const double flops = 2.0 * Mp * Np * K;
-  const ModelConstants& c = model_constants();
+  const ModelConstants& c = mc;
   const int fam = d.dtype == DT_F32 ? 1 : 0;
   double rate = c.tile_tflops[fam][p.cfg] * 1e12;
   // few workgroups leave compute units idle

@@ -187,6 +187,14 @@ def test_gemm_call_rejects_bad_arguments():
     g.N = 64
     g.tile_cfg = 17
     assert L.runlora_gemm(ctypes.byref(g), None) == rl.RL_ERR_VARIANT
+    g.tile_cfg = 8          # streaming kernel: N <= 128 only
+    g.N = 136
+    assert L.runlora_gemm(ctypes.byref(g), None) == rl.RL_ERR_UNSUPPORTED
+    g.N = 64
+    g.tile_cfg = 1
+    g.trans_out = 1         # transposed store exists in the streaming kernel only
+    assert L.runlora_gemm(ctypes.byref(g), None) == rl.RL_ERR_UNSUPPORTED
+    g.trans_out = 0
     g.tile_cfg = -1
     g.C = None
     assert L.runlora_gemm(ctypes.byref(g), None) == rl.RL_ERR_NULL

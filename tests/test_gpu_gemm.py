@@ -112,3 +112,31 @@ def test_gemm_strided_rows_and_aliased_addend():
     torch.cuda.synchronize()
     assert relerr(to_f64(C), want) < TOL[dtype]
     assert np.array_equal(to_f64(Cbuf[:, N:]), Cbh[:, N:])      # padding columns untouched
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("layout", list(LAYOUTS))
+@pytest.mark.parametrize("N", [8, 24, 56, 120])
+def test_streaming_kernel(N, layout, dtype):
+    """The rank-r streaming kernel (tile_cfg 8): every operand layout, ragged M and K, K split over
+    workgroups or not, plain and transposed store."""
+    import torch
+    a_str, b_kc = LAYOUTS[layout]
+    M, K = (264, 1000) if a_str else (333, 520)
+    print(f"case streaming N={N} layout={layout} dtype={dtype}", flush=True)
+    A, Ah = make(7, 1, (K, M) if a_str else (M, K), dtype)
+    B, Bh = make(7, 2, (N, K) if b_kc else (K, N), dtype, 1.0 / K)
+    want = oracle.matmul(Ah, Bh, ta=a_str, tb=b_kc)
+    for splits in (1, 3):
+        C = torch.full((M, N), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+        rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, tile_cfg=8, splits=splits)
+        Ct = torch.full((N, (M + 7) // 8 * 8), float("nan"), dtype=torch_dtype(dtype), device="cuda")[:, :M]
+        rl.runlora_gemm(A, B, Ct, a_strided=a_str, b_kcontig=b_kc, tile_cfg=8, splits=splits, trans_out=True)
+        torch.cuda.synchronize()
+        assert relerr(to_f64(C), want) < TOL[dtype], splits
+        assert relerr(to_f64(Ct), want.T) < TOL[dtype], splits
+    # heuristic split
+    C = torch.full((M, N), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, tile_cfg=8)
+    torch.cuda.synchronize()
+    assert relerr(to_f64(C), want) < TOL[dtype]
