@@ -1,0 +1,150 @@
+"""Measure the constants of the selector's time model on the GPU this runs on and write
+csrc/model_constants.hpp (then rebuild the library):
+
+    python -m paper_2312_03415_amd.calibrate [--out PATH]
+
+Everything is timed through the library's own C ABI (runlora_gemm), the way a caller sees it: HIP
+events around a batch of calls on one stream, rotating operand sets so that the 256 MB Infinity
+Cache does not serve them.  Per tile shape and operand layout two contraction lengths give the
+time per K tile and the fixed cost of a round of workgroups; a third run with an addend gives the
+fixed cost with D; short second segments give the pipelined kernel's slow-tile cost; the streaming
+kernel is timed on both orientations of the big operand; a tiny problem gives the launch cost.
+"""
+import argparse
+import os
+
+import torch
+
+from . import binding as rl
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+TILE_BM = [256, 128, 128, 128, 32, 64, 256, 256]
+TILE_BN = [256, 128, 32, 64, 128, 128, 128, 256]
+TILE_BK16 = [64, 64, 64, 64, 64, 64, 32, 64]
+WG_PER_CU = [1, 2, 3, 2, 3, 3, 2, 1]
+NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x128x32 pipelined", "256x256x64 pipelined"]
+LAYOUTS = {"NN": (0, 0), "NT": (0, 1), "TN": (1, 0)}
+
+
+def timeit(fn, iters=8, warm=2):
+    for k in range(warm):
+        fn(k)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for k in range(iters):
+        fn(k)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters * 1e3
+
+
+def gemm_time(dt, layout, M, N, K, cfg, K2=0, addend=False, splits=1, sets=3, trans=False):
+    a_str, b_kc = LAYOUTS[layout]
+    As = [torch.randn((K, M) if a_str else (M, K), device="cuda").to(dt) for _ in range(sets)]
+    Bs = [(torch.randn((N, K) if b_kc else (K, N), device="cuda") / K ** 0.5).to(dt) for _ in range(sets)]
+    C = torch.empty((N, M) if trans else (M, N), device="cuda", dtype=dt)
+    D = torch.randn((M, N), device="cuda").to(dt) if addend else None
+    A2 = torch.randn((M, K2), device="cuda").to(dt) if K2 else None
+    B2 = torch.randn((N, K2) if b_kc else (K2, N), device="cuda").to(dt) if K2 else None
+    ws = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    return timeit(lambda k: rl.runlora_gemm(As[k % sets], Bs[k % sets], C, a_strided=a_str, b_kcontig=b_kc, A2=A2, B2=B2,
+                                            D=D, tile_cfg=cfg, splits=splits, workspace=ws, trans_out=trans))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default=os.path.join(HERE, "csrc", "model_constants.hpp"))
+    args = ap.parse_args()
+    rl.lib()
+    bf, f32 = torch.bfloat16, torch.float32
+
+    # launch cost: a one-tile problem
+    launch = min(gemm_time(bf, "NN", 128, 128, 64, 1) for _ in range(3))
+    print("launch_us", round(launch, 2), flush=True)
+
+    tiles = {0: {}, 1: {}}
+    for fam, dt in ((0, bf), (1, f32)):
+        for cfg in range(8):
+            if fam == 1 and cfg >= 6:
+                tiles[fam][cfg] = dict(tiles[fam][0])   # fp32 falls back to the generic 256x256 tile
+                continue
+            bm, bn = TILE_BM[cfg], TILE_BN[cfg]
+            bk = 32 if fam == 1 else TILE_BK16[cfg]
+            slots = 256 * WG_PER_CU[cfg]
+            # two full rounds of workgroups: 32 tile rows x (2*slots/32) tile columns
+            M, N = bm * 32, bn * (2 * slots // 32)
+            k_long, k_short = (2048, 256) if fam == 1 else (4096, 512)
+            tk, fix = [], []
+            for layout in ("NN", "NT", "TN"):
+                t_long = gemm_time(dt, layout, M, N, k_long, cfg)
+                t_short = gemm_time(dt, layout, M, N, k_short, cfg)
+                per_tile = (t_long - t_short) / 2.0 / ((k_long - k_short) / bk)
+                tk.append(max(per_tile, 1e-3))
+                fix.append(max((t_short - launch) / 2.0 - (k_short / bk) * per_tile, 0.5))
+            t_d = gemm_time(dt, "NN", M, N, k_short, cfg, addend=True)
+            fix_d = max((t_d - launch) / 2.0 - (k_short / bk) * tk[0], fix[0])
+            tiles[fam][cfg] = dict(tk=tk, fix=sum(fix) / 3.0, fix_d=fix_d)
+            print(fam, NAMES[cfg], [round(v, 3) for v in tk], round(tiles[fam][cfg]["fix"], 2), round(fix_d, 2), flush=True)
+
+    # slow-tile cost of the pipelined kernel: a 64-wide second segment = one more (slow) K tile per round
+    t0 = gemm_time(bf, "NT", 8192, 4096, 4096, 7)
+    t1 = gemm_time(bf, "NT", 8192, 4096, 4096, 7, K2=64)
+    slow = max((t1 - t0) / 2.0 - tiles[0][7]["tk"][1], 0.0)
+    print("slow_tile_us", round(slow, 2), flush=True)
+
+    # streaming kernel: two sizes per orientation -> rate and fixed cost
+    def stream(layout, M, K, sets):
+        return gemm_time(bf, layout, M, 32, K, 8, sets=sets)
+    rates, fixes = [], []
+    # both sizes rotate over > 512 MB of operands, beyond the 256 MB Infinity Cache
+    for layout, (Mb, Kb), (Ms, Ks) in (("NN", (8192, 8192), (8192, 2048)), ("TN", (8192, 8192), (8192, 2048))):
+        tb, ts = stream(layout, Mb, Kb, 5), stream(layout, Ms, Ks, 18)
+        bytes_b, bytes_s = 2.0 * Mb * Kb, 2.0 * Ms * Ks
+        rate = (bytes_b - bytes_s) / (tb - ts) / 1e6          # TB/s
+        rates.append(rate)
+        fixes.append(max(ts - launch - bytes_s / rate / 1e6, 0.0))
+    print("stream_tbps", [round(v, 2) for v in rates], "fix", [round(v, 2) for v in fixes], flush=True)
+
+    # reduce stage: forced 4-way split of a streaming problem vs no split
+    t1 = gemm_time(bf, "NN", 8192, 128, 4096, 8, splits=1)
+    t4 = gemm_time(bf, "NN", 8192, 128, 4096, 8, splits=4)
+    extra = max(t4 - t1 - launch, 1.0)
+    reduce_tbps = 4.0 * 8192 * 128 * 5 / extra / 1e6
+    print("reduce_tbps", round(reduce_tbps, 2), flush=True)
+
+    def row(t):
+        return "{{%.3f, %.3f, %.3f}, %.2f, %.2f, %d}" % (t["tk"][0], t["tk"][1], t["tk"][2], t["fix"], t["fix_d"], t["wg"])
+
+    lines = []
+    for fam in (0, 1):
+        rows = []
+        for cfg in range(8):
+            t = dict(tiles[fam][cfg], wg=WG_PER_CU[cfg])
+            rows.append("           %s,  // %s" % (row(t), NAMES[cfg]))
+        lines.append("       {\n" + "\n".join(rows) + "\n       }")
+    body = ",\n".join(lines)
+    text = open(args.out).read()
+    head = text[:text.index("inline const ModelConstants& model_constants()")]
+    out = head + """inline const ModelConstants& model_constants() {
+  static const ModelConstants c = {
+      {
+%s},
+      %.2f,
+      {%.2f, %.2f},
+      %.2f,
+      %.2f,
+      %.2f,
+  };
+  return c;
+}
+
+}  // namespace rl
+""" % (body, slow, rates[0], rates[1], sum(fixes) / 2.0, reduce_tbps, launch)
+    with open(args.out, "w") as fh:
+        fh.write(out)
+    print("wrote", args.out)
+
+
+if __name__ == "__main__":
+    main()

@@ -288,8 +288,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
         } else {
           if (g.D) {
             const T* d = static_cast<const T*>(g.D) + (int64_t)m * g.ldd + n;
+            if constexpr (sizeof(T) == 4) {
+              v += *reinterpret_cast<const f32x4*>(d);
+            } else {
+              T d4[4];
+              *reinterpret_cast<i32x2*>(d4) = *reinterpret_cast<const i32x2*>(d);  // one 8-byte load
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)d[e];
+              for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
+            }
           }
           T* c = static_cast<T*>(g.C) + (int64_t)m * g.ldc + n;
           if constexpr (sizeof(T) == 4) {

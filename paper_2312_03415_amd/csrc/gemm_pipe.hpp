@@ -70,9 +70,26 @@ __global__ __launch_bounds__(WM* WN * 64, MIN_WG) void gemm_pipe_kernel(GemmArgs
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in a scalar register
   const int wm = wave / WN, wn = wave % WN;
 
-  // workgroup -> tile (XCD-contiguous renumbering, bands of 8 tile rows; see gemm_kernel)
+  const int nt0 = (g.K[0] + BK - 1) / BK, nt1 = (g.K[1] + BK - 1) / BK;
+  const int full0 = g.K[0] / BK;  // tiles of segment 0 that are complete: the fast path
+  const int t_begin = blockIdx.y * g.tiles_per_split;
+  int t_end = t_begin + g.tiles_per_split;
+  if (t_end > nt0 + nt1) t_end = nt0 + nt1;
+  const T* A0 = static_cast<const T*>(g.A[0]);
+  const T* B0 = static_cast<const T*>(g.B[0]);
+  const size_t stepA = P::A_STR ? (size_t)BK * (size_t)g.lda[0] : (size_t)BK;
+  const size_t stepB = P::B_STR ? (size_t)BK * (size_t)g.ldb[0] : (size_t)BK;
+  const int l31 = lane & 31, hi = lane >> 5, s16 = lane & 15;
+
+  // Persistent workgroups: each walks the output tiles seq = blockIdx.x, blockIdx.x + gridDim.x, ...
+  // so that the stores of one tile drain while the next tile's K loop already runs (a fresh
+  // workgroup per tile would expose every tile's write burst).
   const int total = g.nbm * g.nbn;
-  int id = blockIdx.x;
+  for (int seq = blockIdx.x; seq < total; seq += gridDim.x) {
+  // tile sequence -> tile: consecutive sequence numbers go to different XCDs (8 of them, each with
+  // its own L2), so renumber such that each XCD works on a contiguous run of tiles, then walk the
+  // tile grid in bands of 8 tile rows (a run shares A rows and B columns in its L2)
+  int id = seq;
   {
     const int x = id & 7, slot = id >> 3, q = total >> 3, rem = total & 7;
     id = x * q + (x < rem ? x : rem) + slot;
@@ -84,17 +101,10 @@ __global__ __launch_bounds__(WM* WN * 64, MIN_WG) void gemm_pipe_kernel(GemmArgs
   const int in_band = id - band * per_band;
   const int tile_m = first_m + in_band % band_rows, tile_n = in_band / band_rows;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  const int nt0 = (g.K[0] + BK - 1) / BK, nt1 = (g.K[1] + BK - 1) / BK;
-  const int full0 = g.K[0] / BK;  // tiles of segment 0 that are complete: the fast path
-  const int t_begin = blockIdx.y * g.tiles_per_split;
-  int t_end = t_begin + g.tiles_per_split;
-  if (t_end > nt0 + nt1) t_end = nt0 + nt1;
+  if (seq != (int)blockIdx.x) __syncthreads();  // the previous tile's last LDS reads are done
 
   // ---- fast-path source offsets (segment 0), one per LDS-DMA instruction of this lane.  Rows and
   // columns beyond the matrix are clamped: they only feed outputs that are never stored.
-  const T* A0 = static_cast<const T*>(g.A[0]);
-  const T* B0 = static_cast<const T*>(g.B[0]);
   uint32_t offA[A_IPW], offB[B_IPW];
 #pragma unroll
   for (int j = 0; j < A_IPW; ++j) {
@@ -122,9 +132,6 @@ __global__ __launch_bounds__(WM* WN * 64, MIN_WG) void gemm_pipe_kernel(GemmArgs
       offB[j] = (uint32_t)row * (uint32_t)g.ldb[0] + (uint32_t)gc;
     }
   }
-  const size_t stepA = P::A_STR ? (size_t)BK * (size_t)g.lda[0] : (size_t)BK;
-  const size_t stepB = P::B_STR ? (size_t)BK * (size_t)g.ldb[0] : (size_t)BK;
-
   // Request K tile t into LDS stage `st`.
   auto issue_tile = [&](int t, int st) {
     unsigned char* sA = smem + st * P::STAGE_BYTES;
@@ -191,7 +198,6 @@ __global__ __launch_bounds__(WM* WN * 64, MIN_WG) void gemm_pipe_kernel(GemmArgs
   };
 
   // ---- fragment reads (one 32-wide block of an operand for K step ks) ---------------------------
-  const int l31 = lane & 31, hi = lane >> 5, s16 = lane & 15;
   // K-contiguous tile: row q, 16 bytes at k = 16*ks + 8*hi
   auto read_kc = [&](const unsigned char* tile, int idx0, int ks) -> i32x4 {
     constexpr int CPR = BK / 8, SH = (BK == 64) ? 1 : 2;
@@ -315,8 +321,14 @@ __global__ __launch_bounds__(WM* WN * 64, MIN_WG) void gemm_pipe_kernel(GemmArgs
         } else {
           if (g.D) {
             const T* d = static_cast<const T*>(g.D) + (int64_t)m * g.ldd + n;
+            if constexpr (sizeof(T) == 4) {
+              v += *reinterpret_cast<const f32x4*>(d);
+            } else {
+              T d4[4];
+              *reinterpret_cast<i32x2*>(d4) = *reinterpret_cast<const i32x2*>(d);  // one 8-byte load
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)d[e];
+              for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
+            }
           }
           T* c = static_cast<T*>(g.C) + (int64_t)m * g.ldc + n;
           T o4[4] = {from_f32<T>(v[0]), from_f32<T>(v[1]), from_f32<T>(v[2]), from_f32<T>(v[3])};
@@ -325,6 +337,7 @@ __global__ __launch_bounds__(WM* WN * 64, MIN_WG) void gemm_pipe_kernel(GemmArgs
       }
     }
   }
+  }  // persistent tile loop
 }
 
 }  // namespace rl

@@ -35,48 +35,46 @@ int64_t table1_flops(int is_bwd, int v, int64_t n, int64_t i, int64_t o, int64_t
   }
 }
 
-// Time of one GEMM launch: the slower of its arithmetic at the tile shape's measured rate and its
-// memory traffic at the measured streaming rate, plus a fixed launch cost; a split contraction
-// adds the write and re-read of the fp32 partials and the reduce launch.
+// Time of one launch.
+//  Streaming kernel: bytes / measured streaming rate + a fixed cost (+ the partials' round trip
+//  and the reduce launch when the contraction is also split over workgroups).
+//  Tile GEMM: workgroups run in rounds of (compute units x resident workgroups); a round costs
+//  (K tiles x measured time per K tile) + a fixed prologue/epilogue; partial and second-segment K
+//  tiles of the pipelined kernel go through its slower loader; a split contraction adds the
+//  write and re-read of the fp32 partials and the reduce launch.
 static double step_time_us(const Step& s) {
   const ModelConstants& mc = model_constants();
+  const double e = (double)dtype_size(s.d.dtype);
   if (s.nsk > 0) {
-    // streaming kernel: one read of each operand, one write of the (small) output
-    const double e = (double)dtype_size(s.d.dtype);
-    double bytes = 0, outs = 0;
+    double us = mc.stream_fix_us + mc.launch_us;
+    double outs = 0;
     for (int w = 0; w < s.nsk; ++w) {
       const SkinnyDesc& k = s.sk[w];
-      bytes += e * ((double)k.M * k.K + (double)k.K * k.N + (double)k.M * k.N);
+      const double bytes = e * ((double)k.M * k.K + (double)k.K * k.N + (double)k.M * k.N);
+      us += bytes / (mc.stream_tbps[k.a_strided ? 1 : 0] * 1e12) * 1e6;
       outs += (double)k.M * k.N;
     }
-    double us = bytes / (mc.stream_tbps * 1e12) * 1e6 + mc.launch_us;
-    if (s.skplan.splits > 1) us += 2.0 * 4.0 * outs * s.skplan.splits / (mc.stream_tbps * 1e12) * 1e6 + mc.launch_us;
+    if (s.skplan.splits > 1) us += 4.0 * outs * (s.skplan.splits + 1) / (mc.reduce_tbps * 1e12) * 1e6 + mc.launch_us;
     return us;
   }
   const GemmDesc& d = s.d;
   const GemmPlan& p = s.plan;
-  const double e = (double)dtype_size(d.dtype);
-  const double K = (double)(d.K[0] + (d.nseg > 1 ? d.K[1] : 0));
-  // the engine multiplies whole tiles: count the padded problem
-  const double Mp = (double)p.nbm * p.bm, Np = (double)p.nbn * p.bn;
-  const double flops = 2.0 * Mp * Np * K;
-  const ModelConstants& c = mc;
-  const int fam = d.dtype == DT_F32 ? 1 : 0;
-  double rate = c.tile_tflops[fam][p.cfg] * 1e12;
-  // few workgroups leave compute units idle
+  const TileModel& tm = mc.tile[d.dtype == DT_F32 ? 1 : 0][p.cfg];
+  const int lay = d.a_strided ? 2 : (d.b_kcontig ? 1 : 0);
   const double wgs = (double)p.nbm * p.nbn * p.splits;
-  const double fill = wgs >= 256.0 ? 1.0 : wgs / 256.0;
-  rate *= fill;
-  // operand traffic: each A row-band is read once per pass over the column tiles that do not share
-  // an L2, modelled as one read of each operand plus the output (and addend)
-  double bytes = e * ((double)d.M * K + K * (double)d.N + (double)d.M * d.N * (d.D ? 2.0 : 1.0));
-  double t = flops / rate;
-  double tm = bytes / (c.stream_tbps * 1e12);
-  double us = (t > tm ? t : tm) * 1e6 + c.launch_us;
-  if (p.splits > 1) {
-    const double pb = (double)p.partial_bytes;
-    us += 2.0 * pb / (c.stream_tbps * 1e12) * 1e6 + c.launch_us;
-  }
+  const double slots = 256.0 * tm.wg_per_cu;
+  double rounds = wgs / slots;
+  rounds = rounds <= 1.0 ? 1.0 : (double)(int64_t)(rounds + 0.999);
+  const int64_t kt0 = (d.K[0] + p.bk - 1) / p.bk, kt1 = d.nseg > 1 ? (d.K[1] + p.bk - 1) / p.bk : 0;
+  double ktiles = (double)(kt0 + kt1);
+  if (p.splits > 1) ktiles = (double)p.tiles_per_split;
+  double slow = 0;
+  if (p.cfg == CFG_P256x256 || p.cfg == CFG_P256x128) slow = (double)(kt1 + (d.K[0] % p.bk ? 1 : 0));
+  const bool addend = d.D != nullptr && p.splits == 1;
+  double us = rounds * (ktiles * tm.tk_us[lay] + (addend ? tm.tfix_d_us : tm.tfix_us) + slow * mc.slow_tile_us) +
+              mc.launch_us;
+  if (p.splits > 1)
+    us += (double)d.M * d.N * (4.0 * (p.splits + 1) + (d.D ? e : 0.0) + e) / (mc.reduce_tbps * 1e12) * 1e6 + mc.launch_us;
   return us;
 }
 
