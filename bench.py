@@ -29,7 +29,11 @@ TILE_NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/), scaled by what the same counters read for a copy kernel of known size; None until
 # measured for the workload.
-TRAFFIC_BYTES = {}
+TRAFFIC_BYTES = {
+    # profiles/bench_opt13b_hbm_traffic.txt: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per launch
+    ("opt13b", "gemm_kernel<bf16,NN,256x256p>"): int((105639 * 2.0 + 84189) * 1024),
+    ("opt13b", "gemm_kernel<bf16,NT,256x256p>"): int((116572 * 2.0 + 86586) * 1024),
+}
 
 
 def parse():
@@ -41,6 +45,8 @@ def parse():
     ap.add_argument("--rank", type=int, default=None, help="LoRA rank override (llama7b: 8/32/128)")
     ap.add_argument("--sets", type=int, default=3, help="rotating input/output sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a 1 GiB device copy five times (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -59,6 +65,14 @@ def main():
     rl.lib()  # fail loudly if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4, "copies": 5}))
+        return
 
     if args.workload == "opt13b":
         layers = synth.config_opt13b_mlp("bf16")
@@ -144,9 +158,11 @@ def main():
     recs = rl.runlora_profile_collect(args.steps * len(layers) * 16)
     rl.runlora_profile_disable()
     groups = {}
+    ridge = MFMA_PEAK_TFLOPS[dtype] * 1e12 / (HBM_PEAK_GBPS * 1e9)
     for r in recs:
         lay = "NN" if not r["a_strided"] and not r["b_kcontig"] else ("NT" if r["b_kcontig"] else "TN")
-        key = (lay, TILE_NAMES[r["tile_cfg"]])
+        # the same kernel serves compute-bound contractions and memory-bound ones (W + AB has K = r)
+        key = (lay, TILE_NAMES[r["tile_cfg"]] + ("" if r["flops"] / r["bytes"] >= ridge else "/mem"))
         g = groups.setdefault(key, dict(us=0.0, flops=0.0, bytes=0.0, launches=0, what=set()))
         g["us"] += r["us"]; g["flops"] += r["flops"]; g["bytes"] += r["bytes"]; g["launches"] += 1
         g["what"].add(r["what"])
@@ -154,7 +170,6 @@ def main():
     dom = groups[dom_key]
     total_kernel_us = sum(g["us"] for g in groups.values())
     intensity = dom["flops"] / dom["bytes"]
-    ridge = MFMA_PEAK_TFLOPS[dtype] * 1e12 / (HBM_PEAK_GBPS * 1e9)
     kname = "gemm_kernel<%s,%s,%s>" % (dtype, dom_key[0], dom_key[1])
     if intensity >= ridge:
         ach = dom["flops"] / dom["us"] / 1e6
@@ -164,6 +179,11 @@ def main():
         ach = dom["bytes"] / dom["us"] / 1e3
         roofline = dict(bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
                         frac=round(ach / HBM_PEAK_GBPS, 4))
+    if roofline["bound"] == "mfma":
+        # what a bare MFMA loop sustains on this (power-limited) GPU: on zeros, and on random operands
+        roofline["mfma_probe_tflops"] = {"zeros": round(rl.runlora_probe_mfma(False), 1),
+                                         "random": round(rl.runlora_probe_mfma(True), 1)}
+        roofline["frac_of_random_data_probe"] = round(ach / roofline["mfma_probe_tflops"]["random"], 4)
     roofline.update(traffic=TRAFFIC_BYTES.get((args.workload, kname)), kernel=kname,
                     products=sorted(dom["what"]), launches_per_step=dom["launches"] / args.steps,
                     avg_launch_us=round(dom["us"] / dom["launches"], 2),

@@ -234,6 +234,15 @@ int runlora_profile_enable(int max_steps);
 int runlora_profile_collect(rl_step_time_t* out, int cap);
 int runlora_profile_disable(void);
 
+/*
+ * Measure what the matrix cores sustain on this GPU with nothing else running: a loop of
+ * independent bf16 MFMAs on zeros (random_data = 0) or on random operands (random_data = 1).
+ * The chip is power-limited, so the two differ; the second is the ceiling for N(0,1)-like data.
+ * scratch: device buffer of at least 512 KiB (overwritten).  Synchronises the stream.  Result in
+ * TFLOP/s through *tflops (host).  For measurement reports only.
+ */
+int runlora_probe_mfma(void* scratch, size_t scratch_bytes, int random_data, void* stream, double* tflops);
+
 const char* runlora_strerror(int code);
 const char* runlora_last_hip_error(void); /* text of the last RL_ERR_HIP on this thread */
 int runlora_version(void);

@@ -31,7 +31,7 @@ EXPORTS = (
     "runlora_forward", "runlora_backward", "runlora_select", "runlora_select_by", "runlora_flops",
     "runlora_model_time_us", "runlora_workspace_bytes", "runlora_strerror", "runlora_last_hip_error",
     "runlora_version", "runlora_gemm", "runlora_gemm_workspace_bytes",
-    "runlora_profile_enable", "runlora_profile_collect", "runlora_profile_disable",
+    "runlora_profile_enable", "runlora_profile_collect", "runlora_profile_disable", "runlora_probe_mfma",
 )
 
 
@@ -117,6 +117,8 @@ def lib():
     L.runlora_profile_enable.restype = ci
     L.runlora_profile_collect.argtypes = [ctypes.POINTER(rl_step_time_t), ci]
     L.runlora_profile_collect.restype = ci
+    L.runlora_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ci, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double)]
+    L.runlora_probe_mfma.restype = ci
     L.runlora_profile_disable.argtypes = []
     L.runlora_profile_disable.restype = ci
     _lib = L
@@ -245,6 +247,16 @@ def runlora_profile_collect(cap=4096):
 
 def runlora_profile_disable():
     _check(lib().runlora_profile_disable())
+
+
+def runlora_probe_mfma(random_data, device="cuda"):
+    """Sustained bf16 MFMA TFLOP/s of this GPU on zeros (False) or random operands (True)."""
+    import torch
+    scratch = torch.empty(1 << 20, dtype=torch.uint8, device=device)
+    out = ctypes.c_double(0.0)
+    _check(lib().runlora_probe_mfma(scratch.data_ptr(), scratch.numel(), int(bool(random_data)),
+                                    torch.cuda.current_stream().cuda_stream, ctypes.byref(out)))
+    return out.value
 
 
 # ---- conveniences on top of the ABI (device memory only) --------------------------------------

@@ -5,7 +5,8 @@ csrc/model_constants.hpp (then rebuild the library):
 
 Everything is timed through the library's own C ABI (runlora_gemm), the way a caller sees it: HIP
 events around a batch of calls on one stream, rotating operand sets so that the 256 MB Infinity
-Cache does not serve them.  Per tile shape and operand layout two contraction lengths give the
+Cache does not serve them, on problems long enough that the GPU and not the caller's launch rate
+sets the time.  Per tile shape and operand layout two contraction lengths give the
 time per K tile and the fixed cost of a round of workgroups; a third run with an addend gives the
 fixed cost with D; short second segments give the pipelined kernel's slow-tile cost; the streaming
 kernel is timed on both orientations of the big operand; a tiny problem gives the launch cost.
@@ -59,8 +60,21 @@ def main():
     rl.lib()
     bf, f32 = torch.bfloat16, torch.float32
 
-    # launch cost: a one-tile problem
-    launch = min(gemm_time(bf, "NN", 128, 128, 64, 1) for _ in range(3))
+    # cost of a launch on the GPU's side (dispatch + a kernel that does next to nothing): HIP events
+    # recorded by the library around each step of a tiny layer
+    n, i, o, r = 64, 64, 64, 8
+    X, W = torch.randn(n, i, device="cuda").to(bf), torch.randn(i, o, device="cuda").to(bf)
+    A, B = torch.randn(i, r, device="cuda").to(bf), torch.randn(r, o, device="cuda").to(bf)
+    Y, T = torch.empty(n, o, device="cuda", dtype=bf), torch.empty(n, r, device="cuda", dtype=bf)
+    ws = rl.new_workspace(0, 0, n, i, o, r, rl.RL_BF16)
+    rl.runlora_profile_enable(4096)
+    for _ in range(50):
+        rl.runlora_forward(0, X, W, A, B, Y, rl.new_saved(T), workspace=ws)
+    torch.cuda.synchronize()
+    recs = rl.runlora_profile_collect(4096)
+    rl.runlora_profile_disable()
+    us = sorted(rec["us"] for rec in recs[30:])
+    launch = us[len(us) // 2]
     print("launch_us", round(launch, 2), flush=True)
 
     tiles = {0: {}, 1: {}}
@@ -81,9 +95,9 @@ def main():
                 t_short = gemm_time(dt, layout, M, N, k_short, cfg)
                 per_tile = (t_long - t_short) / 2.0 / ((k_long - k_short) / bk)
                 tk.append(max(per_tile, 1e-3))
-                fix.append(max((t_short - launch) / 2.0 - (k_short / bk) * per_tile, 0.5))
+                fix.append(max(t_short / 2.0 - (k_short / bk) * per_tile, 0.5))
             t_d = gemm_time(dt, "NN", M, N, k_short, cfg, addend=True)
-            fix_d = max((t_d - launch) / 2.0 - (k_short / bk) * tk[0], fix[0])
+            fix_d = max(t_d / 2.0 - (k_short / bk) * tk[0], fix[0])
             tiles[fam][cfg] = dict(tk=tk, fix=sum(fix) / 3.0, fix_d=fix_d)
             print(fam, NAMES[cfg], [round(v, 3) for v in tk], round(tiles[fam][cfg]["fix"], 2), round(fix_d, 2), flush=True)
 
@@ -98,19 +112,20 @@ def main():
         return gemm_time(bf, layout, M, 32, K, 8, sets=sets)
     rates, fixes = [], []
     # both sizes rotate over > 512 MB of operands, beyond the 256 MB Infinity Cache
-    for layout, (Mb, Kb), (Ms, Ks) in (("NN", (8192, 8192), (8192, 2048)), ("TN", (8192, 8192), (8192, 2048))):
-        tb, ts = stream(layout, Mb, Kb, 5), stream(layout, Ms, Ks, 18)
+    # (and both run long enough that the GPU, not the caller's launch rate, sets the time)
+    for layout, (Mb, Kb), (Ms, Ks) in (("NN", (16384, 8192), (8192, 8192)), ("TN", (8192, 16384), (8192, 8192))):
+        tb, ts = stream(layout, Mb, Kb, 3), stream(layout, Ms, Ks, 5)
         bytes_b, bytes_s = 2.0 * Mb * Kb, 2.0 * Ms * Ks
         rate = (bytes_b - bytes_s) / (tb - ts) / 1e6          # TB/s
         rates.append(rate)
-        fixes.append(max(ts - launch - bytes_s / rate / 1e6, 0.0))
+        fixes.append(max(ts - bytes_s / rate / 1e6, 0.0))
     print("stream_tbps", [round(v, 2) for v in rates], "fix", [round(v, 2) for v in fixes], flush=True)
 
-    # reduce stage: forced 4-way split of a streaming problem vs no split
-    t1 = gemm_time(bf, "NN", 8192, 128, 4096, 8, splits=1)
-    t4 = gemm_time(bf, "NN", 8192, 128, 4096, 8, splits=4)
-    extra = max(t4 - t1 - launch, 1.0)
-    reduce_tbps = 4.0 * 8192 * 128 * 5 / extra / 1e6
+    # second stage of a split contraction: a half-filling 256x256 grid split in two vs its one-round model
+    t2 = gemm_time(bf, "NT", 4096, 2048, 8192, 7, splits=2)
+    model_round = 64 * tiles[0][7]["tk"][1] + tiles[0][7]["fix"]
+    extra = max(t2 - model_round, 2.0)
+    reduce_tbps = 4096.0 * 2048 * (4 * 3 + 2) / extra / 1e6
     print("reduce_tbps", round(reduce_tbps, 2), flush=True)
 
     def row(t):

@@ -75,6 +75,79 @@ template <> __device__ __forceinline__ float from_f32<float>(float v) { return v
 template <> __device__ __forceinline__ __bf16 from_f32<__bf16>(float v) { return (__bf16)v; }
 template <> __device__ __forceinline__ _Float16 from_f32<_Float16>(float v) { return (_Float16)v; }
 
+// ---- epilogue of one 32x32 accumulator block ------------------------------------------------------
+// With the MFMA operands swapped, lane l holds row m = l%32 and, for q = 0..3, the four consecutive
+// columns 8q + 4(l/32) + {0..3}.  For 16-bit outputs the two half-waves exchange their halves of
+// column groups (q, q+1) (v_permlane32_swap): lanes 0-31 then own columns 8q..8q+7 and lanes 32-63
+// columns 8(q+1)..8(q+1)+7 of their row, so each lane stores 16 bytes and the pair (l, l+32)
+// fills a 32-byte sector per store instead of half of one.
+struct Epilogue {
+  void* C;
+  int64_t ldc;
+  const void* D;
+  int64_t ldd;
+  float* partial;  // [splits][M][N] or nullptr
+  int M, N, split;
+};
+
+template <typename T>
+__device__ __forceinline__ void store_block(const Epilogue& ep, const f32x16& acc, int m, int nbase, int lane) {
+  if (m >= ep.M) return;
+  const int h = lane >> 5;
+  if (ep.partial) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n = nbase + 8 * q + 4 * h;
+      if (n >= ep.N) continue;
+      f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      *reinterpret_cast<f32x4*>(ep.partial + ((int64_t)ep.split * ep.M + m) * ep.N + n) = v;
+    }
+    return;
+  }
+  if constexpr (sizeof(T) == 4) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n = nbase + 8 * q + 4 * h;
+      if (n >= ep.N) continue;
+      f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      if (ep.D) v += *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.D) + (int64_t)m * ep.ldd + n);
+      *reinterpret_cast<f32x4*>(static_cast<float*>(ep.C) + (int64_t)m * ep.ldc + n) = v;
+    }
+  } else {
+#pragma unroll
+    for (int qp = 0; qp < 2; ++qp) {  // column groups (2qp, 2qp+1)
+      unsigned pa[2], pb[2];          // packed 16-bit pairs of group 2qp and 2qp+1
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const int q = 2 * qp + w;
+        f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        if (ep.D) {
+          const int n = nbase + 8 * q + 4 * h;
+          if (n < ep.N) {
+            T d4[4];
+            *reinterpret_cast<i32x2*>(d4) =
+                *reinterpret_cast<const i32x2*>(static_cast<const T*>(ep.D) + (int64_t)m * ep.ldd + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
+          }
+        }
+        T o4[4] = {from_f32<T>(v[0]), from_f32<T>(v[1]), from_f32<T>(v[2]), from_f32<T>(v[3])};
+        unsigned* dst = w == 0 ? pa : pb;
+        dst[0] = reinterpret_cast<unsigned*>(o4)[0];
+        dst[1] = reinterpret_cast<unsigned*>(o4)[1];
+      }
+      // after the swap: lanes 0-31 hold (pa of h=0, pa of h=1), lanes 32-63 hold (pb of h=0, pb of h=1)
+      auto s0 = __builtin_amdgcn_permlane32_swap(pa[0], pb[0], false, false);
+      auto s1 = __builtin_amdgcn_permlane32_swap(pa[1], pb[1], false, false);
+      const int n = nbase + 8 * (2 * qp + h);
+      if (n < ep.N) {  // N is a multiple of 8 for 16-bit types: the 8 columns are valid together
+        i32x4 out = {(int)s0[0], (int)s1[0], (int)s0[1], (int)s1[1]};
+        *reinterpret_cast<i32x4*>(static_cast<T*>(ep.C) + (int64_t)m * ep.ldc + n) = out;
+      }
+    }
+  }
+}
+
 // LDS row length (elements) for a tile whose rows hold `cols` elements.
 //  K-contiguous tile: +16 bytes, so 16 consecutive rows read by 16-byte loads hit distinct banks.
 //  K-strided tile   : row stride = 64 bytes mod 128 (16-bit, transposing loads) / +8 floats (fp32).
@@ -268,46 +341,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
     stage ^= 1;
   }
 
-  // ---- epilogue.  With the operands swapped, lane l of a 32x32 block holds row m = l%32 and the
-  // four consecutive columns n = 8*(v/4) + 4*(l/32) + (v%4): one 8- or 16-byte store per group.
-  const int mrow = lane & 31, nsub = 4 * (lane >> 5);
+  // ---- epilogue
+  Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, (int)blockIdx.y};
 #pragma unroll
-  for (int a = 0; a < G::TM; ++a) {
-    const int m = m0 + wm * G::WTM + a * 32 + mrow;
-    if (m >= g.M) continue;
+  for (int a = 0; a < G::TM; ++a)
 #pragma unroll
-    for (int b = 0; b < G::TN; ++b) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn * G::WTN + b * 32 + 8 * q + nsub;
-        if (n >= g.N) continue;  // N is a multiple of 4, so n..n+3 are valid together
-        f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
-        if (g.partial) {
-          float* p = g.partial + ((int64_t)blockIdx.y * g.M + m) * g.N + n;
-          *reinterpret_cast<f32x4*>(p) = v;
-        } else {
-          if (g.D) {
-            const T* d = static_cast<const T*>(g.D) + (int64_t)m * g.ldd + n;
-            if constexpr (sizeof(T) == 4) {
-              v += *reinterpret_cast<const f32x4*>(d);
-            } else {
-              T d4[4];
-              *reinterpret_cast<i32x2*>(d4) = *reinterpret_cast<const i32x2*>(d);  // one 8-byte load
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
-            }
-          }
-          T* c = static_cast<T*>(g.C) + (int64_t)m * g.ldc + n;
-          if constexpr (sizeof(T) == 4) {
-            *reinterpret_cast<f32x4*>(c) = v;
-          } else {
-            T o4[4] = {from_f32<T>(v[0]), from_f32<T>(v[1]), from_f32<T>(v[2]), from_f32<T>(v[3])};
-            *reinterpret_cast<i32x2*>(c) = *reinterpret_cast<i32x2*>(o4);
-          }
-        }
-      }
-    }
-  }
+    for (int b = 0; b < G::TN; ++b)
+      store_block<T>(ep, acc[a][b], m0 + wm * G::WTM + a * 32 + (lane & 31), n0 + wn * G::WTN + b * 32, lane);
 }
 
 // Sum the split-K partials in slice order and round once: C = sum_z partial[z] (+ D).

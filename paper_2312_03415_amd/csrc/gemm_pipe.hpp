@@ -302,41 +302,13 @@ __global__ __launch_bounds__(WM* WN * 64, MIN_WG) void gemm_pipe_kernel(GemmArgs
 #undef RL_FENCE
   }
 
-  // ---- epilogue (as gemm_kernel: lane holds row m = l%32, columns 8*q + 4*(l/32) .. +3)
-  const int mrow = lane & 31, nsub = 4 * (lane >> 5);
+  // ---- epilogue
+  Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, (int)blockIdx.y};
 #pragma unroll
-  for (int a = 0; a < P::TM; ++a) {
-    const int m = m0 + wm * P::WTM + a * 32 + mrow;
-    if (m >= g.M) continue;
+  for (int a = 0; a < P::TM; ++a)
 #pragma unroll
-    for (int b = 0; b < P::TN; ++b) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn * P::WTN + b * 32 + 8 * q + nsub;
-        if (n >= g.N) continue;
-        f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
-        if (g.partial) {
-          float* p = g.partial + ((int64_t)blockIdx.y * g.M + m) * g.N + n;
-          *reinterpret_cast<f32x4*>(p) = v;
-        } else {
-          if (g.D) {
-            const T* d = static_cast<const T*>(g.D) + (int64_t)m * g.ldd + n;
-            if constexpr (sizeof(T) == 4) {
-              v += *reinterpret_cast<const f32x4*>(d);
-            } else {
-              T d4[4];
-              *reinterpret_cast<i32x2*>(d4) = *reinterpret_cast<const i32x2*>(d);  // one 8-byte load
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
-            }
-          }
-          T* c = static_cast<T*>(g.C) + (int64_t)m * g.ldc + n;
-          T o4[4] = {from_f32<T>(v[0]), from_f32<T>(v[1]), from_f32<T>(v[2]), from_f32<T>(v[3])};
-          *reinterpret_cast<i32x2*>(c) = *reinterpret_cast<i32x2*>(o4);
-        }
-      }
-    }
-  }
+    for (int b = 0; b < P::TN; ++b)
+      store_block<T>(ep, acc[a][b], m0 + wm * P::WTM + a * 32 + (lane & 31), n0 + wn * P::WTN + b * 32, lane);
   }  // persistent tile loop
 }
 

@@ -54,7 +54,7 @@ static double step_time_us(const Step& s) {
       us += bytes / (mc.stream_tbps[k.a_strided ? 1 : 0] * 1e12) * 1e6;
       outs += (double)k.M * k.N;
     }
-    if (s.skplan.splits > 1) us += 4.0 * outs * (s.skplan.splits + 1) / (mc.reduce_tbps * 1e12) * 1e6 + mc.launch_us;
+    if (s.skplan.splits > 1) us += 4.0 * outs * (s.skplan.splits + 1) / (mc.reduce_tbps * 1e12) * 1e6 + mc.stream_fix_us + mc.launch_us;
     return us;
   }
   const GemmDesc& d = s.d;
@@ -64,14 +64,21 @@ static double step_time_us(const Step& s) {
   const double wgs = (double)p.nbm * p.nbn * p.splits;
   const double slots = 256.0 * tm.wg_per_cu;
   double rounds = wgs / slots;
-  rounds = rounds <= 1.0 ? 1.0 : (double)(int64_t)(rounds + 0.999);
+  // a grid that does not fill the resident slots leaves each workgroup more of its compute unit
+  double share = 1.0;
+  if (rounds < 1.0) {
+    share = rounds > 1.0 / tm.wg_per_cu ? rounds : 1.0 / tm.wg_per_cu;
+    rounds = 1.0;
+  } else {
+    rounds = (double)(int64_t)(rounds + 0.999);
+  }
   const int64_t kt0 = (d.K[0] + p.bk - 1) / p.bk, kt1 = d.nseg > 1 ? (d.K[1] + p.bk - 1) / p.bk : 0;
   double ktiles = (double)(kt0 + kt1);
   if (p.splits > 1) ktiles = (double)p.tiles_per_split;
   double slow = 0;
   if (p.cfg == CFG_P256x256 || p.cfg == CFG_P256x128) slow = (double)(kt1 + (d.K[0] % p.bk ? 1 : 0));
   const bool addend = d.D != nullptr && p.splits == 1;
-  double us = rounds * (ktiles * tm.tk_us[lay] + (addend ? tm.tfix_d_us : tm.tfix_us) + slow * mc.slow_tile_us) +
+  double us = rounds * (ktiles * tm.tk_us[lay] * share + (addend ? tm.tfix_d_us : tm.tfix_us) + slow * mc.slow_tile_us) +
               mc.launch_us;
   if (p.splits > 1)
     us += (double)d.M * d.N * (4.0 * (p.splits + 1) + (d.D ? e : 0.0) + e) / (mc.reduce_tbps * 1e12) * 1e6 + mc.launch_us;
