@@ -43,6 +43,7 @@ struct GemmArgs {
   int M, N;
   int tiles_per_split;  // K tiles per gridDim.y slice
   int nbm, nbn;         // tile grid
+  int splits;           // number of K slices (gemm_mc_kernel: folded into blockIdx.x)
 };
 
 // ---- per-type pieces --------------------------------------------------------------------------

@@ -1,0 +1,435 @@
+// Matrix-core kernel for the large contractions of the LoRA layer (X W, dY W^T, X^T dY and their
+// K-concatenated forms [X|T][W;B], [dY|Z1][W^T;A^T]; Eq. 1 / Eq. 3 and Algorithms 1-5 of arxiv
+// 2312.03415) in bf16 / fp16 on gfx950.  Same contract as gemm_kernel (gemm_engine.hpp).
+//
+// Shape of the kernel
+//  - 256x256 output tile per workgroup, 4 wavefronts (one per SIMD), each owning a 128x128 sub-tile:
+//    16 accumulator blocks of 32x32 = 256 accumulator registers, which leaves the other half of
+//    the 512-entry register file for double-buffered operand fragments.  A K step (16) is
+//    16 MFMAs fed by 8 LDS reads of 16 bytes: half the LDS traffic per MFMA of a 128x64 sub-tile.
+//  - K tile = 32.  LDS is a ring of NS (4) stages of 32 KB (A 256x32 + B 256x32); global memory
+//    goes straight to LDS (16-byte LDS-DMA loads, no register staging).  Three K tiles are in
+//    flight while one is multiplied, so a load has ~3000 MFMA cycles to land.
+//  - The load stream is continuous over everything a persistent workgroup does: when the K tiles
+//    of one output tile are exhausted it goes on with the next output tile, so the first tiles of
+//    the next output tile arrive while the current one is being stored.
+//  - One s_barrier per K tile, placed among the MFMAs of the tile's second K step.  It orders
+//    "everyone has read stage s" before "stage s is refilled" and "my loads of tile t+1 have
+//    landed" (s_waitcnt vmcnt(8(NS-2)), loads return in order) before "anyone reads tile t+1".
+//  - A partial K tile (K % 32 != 0, e.g. the rank-r segment with r = 8 or 16) takes the same route:
+//    its out-of-range 16-byte chunks are fetched from an in-range address of the same row and the
+//    fragment registers that hold k >= K are zeroed on both operands after the LDS read.
+//  - LDS-DMA writes lane l's 16 bytes at base + 16 l, so rows cannot be padded; bank conflicts are
+//    avoided by an XOR swizzle applied on the global-address side:
+//      K-contiguous tile [256 rows][4 chunks]     : chunk c of row q sits in slot c ^ ((q >> 2) & 3)
+//      K-strided tile    [32 k-rows][32 chunks]   : chunk c of k-row q sits in slot c ^ (4 (q & 3))
+#pragma once
+#include <type_traits>
+
+#include "gemm_engine.hpp"
+
+namespace rl {
+
+typedef __attribute__((address_space(3))) void mc_lds_void_t;
+typedef __attribute__((address_space(1))) const void mc_global_cvoid_t;
+
+template <int AL, int BL, int NS_>
+struct McTile {
+  static constexpr int BM = 256, BN = 256, BK = 32, NS = NS_;
+  static constexpr int NW = 4, NT = NW * 64;
+  static constexpr int WTM = 128, WTN = 128, TM = 4, TN = 4;
+  static constexpr bool A_STR = (AL == 1), B_STR = (BL == 0);
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = NS * STAGE_BYTES;
+  static constexpr int IPW = (A_BYTES / 1024) / NW;  // 1 KB LDS-DMA instructions per wave per operand tile (4)
+  static constexpr int LPT = 2 * IPW;                // loads per K tile per wave
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+
+// s_waitcnt immediate: at most `vm` vector-memory operations outstanding; lgkm_zero = also wait for
+// every LDS / scalar-memory operation; the export counter is left alone
+constexpr int mc_wait_imm(int vm, bool lgkm_zero) {
+  return (vm & 15) | (7 << 4) | ((lgkm_zero ? 0 : 15) << 8) | ((vm >> 4) << 14);
+}
+
+// The kernel body is a device function (the buffer-descriptor builtins exist only in device code).
+template <typename T, int AL, int BL, int NS>
+__device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
+  using P = McTile<AL, BL, NS>;
+  constexpr int BM = P::BM, BN = P::BN, BK = P::BK, IPW = P::IPW;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  unsigned char* smem = smem_raw;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l31 = lane & 31, hi = lane >> 5, s16 = lane & 15;
+
+  // K tiles of one output tile: segment 0 then segment 1; the last tile of a segment may be partial
+  const int nt0 = (g.K[0] + BK - 1) / BK, nt1 = (g.K[1] + BK - 1) / BK;
+  const int ntk = nt0 + nt1;
+  const int total = g.nbm * g.nbn;
+  const int nwork = total * g.splits;  // work item w = split * total + tile sequence number
+
+  // tile sequence number -> (m0, n0).  Consecutive workgroups sit on different XCDs (8, each with its
+  // own L2): renumber so that each XCD works on a contiguous run of tiles, then walk the tile grid in
+  // bands of 8 tile rows (a run shares A rows and B columns in its L2).
+  auto tile_origin = [&](int seq, int& m0, int& n0) {
+    int id;
+    {
+      const int x = seq & 7, slot = seq >> 3, q = total >> 3, rem = total & 7;
+      id = x * q + (x < rem ? x : rem) + slot;
+    }
+    constexpr int BAND = 8;
+    const int per_band = BAND * g.nbn;
+    const int band = id / per_band, first_m = band * BAND;
+    const int band_rows = (g.nbm - first_m) < BAND ? (g.nbm - first_m) : BAND;
+    const int in_band = id - band * per_band;
+    m0 = (first_m + in_band % band_rows) * BM;
+    n0 = (in_band / band_rows) * BN;
+  };
+  auto split_range = [&](int w, int& tile_seq, int& split, int& u0, int& u1) {
+    split = w / total;
+    tile_seq = w - split * total;
+    u0 = split * g.tiles_per_split;
+    u1 = u0 + g.tiles_per_split;
+    if (u1 > ntk) u1 = ntk;
+  };
+
+  // ---- load cursor: which K tile of which work item the next LDS-DMA batch fetches -----------------
+  // Everything the fetch itself needs is kept ready in registers (two uniform pointers to the tile's
+  // k origin and one per-lane offset per instruction), so that the eight loads are straight-line code
+  // that the scheduler can spread between the MFMAs.  Moving on to the next tile is a pointer bump,
+  // except at an "event" (partial tile, segment switch, next work item), where the state is rebuilt.
+  const int K0 = g.K[0], K1 = g.K[1];
+  const T* const segA0 = static_cast<const T*>(g.A[0]);
+  const T* const segA1 = static_cast<const T*>(g.A[1]);
+  const T* const segB0 = static_cast<const T*>(g.B[0]);
+  const T* const segB1 = static_cast<const T*>(g.B[1]);
+  const uint32_t lda0 = (uint32_t)g.lda[0], lda1 = (uint32_t)g.lda[1];
+  const uint32_t ldb0 = (uint32_t)g.ldb[0], ldb1 = (uint32_t)g.ldb[1];
+  int cw = blockIdx.x, cu = 0, cu_end = 0, cm0 = 0, cn0 = 0, cnext = 0;
+  bool clive = true;
+  // Loads go through buffer descriptors: a uniform descriptor per operand and segment, a uniform
+  // byte offset for the K tile (scalar register) and one 32-bit per-lane byte offset per instruction.
+  auto extent_bytes = [&](bool strided, int rows_or_cols, int K, uint32_t ld) -> uint32_t {
+    // [rows, K] with K contiguous, or [K, cols] strided; 0 for an absent segment
+    if (K <= 0) return 0u;
+    const uint64_t e = strided ? ((uint64_t)(K - 1) * ld + (uint64_t)rows_or_cols) : ((uint64_t)(rows_or_cols - 1) * ld + (uint64_t)K);
+    return (uint32_t)(e * 2u);
+  };
+  const __amdgpu_buffer_rsrc_t rsA0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(segA0), 0, extent_bytes(P::A_STR, g.M, K0, lda0), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsA1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(segA1), 0, extent_bytes(P::A_STR, g.M, K1, lda1), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsB0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(segB0), 0, extent_bytes(P::B_STR, g.N, K0, ldb0), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsB1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(segB1), 0, extent_bytes(P::B_STR, g.N, K1, ldb1), 0x00020000);
+  __amdgpu_buffer_rsrc_t rsA = rsA0, rsB = rsB0;  // descriptors of the cursor's segment
+  uint32_t kA = 0, kB = 0;            // byte offset of the cursor's tile (k origin) in its segment (uniform)
+  uint32_t stepA = 0, stepB = 0;      // bytes from one K tile to the next in the current segment
+  uint32_t offA[IPW], offB[IPW];      // per-lane byte offsets, one per instruction
+
+  // Rebuild the state for tile cu of work item cw (tile origin cm0, cn0).  Rows / columns beyond the
+  // matrix are clamped: they only feed outputs that are never stored.  In a partial tile the chunks
+  // with k >= kvalid are fetched from k = 0 of the same row / column (in range); the multiply
+  // zeroes them.
+  auto cursor_setup = [&]() {
+    const int seg = cu < nt0 ? 0 : 1;
+    const int ts = cu - (seg ? nt0 : 0);
+    const int kvalid = (seg ? K1 : K0) - ts * BK;
+    const uint32_t lda = seg ? lda1 : lda0, ldb = seg ? ldb1 : ldb0;
+    stepA = 2u * (P::A_STR ? (uint32_t)BK * lda : (uint32_t)BK);
+    stepB = 2u * (P::B_STR ? (uint32_t)BK * ldb : (uint32_t)BK);
+    rsA = seg ? rsA1 : rsA0;
+    rsB = seg ? rsB1 : rsB0;
+    kA = (uint32_t)ts * stepA;
+    kB = (uint32_t)ts * stepB;
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+      const int p = (wave * IPW + j) * 64 + lane;
+      {
+        const int row = P::A_STR ? (p >> 5) : (p >> 2);
+        const int col = P::A_STR ? (((p & 31) ^ (4 * (row & 3))) << 3) : (((p & 3) ^ ((row >> 2) & 3)) << 3);
+        if constexpr (!P::A_STR) {
+          int gr = cm0 + row; gr = gr < g.M ? gr : g.M - 1;
+          offA[j] = 2u * ((uint32_t)gr * lda + (uint32_t)(col < kvalid ? col : 0));
+        } else {
+          int gc = cm0 + col; gc = gc < g.M ? gc : g.M - 8;
+          offA[j] = 2u * ((uint32_t)(row < kvalid ? row : 0) * lda + (uint32_t)gc);
+        }
+      }
+      {
+        const int row = P::B_STR ? (p >> 5) : (p >> 2);
+        const int col = P::B_STR ? (((p & 31) ^ (4 * (row & 3))) << 3) : (((p & 3) ^ ((row >> 2) & 3)) << 3);
+        if constexpr (!P::B_STR) {
+          int gr = cn0 + row; gr = gr < g.N ? gr : g.N - 1;
+          offB[j] = 2u * ((uint32_t)gr * ldb + (uint32_t)(col < kvalid ? col : 0));
+        } else {
+          int gc = cn0 + col; gc = gc < g.N ? gc : g.N - 8;
+          offB[j] = 2u * ((uint32_t)(row < kvalid ? row : 0) * ldb + (uint32_t)gc);
+        }
+      }
+    }
+    // the next tile index at which the state must be rebuilt again
+    if (kvalid < BK) {
+      cnext = cu + 1;  // offsets of a partial tile are its own
+    } else {
+      cnext = cu_end;
+      if (cu < nt0 && nt0 < cnext) cnext = nt0;                                 // segment switch
+      if ((K0 % BK) != 0 && cu < nt0 - 1 && nt0 - 1 < cnext) cnext = nt0 - 1;  // partial tail of segment 0
+      if ((K1 % BK) != 0 && ntk - 1 < cnext) cnext = ntk - 1;                  // partial tail of segment 1
+    }
+  };
+  auto cursor_open = [&]() {  // start loading work item cw
+    int seq, split;
+    split_range(cw, seq, split, cu, cu_end);
+    tile_origin(seq, cm0, cn0);
+    cursor_setup();
+  };
+  cursor_open();
+
+  // Fetch the A half / the B half of the cursor's K tile into LDS stage `st`: four loads each, no
+  // branches.  The two halves are issued in different K steps so that the loads are spread evenly
+  // over the MFMAs (a burst of loads from all four waves backs up the address unit and stalls issue).
+  auto issue_A1 = [&](int st, int j) {
+    unsigned char* sA = smem + st * P::STAGE_BYTES;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)(sA + (wave * IPW + j) * 1024), 16, offA[j], kA, 0, 0);
+  };
+  auto issue_B1 = [&](int st, int j) {
+    unsigned char* sB = smem + st * P::STAGE_BYTES + P::A_BYTES;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)(sB + (wave * IPW + j) * 1024), 16, offB[j], kB, 0, 0);
+  };
+  auto issue_A = [&](int st) {
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) issue_A1(st, j);
+  };
+  auto issue_B = [&](int st) {
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) issue_B1(st, j);
+  };
+  // Move the cursor on.  Past the last work item it stays on the last tile, which is then fetched
+  // again (into a stage nobody reads), so that the number of loads in flight, which the waits below
+  // count, never changes.
+  auto cursor_advance = [&]() {
+    if (!clive) return;
+    ++cu;
+    if (cu != cnext) {
+      kA += stepA;
+      kB += stepB;
+      return;
+    }
+    if (cu == cu_end) {
+      if (cw + (int)gridDim.x < nwork) {
+        cw += gridDim.x;
+        cursor_open();
+      } else {
+        clive = false;
+        --cu;
+      }
+      return;
+    }
+    cursor_setup();
+  };
+
+  // ---- fragment addresses (bytes inside a stage, stage 0) -------------------------------------------
+  // K-contiguous tile: row q, the 16 bytes at k = 16 ks + 8 hi live in slot (2 ks + hi) ^ ((q >> 2) & 3)
+  // K-strided tile: transposing 8-byte LDS load; within a 16-lane group lane s points at k-row
+  // 16 ks + 8 hi + s/4 (+4 for the second load), columns c0 + 4 (s%4) .. +3, and receives column c0 + s
+  // for four consecutive k.  Block b of the wave's 128 columns: chunk slot (16 w + 4 b + ...) ^ 4 (s/4).
+  uint32_t fragA[4], fragB[4];
+  {
+    const int sw = (l31 >> 2) & 3;
+    if constexpr (!P::A_STR) {
+      const uint32_t rowb = (uint32_t)(wm * 128 + l31) * 64u;
+      fragA[0] = rowb + (uint32_t)((hi ^ sw) << 4);
+      fragA[1] = rowb + (uint32_t)(((2 + hi) ^ sw) << 4);
+      fragA[2] = fragA[3] = 0;
+    } else {
+      const int k = s16 >> 2;
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        fragA[b] = (uint32_t)((8 * hi + k) * 512 + (wm * 16 + ((b ^ k) << 2) + 2 * ((lane >> 4) & 1) + ((s16 & 3) >> 1)) * 16 +
+                              ((4 * (s16 & 3)) & 7) * 2);
+    }
+    if constexpr (!P::B_STR) {
+      const uint32_t rowb = (uint32_t)(wn * 128 + l31) * 64u;
+      fragB[0] = P::A_BYTES + rowb + (uint32_t)((hi ^ sw) << 4);
+      fragB[1] = P::A_BYTES + rowb + (uint32_t)(((2 + hi) ^ sw) << 4);
+      fragB[2] = fragB[3] = 0;
+    } else {
+      const int k = s16 >> 2;
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        fragB[b] = P::A_BYTES +
+                   (uint32_t)((8 * hi + k) * 512 + (wn * 16 + ((b ^ k) << 2) + 2 * ((lane >> 4) & 1) + ((s16 & 3) >> 1)) * 16 +
+                              ((4 * (s16 & 3)) & 7) * 2);
+    }
+  }
+  // LDS byte address of the ring (dynamic LDS need not start at 0)
+  const uint32_t lds_base = (uint32_t)(uintptr_t)((mc_lds_void_t*)smem);
+
+  i32x4 fa[2][4], fb[2][4];
+  // One 32-wide operand fragment of K step KSR from the stage at byte offset `soff`.
+  //  K-contiguous operand: one 16-byte LDS load.
+  //  K-strided operand: two transposing 8-byte LDS loads, issued through inline assembly: the
+  //  compiler makes every LDS read it knows about wait for all outstanding LDS-DMA loads
+  //  (s_waitcnt vmcnt(0)), which would serialise the ring; reads it cannot see are waited for by
+  //  hand (wait_tr below).
+  auto read_frag_op = [&](bool strided, const uint32_t (&fr)[4], uint32_t soff, int blk, auto ksr_c) -> i32x4 {
+    constexpr int KSR = decltype(ksr_c)::value;
+    if (!strided) {
+      return *reinterpret_cast<const i32x4*>(smem + soff + fr[KSR] + blk * 2048);
+    } else {
+      const uint32_t addr = lds_base + soff + fr[blk];
+      i32x2 lo, hi2;
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "i"(KSR * 8192));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi2) : "v"(addr), "i"(KSR * 8192 + 2048));
+      i32x4 out = {lo[0], lo[1], hi2[0], hi2[1]};
+      return out;
+    }
+  };
+  // everything the hand-issued LDS reads fetched into buffer `buf` has arrived
+  auto wait_tr = [&](int buf) {
+    if constexpr (P::A_STR && P::B_STR)
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(fa[buf][0]), "+v"(fa[buf][1]), "+v"(fa[buf][2]), "+v"(fa[buf][3]), "+v"(fb[buf][0]),
+                     "+v"(fb[buf][1]), "+v"(fb[buf][2]), "+v"(fb[buf][3]));
+    else if constexpr (P::A_STR)
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fa[buf][0]), "+v"(fa[buf][1]), "+v"(fa[buf][2]), "+v"(fa[buf][3]));
+    else if constexpr (P::B_STR)
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(fb[buf][0]), "+v"(fb[buf][1]), "+v"(fb[buf][2]), "+v"(fb[buf][3]));
+  };
+  // zero the fragment registers of K step ks that hold k >= kvalid (this lane's 8 k start at 16 ks + 8 hi)
+  auto mask_frags = [&](int buf, int ks, int kvalid) {
+    if (ks * 16 + 8 * hi >= kvalid) {
+#pragma unroll
+      for (int a = 0; a < 4; ++a) fa[buf][a] = i32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int b = 0; b < 4; ++b) fb[buf][b] = i32x4{0, 0, 0, 0};
+    }
+  };
+
+  f32x16 acc[4][4];
+
+#ifndef MC_VMEM_AT
+#define MC_VMEM_AT(q) (((q) & 3) == 3)
+#endif
+#define MC_FENCE() __builtin_amdgcn_sched_barrier(0)
+  // One K step, in exactly this instruction order (a scheduling fence after every piece): 16 MFMAs out
+  // of fragment buffer `bufc`; behind each of the first 8, one fragment of K step KSR of the stage at
+  // `soff` goes to buffer `bufr`; behind every fourth, one of the 4 LDS-DMA loads `issue_one(j)`.
+  // A wave issues at most one instruction per 4 cycles and an MFMA occupies the matrix core for 32, so
+  // up to ~7 other instructions fit behind each MFMA; spreading them keeps the matrix core fed, and
+  // spreading the loads keeps the four waves from flooding the address unit at the same moment.
+  auto kstep = [&](auto ksr_c, int bufc, int bufr, uint32_t soff, auto issue_one) {
+    wait_tr(bufc);
+    MC_FENCE();
+    int j = 0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      Elem<T>::mma(acc[q >> 2][q & 3], fb[bufc][q & 3], fa[bufc][q >> 2]);
+      MC_FENCE();
+      if (q < 4) {
+        fa[bufr][q] = read_frag_op(P::A_STR, fragA, soff, q, ksr_c);
+        MC_FENCE();
+      } else if (q < 8) {
+        fb[bufr][q - 4] = read_frag_op(P::B_STR, fragB, soff, q - 4, ksr_c);
+        MC_FENCE();
+      }
+      if (MC_VMEM_AT(q)) {
+        issue_one(j++);
+        MC_FENCE();
+      }
+    }
+  };
+  // all of this wave's LDS reads are complete and at most `vm` of its loads are in flight; then
+  // the workgroup barrier.  The empty asm statements keep the compiler from moving memory
+  // accesses across it.
+#define MC_SYNC(vm)                                                         \
+  do {                                                                      \
+    MC_FENCE();                                                             \
+    asm volatile("" ::: "memory");                                          \
+    __builtin_amdgcn_s_waitcnt(mc_wait_imm((vm), true));                    \
+    __builtin_amdgcn_s_barrier();                                           \
+    asm volatile("" ::: "memory");                                          \
+    MC_FENCE();                                                             \
+  } while (0)
+
+  // ---- prologue: fill the ring (the last tile only by its A half: the loop issues B halves in K
+  // step 0 and A halves in K step 1), wait for the first tile
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s) {
+    issue_A(s);
+    issue_B(s);
+    cursor_advance();
+  }
+  issue_A(NS - 1);
+  MC_SYNC((NS - 2) * P::LPT + IPW);
+  {
+    using K0c = std::integral_constant<int, 0>;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) fa[0][a] = read_frag_op(P::A_STR, fragA, 0u, a, K0c{});
+#pragma unroll
+    for (int b = 0; b < 4; ++b) fb[0][b] = read_frag_op(P::B_STR, fragB, 0u, b, K0c{});
+  }
+  int stp = NS - 1;  // stage of the previous tile = where the tile being fetched goes
+  int st = 0;  // stage of the tile being multiplied; runs on across work items
+
+  for (int w = blockIdx.x; w < nwork; w += gridDim.x) {
+    int seq, split, u0, u1, m0, n0;
+    split_range(w, seq, split, u0, u1);
+    tile_origin(seq, m0, n0);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    for (int u = u0; u < u1; ++u) {
+      const int kvalid = u < nt0 ? K0 - u * BK : K1 - (u - nt0) * BK;  // >= 32 for a full tile
+      const int stn = (st + 1 == NS) ? 0 : st + 1;
+      if (kvalid < BK) {  // partial tile (wave-uniform): zero what lies beyond K
+        MC_FENCE();
+        wait_tr(0);
+        mask_frags(0, 0, kvalid);
+      }
+      // K step 0 out of buffer 0; K step 1's fragments go to buffer 1; second half of the fetch
+      // that the previous K step began
+      kstep(std::integral_constant<int, 1>{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES), [&](int j) { issue_B1(stp, j); });
+      cursor_advance();
+      // Tile u+1 must have landed (own loads, then everyone's: loads return in order, so "at most
+      // (NS-2) tiles' worth outstanding" means tile u+1 is in), and everyone must be done reading
+      // stage st before it is refilled.
+      MC_SYNC((NS - 2) * P::LPT);
+      if (kvalid < BK) {
+        wait_tr(1);
+        mask_frags(1, 1, kvalid);
+        MC_FENCE();
+      }
+      // K step 1 out of buffer 1, with the next tile's first fragments and the first half of the
+      // refill of stage st
+      kstep(std::integral_constant<int, 0>{}, 1, 0, (uint32_t)(stn * P::STAGE_BYTES), [&](int j) { issue_A1(st, j); });
+      stp = st;
+      st = stn;
+    }
+
+    // ---- epilogue (the next work item's first tiles keep arriving meanwhile)
+    Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split};
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        store_block<T>(ep, acc[a][b], m0 + wm * 128 + a * 32 + l31, n0 + wn * 128 + b * 32, lane);
+  }
+  // the LDS-DMA writes still in flight target this workgroup's LDS: let them land before it is released
+  __builtin_amdgcn_s_waitcnt(mc_wait_imm(0, true));
+#undef MC_SYNC
+#undef MC_FENCE
+}
+
+template <typename T, int AL, int BL, int NS>
+__global__ __launch_bounds__(256, 1) void gemm_mc_kernel(GemmArgs g) {
+  gemm_mc_body<T, AL, BL, NS>(g);
+}
+
+}  // namespace rl
