@@ -24,15 +24,12 @@ import numpy as np
 
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 HBM_PEAK_GBPS = 8000.0
-TILE_NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x128p", "256x256p", "stream32", "stream64", "stream128"]
+TILE_NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x256mc3", "256x256mc", "stream32", "stream64", "stream128"]
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/), scaled by what the same counters read for a copy kernel of known size; None until
 # measured for the workload.
 TRAFFIC_BYTES = {
-    # profiles/bench_opt13b_hbm_traffic.txt: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per launch
-    ("opt13b", "gemm_kernel<bf16,NN,256x256p>"): int((105639 * 2.0 + 84189) * 1024),
-    ("opt13b", "gemm_kernel<bf16,NT,256x256p>"): int((116572 * 2.0 + 86586) * 1024),
 }
 
 

@@ -192,10 +192,11 @@ size_t runlora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o
  *              (a_strided = 1 with b_kcontig = 1 is not provided)
  *   K2 = 0     no second segment.   D = NULL: no addend (D may alias C).
  *   tile_cfg   -1 = library heuristic; 0..5 = 256x256, 128x128, 128x32, 128x64, 32x128, 64x128
- *              output tile per workgroup in the generic engine; 6 / 7 = 256x128x32 (4 wavefronts)
- *              / 256x256x64 (8 wavefronts) in the hand-pipelined kernel (16-bit types; fp32 falls
- *              back to 0); 8 = the streaming kernel for rank-r products (N <= 128, no second
- *              segment, no addend: 4 wavefronts per 32 output rows split the contraction)
+ *              output tile per workgroup in the generic engine; 6 / 7 = the matrix-core kernel for
+ *              the large contractions (256x256 tile, K tile 32, 4 wavefronts, LDS ring of 3 / 4
+ *              stages filled by LDS-DMA loads; 16-bit types, fp32 falls back to 0); 8 = the
+ *              streaming kernel for rank-r products (N <= 128, no second segment, no addend:
+ *              4 wavefronts per 32 output rows split the contraction)
  *   trans_out  1 = store C transposed, as [N,M] with ldc >= M (streaming kernel only); else 0
  *   splits     0 = heuristic, n > 0 = split the contraction n ways (fp32 partials in the
  *              workspace, summed in a fixed order)

@@ -20,10 +20,10 @@ from . import binding as rl
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 TILE_BM = [256, 128, 128, 128, 32, 64, 256, 256]
-TILE_BN = [256, 128, 32, 64, 128, 128, 128, 256]
-TILE_BK16 = [64, 64, 64, 64, 64, 64, 32, 64]
-WG_PER_CU = [1, 2, 3, 2, 3, 3, 2, 1]
-NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x128x32 pipelined", "256x256x64 pipelined"]
+TILE_BN = [256, 128, 32, 64, 128, 128, 256, 256]
+TILE_BK16 = [64, 64, 64, 64, 64, 64, 32, 32]
+WG_PER_CU = [1, 2, 3, 2, 3, 3, 1, 1]
+NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x256x32 matrix-core, 3 stages", "256x256x32 matrix-core, 4 stages"]
 LAYOUTS = {"NN": (0, 0), "NT": (0, 1), "TN": (1, 0)}
 
 

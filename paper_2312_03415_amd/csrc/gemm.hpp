@@ -27,8 +27,8 @@ struct GemmDesc {
 
 enum TileCfg {
   CFG_BIG = 0, CFG_MID, CFG_TALL32, CFG_TALL64, CFG_WIDE32, CFG_WIDE64,
-  CFG_P256x128,  // hand-pipelined LDS-DMA kernel (16-bit types): 256x128x32, 4 waves, 2 workgroups per CU
-  CFG_P256x256,  // same kernel: 256x256x64, 8 waves, 1 workgroup per CU
+  CFG_MC3,  // matrix-core kernel (gemm_mc.hpp, 16-bit types): 256x256x32, 4 waves, 3-stage LDS ring
+  CFG_MC4,  // same kernel, 4-stage ring (the one the heuristics pick)
   CFG_COUNT
 };
 

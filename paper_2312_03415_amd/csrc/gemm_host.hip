@@ -6,8 +6,8 @@
 namespace rl {
 
 static const int kTileBM[CFG_COUNT] = {256, 128, 128, 128, 32, 64, 256, 256};
-static const int kTileBN[CFG_COUNT] = {256, 128, 32, 64, 128, 128, 128, 256};
-static const int kTileBK16[CFG_COUNT] = {64, 64, 64, 64, 64, 64, 32, 64};  // K tile, 16-bit types
+static const int kTileBN[CFG_COUNT] = {256, 128, 32, 64, 128, 128, 256, 256};
+static const int kTileBK16[CFG_COUNT] = {64, 64, 64, 64, 64, 64, 32, 32};  // K tile, 16-bit types
 
 GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg,
                    int force_splits) {
@@ -15,7 +15,7 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   int cfg;
   if (force_cfg >= 0 && force_cfg < CFG_COUNT) {
     cfg = force_cfg;
-    if ((cfg == CFG_P256x128 || cfg == CFG_P256x256) && dtype == DT_F32) cfg = CFG_BIG;  // 16-bit only
+    if ((cfg == CFG_MC3 || cfg == CFG_MC4) && dtype == DT_F32) cfg = CFG_BIG;  // 16-bit only
   } else if (M <= 32) {
     cfg = CFG_WIDE32;
   } else if (M <= 64) {
@@ -30,7 +30,7 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
     const bool pipe_ok = dtype != DT_F32;
     if (big_tiles >= 160 || (big_tiles >= 80 && K0 + K1 >= 2048))
-      cfg = pipe_ok ? CFG_P256x256 : CFG_BIG;
+      cfg = pipe_ok ? CFG_MC4 : CFG_BIG;
     else
       cfg = CFG_MID;
   }
@@ -45,8 +45,8 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   int splits = 1;
   if (force_splits > 0) {
     splits = force_splits;
-  } else if (cfg == CFG_P256x256 || cfg == CFG_BIG) {
-    if (tiles < 160 && ktiles >= 16) splits = (int)((256 + tiles - 1) / tiles);
+  } else if (cfg == CFG_MC3 || cfg == CFG_MC4 || cfg == CFG_BIG) {
+    if (tiles < 160 && ktiles >= 32) splits = (int)((256 + tiles - 1) / tiles);
   } else if (tiles < 256 && ktiles >= 8) {
     // fill the chip (aim at ~512 workgroups) but keep >= 4 K tiles per slice
     int64_t want = (512 + tiles - 1) / tiles;
@@ -68,10 +68,16 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   if (d.M <= 0 || d.N <= 0) return hipErrorInvalidValue;
   if (plan.splits > 1 && scratch == nullptr) return hipErrorInvalidValue;
   int cfg = plan.cfg;
-  if (cfg == CFG_P256x128 || cfg == CFG_P256x256) {
-    // the pipelined kernel addresses segment 0 with 32-bit element offsets
-    const int64_t a_rows = d.a_strided ? d.K[0] : d.M, b_rows = d.b_kcontig ? d.N : d.K[0];
-    if (a_rows * d.lda[0] >= (1LL << 32) || b_rows * d.ldb[0] >= (1LL << 32) || d.dtype == DT_F32) cfg = CFG_BIG;
+  if (cfg == CFG_MC3 || cfg == CFG_MC4) {
+    // the matrix-core kernel addresses each operand with 32-bit byte offsets, clamps a strided
+    // operand's last columns to [dim-8, dim) and wants every K slice to hold at least one K tile
+    bool ok = d.dtype != DT_F32 && plan.bk == 32;
+    for (int s = 0; s < d.nseg; ++s) {
+      const int64_t a_rows = d.a_strided ? d.K[s] : d.M, b_rows = d.b_kcontig ? d.N : d.K[s];
+      if (a_rows * d.lda[s] >= (1LL << 31) || b_rows * d.ldb[s] >= (1LL << 31)) ok = false;
+    }
+    if ((d.a_strided && d.M < 8) || (!d.b_kcontig && d.N < 8)) ok = false;
+    if (!ok) cfg = CFG_BIG;
   }
   GemmArgs a{};
   for (int s = 0; s < 2; ++s) {
@@ -92,6 +98,7 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   a.tiles_per_split = plan.splits > 1 ? plan.tiles_per_split : (1 << 30);
   a.nbm = plan.nbm;
   a.nbn = plan.nbn;
+  a.splits = plan.splits;
   dim3 grid((unsigned)(plan.nbm * plan.nbn), (unsigned)plan.splits, 1);
   const int al = d.a_strided ? 1 : 0, bl = d.b_kcontig ? 1 : 0;
   hipError_t e;

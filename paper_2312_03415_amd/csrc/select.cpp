@@ -39,8 +39,7 @@ int64_t table1_flops(int is_bwd, int v, int64_t n, int64_t i, int64_t o, int64_t
 //  Streaming kernel: bytes / measured streaming rate + a fixed cost (+ the partials' round trip
 //  and the reduce launch when the contraction is also split over workgroups).
 //  Tile GEMM: workgroups run in rounds of (compute units x resident workgroups); a round costs
-//  (K tiles x measured time per K tile) + a fixed prologue/epilogue; partial and second-segment K
-//  tiles of the pipelined kernel go through its slower loader; a split contraction adds the
+//  (K tiles x measured time per K tile) + a fixed prologue/epilogue; a split contraction adds the
 //  write and re-read of the fp32 partials and the reduce launch.
 static double step_time_us(const Step& s) {
   const ModelConstants& mc = model_constants();
@@ -76,7 +75,7 @@ static double step_time_us(const Step& s) {
   double ktiles = (double)(kt0 + kt1);
   if (p.splits > 1) ktiles = (double)p.tiles_per_split;
   double slow = 0;
-  if (p.cfg == CFG_P256x256 || p.cfg == CFG_P256x128) slow = (double)(kt1 + (d.K[0] % p.bk ? 1 : 0));
+  (void)kt1;  // the matrix-core kernel runs partial and second-segment K tiles at the speed of any other
   const bool addend = d.D != nullptr && p.splits == 1;
   double us = rounds * (ktiles * tm.tk_us[lay] * share + (addend ? tm.tfix_d_us : tm.tfix_us) + slow * mc.slow_tile_us) +
               mc.launch_us;
