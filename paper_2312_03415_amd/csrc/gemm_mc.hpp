@@ -45,6 +45,7 @@ struct McTile {
   static constexpr int IPW = (A_BYTES / 1024) / NW;  // 1 KB LDS-DMA instructions per wave per operand tile (4)
   static constexpr int LPT = 2 * IPW;                // loads per K tile per wave
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+  static_assert(IPW == 4, "four loads per operand tile and wave share one LDS base");
 };
 
 // s_waitcnt immediate: at most `vm` vector-memory operations outstanding; lgkm_zero = also wait for
@@ -119,10 +120,20 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
     const uint64_t e = strided ? ((uint64_t)(K - 1) * ld + (uint64_t)rows_or_cols) : ((uint64_t)(rows_or_cols - 1) * ld + (uint64_t)K);
     return (uint32_t)(e * 2u);
   };
-  const __amdgpu_buffer_rsrc_t rsA0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(segA0), 0, extent_bytes(P::A_STR, g.M, K0, lda0), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsA1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(segA1), 0, extent_bytes(P::A_STR, g.M, K1, lda1), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsB0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(segB0), 0, extent_bytes(P::B_STR, g.N, K0, ldb0), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsB1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(segB1), 0, extent_bytes(P::B_STR, g.N, K1, ldb1), 0x00020000);
+  // The four loads of an operand tile share one LDS base (M0) and differ in the instruction's
+  // immediate offset (0, 1, 2, 3 KB), which the hardware adds to the LDS address and to the memory
+  // address alike.  The memory side is compensated in the per-lane offsets; to keep those
+  // non-negative the descriptors start kBias bytes before the matrix (address arithmetic only:
+  // every address actually formed lies inside the matrix).
+  constexpr uint32_t kBias = (IPW - 1) * 1024;
+  auto make_rsrc = [&](const T* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<unsigned char*>(const_cast<T*>(base)) - kBias, 0,
+                                             bytes ? bytes + kBias : 0u, 0x00020000);
+  };
+  const __amdgpu_buffer_rsrc_t rsA0 = make_rsrc(segA0, extent_bytes(P::A_STR, g.M, K0, lda0));
+  const __amdgpu_buffer_rsrc_t rsA1 = make_rsrc(segA1, extent_bytes(P::A_STR, g.M, K1, lda1));
+  const __amdgpu_buffer_rsrc_t rsB0 = make_rsrc(segB0, extent_bytes(P::B_STR, g.N, K0, ldb0));
+  const __amdgpu_buffer_rsrc_t rsB1 = make_rsrc(segB1, extent_bytes(P::B_STR, g.N, K1, ldb1));
   __amdgpu_buffer_rsrc_t rsA = rsA0, rsB = rsB0;  // descriptors of the cursor's segment
   uint32_t kA = 0, kB = 0;            // byte offset of the cursor's tile (k origin) in its segment (uniform)
   uint32_t stepA = 0, stepB = 0;      // bytes from one K tile to the next in the current segment
@@ -151,10 +162,10 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
         const int col = P::A_STR ? (((p & 31) ^ (4 * (row & 3))) << 3) : (((p & 3) ^ ((row >> 2) & 3)) << 3);
         if constexpr (!P::A_STR) {
           int gr = cm0 + row; gr = gr < g.M ? gr : g.M - 1;
-          offA[j] = 2u * ((uint32_t)gr * lda + (uint32_t)(col < kvalid ? col : 0));
+          offA[j] = 2u * ((uint32_t)gr * lda + (uint32_t)(col < kvalid ? col : 0)) + (kBias - 1024u * j);
         } else {
           int gc = cm0 + col; gc = gc < g.M ? gc : g.M - 8;
-          offA[j] = 2u * ((uint32_t)(row < kvalid ? row : 0) * lda + (uint32_t)gc);
+          offA[j] = 2u * ((uint32_t)(row < kvalid ? row : 0) * lda + (uint32_t)gc) + (kBias - 1024u * j);
         }
       }
       {
@@ -162,10 +173,10 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
         const int col = P::B_STR ? (((p & 31) ^ (4 * (row & 3))) << 3) : (((p & 3) ^ ((row >> 2) & 3)) << 3);
         if constexpr (!P::B_STR) {
           int gr = cn0 + row; gr = gr < g.N ? gr : g.N - 1;
-          offB[j] = 2u * ((uint32_t)gr * ldb + (uint32_t)(col < kvalid ? col : 0));
+          offB[j] = 2u * ((uint32_t)gr * ldb + (uint32_t)(col < kvalid ? col : 0)) + (kBias - 1024u * j);
         } else {
           int gc = cn0 + col; gc = gc < g.N ? gc : g.N - 8;
-          offB[j] = 2u * ((uint32_t)(row < kvalid ? row : 0) * ldb + (uint32_t)gc);
+          offB[j] = 2u * ((uint32_t)(row < kvalid ? row : 0) * ldb + (uint32_t)gc) + (kBias - 1024u * j);
         }
       }
     }
@@ -190,13 +201,23 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   // Fetch the A half / the B half of the cursor's K tile into LDS stage `st`: four loads each, no
   // branches.  The two halves are issued in different K steps so that the loads are spread evenly
   // over the MFMAs (a burst of loads from all four waves backs up the address unit and stalls issue).
-  auto issue_A1 = [&](int st, int j) {
-    unsigned char* sA = smem + st * P::STAGE_BYTES;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)(sA + (wave * IPW + j) * 1024), 16, offA[j], kA, 0, 0);
+  auto issue_A1 = [&](int st, int j) {  // j must be a constant after unrolling: it is the immediate offset
+    unsigned char* sA = smem + st * P::STAGE_BYTES + wave * (IPW * 1024);
+    switch (j) {
+      case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[0], kA, 0, 0); break;
+      case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[1], kA, 1024, 0); break;
+      case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[2], kA, 2048, 0); break;
+      default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[3], kA, 3072, 0); break;
+    }
   };
   auto issue_B1 = [&](int st, int j) {
-    unsigned char* sB = smem + st * P::STAGE_BYTES + P::A_BYTES;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)(sB + (wave * IPW + j) * 1024), 16, offB[j], kB, 0, 0);
+    unsigned char* sB = smem + st * P::STAGE_BYTES + P::A_BYTES + wave * (IPW * 1024);
+    switch (j) {
+      case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[0], kB, 0, 0); break;
+      case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[1], kB, 1024, 0); break;
+      case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[2], kB, 2048, 0); break;
+      default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[3], kB, 3072, 0); break;
+    }
   };
   auto issue_A = [&](int st) {
 #pragma unroll
@@ -310,9 +331,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 
   f32x16 acc[4][4];
 
-#ifndef MC_VMEM_AT
 #define MC_VMEM_AT(q) (((q) & 3) == 3)
-#endif
 #define MC_FENCE() __builtin_amdgcn_sched_barrier(0)
   // One K step, in exactly this instruction order (a scheduling fence after every piece): 16 MFMAs out
   // of fragment buffer `bufc`; behind each of the first 8, one fragment of K step KSR of the stage at
@@ -424,6 +443,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   // the LDS-DMA writes still in flight target this workgroup's LDS: let them land before it is released
   __builtin_amdgcn_s_waitcnt(mc_wait_imm(0, true));
 #undef MC_SYNC
+#undef MC_VMEM_AT
 #undef MC_FENCE
 }
 
