@@ -25,8 +25,11 @@
  *     first HIP call, so they behave the same on a host without a GPU.  No exception crosses
  *     the boundary.
  *   - Element types: RL_F32, RL_F16, RL_BF16 for every tensor of a call (one type per call).
- *     RL_INT4_G64 is allowed for W only (see rl_tensor_t).  Accumulation is fp32 throughout;
- *     each result is rounded once (nearest even) to the storage type.
+ *     RL_INT4_G64 is allowed for W only (see rl_tensor_t), with RL_F16 / RL_BF16 activations: W is
+ *     dequantised inside the GEMMs that read it (q * scale, rounded to the activation type) and
+ *     never written out densely.  The graphs that need W + AB as a matrix (RL_FWD2, RL_BWD4,
+ *     RL_BWD5) return RL_ERR_UNSUPPORTED for an int4 W.  Accumulation is fp32 throughout; each
+ *     result is rounded once (nearest even) to the storage type.
  *   - Alignment: data pointers 16-byte aligned; ld (elements between rows) >= cols and a
  *     multiple of 8 (16-bit types) or 4 (fp32); i, o and r multiples of 8 (16-bit) or 4 (fp32);
  *     n is arbitrary (>= 1).  Anything else returns RL_ERR_ALIGN / RL_ERR_SHAPE.
@@ -93,6 +96,7 @@ typedef enum {
  * A dense row-major matrix in device memory.
  *   data   device pointer to element (0,0); for RL_INT4_G64: packed nibbles, two per byte, element
  *          (k,j) in byte (k*ld + j)/2, low nibble for even j, value = nibble - 8 in [-7,7]
+ *          (ld a multiple of 8, data and scales 16-byte aligned)
  *   rows, cols, ld   in elements; ld = distance between consecutive rows
  *   dtype  rl_dtype_t
  *   scales RL_INT4_G64 only: device pointer to fp16 scales [ceil(rows/64), cols], row-major, dense
@@ -179,9 +183,12 @@ double runlora_model_time_us(int is_bwd, int variant, int64_t n, int64_t i, int6
                              int dtype);
 
 /* Scratch bytes needed by a forward variant (bwd < 0), a backward variant (fwd < 0), or the
- * larger of the two.  w_dtype is W's dtype (RL_INT4_G64 or the same as dtype). */
+ * larger of the two, for a dense W of the layer dtype.  0 for an unknown variant or dtype. */
 size_t runlora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r,
                                int dtype);
+/* Same with W's dtype explicit: w_dtype = dtype (dense) or RL_INT4_G64. */
+size_t runlora_workspace_bytes_w(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r,
+                                 int dtype, int w_dtype);
 
 /*
  * The building block every step above is made of, exposed for tests, tuning and calibration of

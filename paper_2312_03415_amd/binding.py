@@ -29,7 +29,7 @@ RL_ERR_ALIGN, RL_ERR_ALIAS, RL_ERR_WORKSPACE, RL_ERR_UNSUPPORTED, RL_ERR_HIP = -
 
 EXPORTS = (
     "runlora_forward", "runlora_backward", "runlora_select", "runlora_select_by", "runlora_flops",
-    "runlora_model_time_us", "runlora_workspace_bytes", "runlora_strerror", "runlora_last_hip_error",
+    "runlora_model_time_us", "runlora_workspace_bytes", "runlora_workspace_bytes_w", "runlora_strerror", "runlora_last_hip_error",
     "runlora_version", "runlora_gemm", "runlora_gemm_workspace_bytes",
     "runlora_profile_enable", "runlora_profile_collect", "runlora_profile_disable", "runlora_probe_mfma",
 )
@@ -103,6 +103,8 @@ def lib():
     L.runlora_model_time_us.restype = ctypes.c_double
     L.runlora_workspace_bytes.argtypes = [ci, ci, i64, i64, i64, i64, ci]
     L.runlora_workspace_bytes.restype = ctypes.c_size_t
+    L.runlora_workspace_bytes_w.argtypes = [ci, ci, i64, i64, i64, i64, ci, ci]
+    L.runlora_workspace_bytes_w.restype = ctypes.c_size_t
     L.runlora_strerror.argtypes = [ci]
     L.runlora_strerror.restype = ctypes.c_char_p
     L.runlora_last_hip_error.argtypes = []
@@ -143,10 +145,36 @@ def dtype_from_name(name):
     return {"f32": RL_F32, "f16": RL_F16, "bf16": RL_BF16, "int4": RL_INT4_G64}[name]
 
 
+class Int4Weight:
+    """A frozen W [rows, cols] stored as symmetric int4 with one fp16 scale per 64 rows per column
+    (RL_INT4_G64): `packed` is a uint8 device tensor [rows, ld/2] (element (k,j) in the low nibble of
+    byte j/2 of row k for even j, high nibble for odd j; value = nibble - 8), `scales` an fp16 device
+    tensor [ceil(rows/64), cols]."""
+
+    def __init__(self, packed, scales, rows, cols):
+        assert packed.dim() == 2 and packed.stride(1) == 1 and packed.shape[0] == rows
+        assert scales.dim() == 2 and scales.is_contiguous() and scales.shape == ((rows + 63) // 64, cols)
+        self.packed, self.scales, self.rows, self.cols = packed, scales, rows, cols
+        self.ld = packed.stride(0) * 2
+
+    @staticmethod
+    def from_host(q, scale, device="cuda"):
+        """q: int8 numpy [rows, cols] with values in [-7,7] (cols even); scale: float16 numpy."""
+        import numpy as np
+        import torch
+        rows, cols = q.shape
+        u = (q.astype(np.int16) + 8).astype(np.uint8)
+        packed = (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
+        return Int4Weight(torch.from_numpy(np.ascontiguousarray(packed)).to(device),
+                          torch.from_numpy(np.ascontiguousarray(scale)).to(device), rows, cols)
+
+
 def tensor_desc(t):
-    """rl_tensor_t view of a 2-D torch tensor (None -> NULL pointer argument)."""
+    """rl_tensor_t view of a 2-D torch tensor or an Int4Weight (None -> NULL pointer argument)."""
     if t is None:
         return None
+    if isinstance(t, Int4Weight):
+        return rl_tensor_t(t.packed.data_ptr(), t.rows, t.cols, t.ld, RL_INT4_G64, t.scales.data_ptr(), 64)
     if t.dim() != 2 or t.stride(1) != 1:
         raise ValueError("expected a 2-D tensor with contiguous rows")
     return rl_tensor_t(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), dtype_code(t.dtype), None, 0)
@@ -204,8 +232,10 @@ def runlora_model_time_us(is_bwd, variant, n, i, o, r, dtype):
     return float(lib().runlora_model_time_us(int(is_bwd), variant, n, i, o, r, dtype))
 
 
-def runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype):
-    return int(lib().runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype))
+def runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype, w_dtype=None):
+    if w_dtype is None:
+        return int(lib().runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype))
+    return int(lib().runlora_workspace_bytes_w(fwd, bwd, n, i, o, r, dtype, w_dtype))
 
 
 def runlora_gemm(A, B, C, a_strided=False, b_kcontig=False, A2=None, B2=None, D=None, tile_cfg=-1, splits=0,
@@ -269,7 +299,7 @@ def new_saved(T=None):
     return s
 
 
-def new_workspace(fwd, bwd, n, i, o, r, dtype, device="cuda"):
+def new_workspace(fwd, bwd, n, i, o, r, dtype, device="cuda", w_dtype=None):
     import torch
-    nbytes = runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype)
+    nbytes = runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype, w_dtype)
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)

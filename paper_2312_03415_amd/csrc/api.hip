@@ -61,6 +61,38 @@ Mat mat(const rl_tensor_t* t) {
   return m;
 }
 
+// the frozen W: dense in the layer dtype, or int4 with group scales (16-bit activations only)
+int check_weight(const rl_tensor_t* W, int64_t i, int64_t o, int dtype, bool* int4) {
+  *int4 = false;
+  if (!W || !W->data) return RL_ERR_NULL;
+  if (W->dtype != RL_INT4_G64) return check_tensor(W, i, o, dtype);
+  if (dtype == RL_F32) return RL_ERR_DTYPE;
+  if (!W->scales) return RL_ERR_NULL;
+  if (W->group != 64) return RL_ERR_UNSUPPORTED;
+  if (W->rows != i || W->cols != o || W->ld < W->cols) return RL_ERR_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(W->data) & 15) != 0 || (reinterpret_cast<uintptr_t>(W->scales) & 15) != 0 ||
+      W->ld % 8 != 0)
+    return RL_ERR_ALIGN;
+  *int4 = true;
+  return RL_OK;
+}
+
+Range weight_range(const rl_tensor_t* W, int64_t i, int64_t o, size_t esz, bool int4) {
+  if (!int4) return range_of(W->data, i, W->ld, o, esz);
+  const char* lo = static_cast<const char*>(W->data);
+  return {lo, lo + ((size_t)(i - 1) * (size_t)W->ld + (size_t)o + 1) / 2};
+}
+
+Mat weight_mat(const rl_tensor_t* W, int64_t o, bool int4) {
+  Mat m = mat(W);
+  if (int4) {
+    m.scales = W->scales;
+    m.lds = o;  // scales are dense [ceil(i/64), o]
+  }
+  return m;
+}
+
+
 // optional per-step event timing (runlora_profile_*), one recorder per host thread
 struct Profiler {
   bool on = false;
@@ -137,24 +169,25 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
   const int dtype = X->dtype;
   const int dt = internal_dtype(dtype);
   if (dt < 0) return RL_ERR_DTYPE;
-  if (W->dtype == RL_INT4_G64) return RL_ERR_UNSUPPORTED;
   const int64_t n = X->rows, i = X->cols, o = W->cols, r = A->cols;
   int rc;
+  bool w_int4 = false;
   if ((rc = check_dims(n, i, o, r, dtype)) != RL_OK) return rc;
   if ((rc = check_tensor(X, n, i, dtype)) != RL_OK) return rc;
-  if ((rc = check_tensor(W, i, o, dtype)) != RL_OK) return rc;
+  if ((rc = check_weight(W, i, o, dtype, &w_int4)) != RL_OK) return rc;
+  if (w_int4 && variant == RL_FWD2) return RL_ERR_UNSUPPORTED;  // no dense W to merge AB into
   if ((rc = check_tensor(A, i, r, dtype)) != RL_OK) return rc;
   if ((rc = check_tensor(B, r, o, dtype)) != RL_OK) return rc;
   if ((rc = check_tensor(Y, n, o, dtype)) != RL_OK) return rc;
   const size_t esz = dtype_size(dt);
   Range ry = range_of(Y->data, n, Y->ld, o, esz);
-  if (overlap(ry, range_of(X->data, n, X->ld, i, esz)) || overlap(ry, range_of(W->data, i, W->ld, o, esz)) ||
+  if (overlap(ry, range_of(X->data, n, X->ld, i, esz)) || overlap(ry, weight_range(W, i, o, esz, w_int4)) ||
       overlap(ry, range_of(A->data, i, A->ld, r, esz)) || overlap(ry, range_of(B->data, r, B->ld, o, esz)))
     return RL_ERR_ALIAS;
 
-  LayerDims L{n, i, o, r, dt};
+  LayerDims L{n, i, o, r, dt, w_int4};
   FwdOperands op;
-  op.X = mat(X); op.W = mat(W); op.A = mat(A); op.B = mat(B); op.Y = mat(Y);
+  op.X = mat(X); op.W = weight_mat(W, o, w_int4); op.A = mat(A); op.B = mat(B); op.Y = mat(Y);
   if (variant == RL_FWD_DEFAULT) {
     if (!saved->T) return RL_ERR_NULL;
     const int64_t q = dtype == RL_F32 ? 4 : 8;
@@ -191,12 +224,13 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   const int dtype = dY->dtype;
   const int dt = internal_dtype(dtype);
   if (dt < 0) return RL_ERR_DTYPE;
-  if (W->dtype == RL_INT4_G64) return RL_ERR_UNSUPPORTED;
   const int64_t n = dY->rows, o = dY->cols, i = W->rows, r = A->cols;
   int rc;
+  bool w_int4 = false;
   if ((rc = check_dims(n, i, o, r, dtype)) != RL_OK) return rc;
   if ((rc = check_tensor(dY, n, o, dtype)) != RL_OK) return rc;
-  if ((rc = check_tensor(W, i, o, dtype)) != RL_OK) return rc;
+  if ((rc = check_weight(W, i, o, dtype, &w_int4)) != RL_OK) return rc;
+  if (w_int4 && (variant == RL_BWD4 || variant == RL_BWD5)) return RL_ERR_UNSUPPORTED;
   if ((rc = check_tensor(A, i, r, dtype)) != RL_OK) return rc;
   if ((rc = check_tensor(B, r, o, dtype)) != RL_OK) return rc;
   if (dX && (rc = check_tensor(dX, n, i, dtype)) != RL_OK) return rc;
@@ -216,7 +250,7 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   }
   const size_t esz = dtype_size(dt);
   Range in[6] = {range_of(dY->data, n, dY->ld, o, esz), range_of(saved->X, n, saved->ldx, i, esz),
-                 range_of(W->data, i, W->ld, o, esz), range_of(A->data, i, A->ld, r, esz),
+                 weight_range(W, i, o, esz, w_int4), range_of(A->data, i, A->ld, r, esz),
                  range_of(B->data, r, B->ld, o, esz),
                  (variant == RL_BWD_DEFAULT) ? range_of(saved->T, n, saved->ldt, r, esz) : Range{nullptr, nullptr}};
   Range outr[3];
@@ -231,9 +265,9 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
       if (overlap(outr[a], outr[b])) return RL_ERR_ALIAS;
   }
 
-  LayerDims L{n, i, o, r, dt};
+  LayerDims L{n, i, o, r, dt, w_int4};
   BwdOperands op;
-  op.dY = mat(dY); op.W = mat(W); op.A = mat(A); op.B = mat(B);
+  op.dY = mat(dY); op.W = weight_mat(W, o, w_int4); op.A = mat(A); op.B = mat(B);
   op.X.ptr = saved->X; op.X.ld = saved->ldx;
   op.T.ptr = saved->T; op.T.ld = saved->ldt;
   op.want_dX = dX != nullptr; op.want_dA = dA != nullptr; op.want_dB = dB != nullptr;
@@ -249,9 +283,15 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
 }
 
 extern "C" size_t runlora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype) {
+  return runlora_workspace_bytes_w(fwd, bwd, n, i, o, r, dtype, dtype);
+}
+
+extern "C" size_t runlora_workspace_bytes_w(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype,
+                                            int w_dtype) {
   const int dt = internal_dtype(dtype);
   if (dt < 0 || n < 1 || i < 1 || o < 1 || r < 1) return 0;
-  LayerDims L{n, i, o, r, dt};
+  if (w_dtype != dtype && w_dtype != RL_INT4_G64) return 0;
+  LayerDims L{n, i, o, r, dt, w_dtype == RL_INT4_G64};
   size_t need = 0;
   Schedule sch;
   if (fwd >= 0) {

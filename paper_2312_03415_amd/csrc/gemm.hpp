@@ -23,6 +23,10 @@ struct GemmDesc {
   int64_t ldc = 0;
   const void* D = nullptr;  // optional addend, same dtype as C (may alias C)
   int64_t ldd = 0;
+  // B[0] is symmetric int4 (packed nibbles, ldb[0] in elements) with fp16 group scales
+  // [rows/64, ldbs]; nullptr = dense.  16-bit types, generic engine only.
+  const void* Bscale = nullptr;
+  int64_t ldbs = 0;
 };
 
 enum TileCfg {
@@ -46,6 +50,9 @@ struct GemmPlan {
 // override the heuristics (used by the tuning sweeps and tests).
 GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg = -1,
                    int force_splits = 0);
+
+// Plan for a product whose B[0] is int4 (GemmDesc::Bscale): generic engine, two tile shapes.
+GemmPlan gemm_plan_int4(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1);
 
 // Enqueue the product.  `scratch` must hold plan.partial_bytes when plan.splits > 1.
 hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream);

@@ -44,6 +44,11 @@ struct GemmArgs {
   int tiles_per_split;  // K tiles per gridDim.y slice
   int nbm, nbn;         // tile grid
   int splits;           // number of K slices (gemm_mc_kernel: folded into blockIdx.x)
+  // B of segment 0 stored as symmetric int4 with group scales (the frozen W of a quantised layer):
+  // element (row, col) of the stored matrix is nibble (row * ldb + col) of B[0] (low nibble first),
+  // value (nibble - 8) * scale[(row / 64) * ldbs + col], scales in fp16.  Bscale == nullptr: dense B.
+  const void* Bscale;
+  int64_t ldbs;
 };
 
 // ---- per-type pieces --------------------------------------------------------------------------
@@ -187,6 +192,19 @@ __device__ __forceinline__ i32x4 read_frag(const T* tile, int idx0, int ks, int 
   }
 }
 
+// Eight int4 weights (one 32-bit word, low nibble first) times their eight fp16 scales -> eight T.
+template <typename T>
+__device__ __forceinline__ i32x4 dequant_chunk(uint32_t w, i32x4 sc) {
+  const _Float16* s8 = reinterpret_cast<const _Float16*>(&sc);
+  T o8[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int q = (int)((w >> (4 * j)) & 15u) - 8;
+    o8[j] = from_f32<T>((float)q * (float)s8[j]);
+  }
+  return *reinterpret_cast<i32x4*>(o8);
+}
+
 // ---- the kernel ---------------------------------------------------------------------------------
 // AL: 0 = A stored [M,K] (K contiguous), 1 = A stored [K,M].   BL: 0 = B stored [K,N], 1 = [N,K].
 template <typename T, int AL, int BL, int BM, int BN, int BK, int WM, int WN>
@@ -210,7 +228,9 @@ struct GemmTile {
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
-template <typename T, int AL, int BL, int BM, int BN, int BK, int WM, int WN>
+// BQ: B of segment 0 is int4 with group scales (see GemmArgs); it is dequantised on its way from
+// the load registers to LDS, so the matrix cores see ordinary T operands.
+template <typename T, int AL, int BL, int BM, int BN, int BK, int WM, int WN, bool BQ = false>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
   using G = GemmTile<T, AL, BL, BM, BN, BK, WM, WN>;
   constexpr int NT = G::NT, VE = G::VE;
@@ -252,6 +272,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
   i32x4 ra[G::A_PER], rb[G::B_PER];
+  uint32_t rq[BQ ? G::B_PER : 1];  // packed int4 words of the tile in flight (BQ, segment 0)
+  bool quant_tile = false;         // the tile in flight is one of the int4 segment
 
   auto load_global = [&](int t) {
     const int s = t < nt0 ? 0 : 1;
@@ -276,21 +298,28 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
       }
       ra[j] = v;
     }
+    if constexpr (BQ) quant_tile = (s == 0);
 #pragma unroll
     for (int j = 0; j < G::B_PER; ++j) {
       const int c = tid + j * NT;
       const int row = c / G::B_CPR, col = (c % G::B_CPR) * VE;
       i32x4 v = {0, 0, 0, 0};
+      uint32_t w = 0x88888888u;  // eight zeros in the int4 encoding
       if (G::B_CHUNKS % NT == 0 || c < G::B_CHUNKS) {
-        if constexpr (G::B_STR) {  // row = k, col = n
-          if (k0 + row < Ks && n0 + col < g.N)
-            v = *reinterpret_cast<const i32x4*>(Bp + (int64_t)(k0 + row) * ldb + n0 + col);
-        } else {  // row = n, col = k
-          if (n0 + row < g.N && k0 + col < Ks)
-            v = *reinterpret_cast<const i32x4*>(Bp + (int64_t)(n0 + row) * ldb + k0 + col);
+        // (sr, sc) = position in the stored matrix
+        const int sr = G::B_STR ? k0 + row : n0 + row, sc = G::B_STR ? n0 + col : k0 + col;
+        const bool ok = G::B_STR ? (k0 + row < Ks && n0 + col < g.N) : (n0 + row < g.N && k0 + col < Ks);
+        if (ok) {
+          if (BQ && s == 0) {
+            w = *reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(g.B[0]) + (((int64_t)sr * ldb + sc) >> 1));
+            v = *reinterpret_cast<const i32x4*>(static_cast<const _Float16*>(g.Bscale) + (int64_t)(sr >> 6) * g.ldbs + sc);
+          } else {
+            v = *reinterpret_cast<const i32x4*>(Bp + (int64_t)sr * ldb + sc);
+          }
         }
       }
       rb[j] = v;
+      if constexpr (BQ) rq[j] = w;
     }
   };
 
@@ -306,8 +335,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
 #pragma unroll
     for (int j = 0; j < G::B_PER; ++j) {
       const int c = tid + j * NT;
-      if (G::B_CHUNKS % NT == 0 || c < G::B_CHUNKS)
-        *reinterpret_cast<i32x4*>(sB + (c / G::B_CPR) * G::B_LD + (c % G::B_CPR) * VE) = rb[j];
+      if (G::B_CHUNKS % NT == 0 || c < G::B_CHUNKS) {
+        i32x4 v = rb[j];
+        if constexpr (BQ) {
+          if (quant_tile) v = dequant_chunk<T>(rq[j], rb[j]);
+        }
+        *reinterpret_cast<i32x4*>(sB + (c / G::B_CPR) * G::B_LD + (c % G::B_CPR) * VE) = v;
+      }
     }
   };
 

@@ -64,10 +64,17 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   return p;
 }
 
+GemmPlan gemm_plan_int4(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1) {
+  // an int4 B runs on the generic engine: 256x256 tiles when they fill the chip, else 128x128
+  const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  return gemm_plan(dtype, M, N, K0, K1, big_tiles >= 160 ? CFG_BIG : CFG_MID, 0);
+}
+
 hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream) {
   if (d.M <= 0 || d.N <= 0) return hipErrorInvalidValue;
   if (plan.splits > 1 && scratch == nullptr) return hipErrorInvalidValue;
   int cfg = plan.cfg;
+  if (d.Bscale != nullptr && cfg != CFG_BIG && cfg != CFG_MID) return hipErrorInvalidValue;  // see gemm_plan_int4
   if (cfg == CFG_MC3 || cfg == CFG_MC4) {
     // the matrix-core kernel addresses each operand with 32-bit byte offsets, clamps a strided
     // operand's last columns to [dim-8, dim) and wants every K slice to hold at least one K tile
@@ -99,6 +106,8 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   a.nbm = plan.nbm;
   a.nbn = plan.nbn;
   a.splits = plan.splits;
+  a.Bscale = d.Bscale;
+  a.ldbs = d.ldbs;
   dim3 grid((unsigned)(plan.nbm * plan.nbn), (unsigned)plan.splits, 1);
   const int al = d.a_strided ? 1 : 0, bl = d.b_kcontig ? 1 : 0;
   hipError_t e;

@@ -26,8 +26,10 @@ struct Builder {
   }
 
   // C[M,N] = op(A)[M,K] op(B)[K,N] (+ second segment) (+ D)
+  // b_is_w: B is the layer's frozen W (int4 when L.w_int4)
   void gemm(const char* what, int a_strided, int b_kcontig, int64_t M, int64_t N, int64_t K, Mat A, Mat B,
-            Mat C, const Mat* D = nullptr, int64_t K2 = 0, const Mat* A2 = nullptr, const Mat* B2 = nullptr) {
+            Mat C, const Mat* D = nullptr, int64_t K2 = 0, const Mat* A2 = nullptr, const Mat* B2 = nullptr,
+            bool b_is_w = false) {
     Step s;
     s.what = what;
     GemmDesc& d = s.d;
@@ -42,7 +44,13 @@ struct Builder {
     d.C = const_cast<void*>(C.ptr);
     d.ldc = C.ld;
     if (D) { d.D = D->ptr; d.ldd = D->ld; }
-    s.plan = gemm_plan(L.dtype, M, N, K, K2);
+    if (b_is_w && L.w_int4) {
+      d.Bscale = B.scales;
+      d.ldbs = B.lds;
+      s.plan = gemm_plan_int4(L.dtype, M, N, K, K2);
+    } else {
+      s.plan = gemm_plan(L.dtype, M, N, K, K2);
+    }
     if (s.plan.partial_bytes > max_partial) max_partial = s.plan.partial_bytes;
     out->steps.push_back(s);
   }
@@ -158,17 +166,18 @@ bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void*
   switch (variant) {
     case 0: {  // default chain: T kept, one kernel per product
       b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, op.T});
-      b.gemm("Y = X W", 0, 0, n, o, i, op.X, op.W, op.Y);
+      b.gemm("Y = X W", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, 0, nullptr, nullptr, true);
       b.gemm("Y += T B", 0, 0, n, o, r, op.T, op.B, op.Y, &op.Y);
       break;
     }
     case 1: {  // forward1: (XW) + ((XA)B), the sum folded into one contraction over [X|T]
       Mat T = b.scratch(n, r);
       b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T});
-      b.gemm("Y = [X|T] [W;B]", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, r, &T, &op.B);
+      b.gemm("Y = [X|T] [W;B]", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, r, &T, &op.B, true);
       break;
     }
     case 2: {  // forward2: X (W + AB)
+      if (L.w_int4) return false;  // no dense buffer to merge AB into
       Mat M = b.scratch(i, o);
       b.gemm("M = W + A B", 0, 0, i, o, r, op.A, op.B, M, &op.W);
       b.gemm("Y = X M", 0, 0, n, o, i, op.X, M, op.Y);
@@ -194,7 +203,7 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
       if (dB) b.skinny("dB = T^T dY", {1, 0, r, o, n, op.T, op.dY, op.dB});
       if (dA) b.skinny("dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA});
       if (dX) {
-        b.gemm("dX = dY W^T", 0, 1, n, i, o, op.dY, op.W, op.dX);
+        b.gemm("dX = dY W^T", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, 0, nullptr, nullptr, true);
         b.gemm("dX += Z1 A^T", 0, 1, n, i, r, Z1, op.A, op.dX, &op.dX);
       }
       break;
@@ -202,7 +211,7 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     case 1: {  // Algorithm 1
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r);
       rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA || dX, dB, dA, dB);
-      if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A);
+      if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A, true);
       break;
     }
     case 2: {  // Algorithm 2
@@ -214,7 +223,7 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
                   {1, 0, r, o, i, op.A, Z2, op.dB});
       else if (dA) b.skinny("dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA});
       else if (dB) b.skinny("dB = A^T Z2", {1, 0, r, o, i, op.A, Z2, op.dB});
-      if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A);
+      if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A, true);
       break;
     }
     case 3: {  // Algorithm 3
@@ -222,10 +231,11 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
       if (dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1});
       if (dA || dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
       z2_grads(b, op, i, o, r, Z2, dA, dB);
-      if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A);
+      if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A, true);
       break;
     }
     case 4: {  // Algorithm 4
+      if (L.w_int4) return false;
       Mat Z1 = b.scratch(i, o), Z2 = b.scratch(i, o);
       if (dX) b.gemm("Z1 = W + A B", 0, 0, i, o, r, op.A, op.B, Z1, &op.W);
       if (dA || dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
@@ -234,6 +244,7 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
       break;
     }
     case 5: {  // Algorithm 5
+      if (L.w_int4) return false;
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r), Z3 = b.scratch(i, o);
       if (dX) b.gemm("Z3 = W + A B", 0, 0, i, o, r, op.A, op.B, Z3, &op.W);
       rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA, dB, dA, dB);

@@ -13,11 +13,15 @@ namespace rl {
 struct Mat {  // device matrix view; ptr may be null when only shapes are needed
   const void* ptr = nullptr;
   int64_t ld = 0;
+  // frozen W stored as int4 with group scales (see GemmDesc::Bscale): ptr = packed nibbles
+  const void* scales = nullptr;
+  int64_t lds = 0;
 };
 
 struct LayerDims {
   int64_t n = 0, i = 0, o = 0, r = 0;
   int dtype = DT_BF16;
+  bool w_int4 = false;  // W is int4: its products run on the generic engine, merged graphs do not exist
 };
 
 struct Step {

@@ -144,9 +144,15 @@ def test_forward_rejects_bad_arguments_before_touching_the_gpu():
     assert call_fwd(1, a, opts=rl.rl_opts_t(None, 0x70000010, need)) == rl.RL_ERR_ALIGN
     # default chain needs the caller's T buffer
     assert call_fwd(0, a) == rl.RL_ERR_NULL
-    # int4 W is declared but not built yet
+    # int4 W: needs scales and group 64; the merged forward does not exist for it; fp32 activations are refused
     b = fwd_args(); b["W"].dtype = rl.RL_INT4_G64
-    assert call_fwd(1, b) == rl.RL_ERR_UNSUPPORTED
+    assert call_fwd(1, b) == rl.RL_ERR_NULL
+    b["W"].scales = 0x50000000
+    assert call_fwd(1, b) == rl.RL_ERR_UNSUPPORTED          # group != 64
+    b["W"].group = 64
+    assert call_fwd(2, b) == rl.RL_ERR_UNSUPPORTED          # X (W + AB) needs a dense W
+    b["W"].scales = 0x50000004
+    assert call_fwd(1, b) == rl.RL_ERR_ALIGN
 
 
 def test_backward_rejects_bad_arguments_before_touching_the_gpu():
