@@ -24,7 +24,7 @@ import numpy as np
 
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 HBM_PEAK_GBPS = 8000.0
-TILE_NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x256mc3", "256x256mc", "stream32", "stream64", "stream128"]
+TILE_NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x256mc3", "256x256mc", "stream32", "stream64", "stream128", "merge"]
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/), scaled by what the same counters read for a copy kernel of known size; None until

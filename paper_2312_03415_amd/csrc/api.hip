@@ -103,6 +103,18 @@ struct Profiler {
 thread_local Profiler g_prof;
 
 void describe_step(const Step& s, rl_step_time_t* r) {
+  if (s.is_merge) {
+    const double e = (double)dtype_size(s.d.dtype);
+    r->what = s.what;
+    r->us = 0.0;
+    r->flops = 2.0 * (double)s.mg.I * (double)s.mg.O * (double)s.mg.R;
+    r->bytes = e * (2.0 * (double)s.mg.I * (double)s.mg.O + (double)s.mg.R * (double)(s.mg.I + s.mg.O));
+    r->M = s.mg.I; r->N = s.mg.O; r->K = s.mg.R;
+    r->tile_cfg = CFG_COUNT + 3;
+    r->splits = 1;
+    r->a_strided = 0; r->b_kcontig = 0;
+    return;
+  }
   if (s.nsk > 0) {
     const double e = (double)dtype_size(s.d.dtype);
     r->what = s.what;
@@ -140,8 +152,9 @@ int run_schedule(const Schedule& sch, char* ws, hipStream_t stream) {
       hipError_t e = hipEventRecord(g_prof.start[g_prof.used], stream);
       if (e != hipSuccess) return set_hip_error(e, "profile event");
     }
-    hipError_t e = s.nsk > 0 ? skinny_run(s.d.dtype, s.nsk, s.sk, s.skplan, partial, stream)
-                             : gemm_run(s.d, s.plan, partial, stream);
+    hipError_t e = s.is_merge ? merge_run(s.d.dtype, s.mg, stream)
+                   : s.nsk > 0 ? skinny_run(s.d.dtype, s.nsk, s.sk, s.skplan, partial, stream)
+                               : gemm_run(s.d, s.plan, partial, stream);
     if (e != hipSuccess) return set_hip_error(e, s.what);
     if (timed) {
       e = hipEventRecord(g_prof.stop[g_prof.used], stream);

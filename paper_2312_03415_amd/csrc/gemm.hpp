@@ -81,6 +81,19 @@ hipError_t skinny_launch_bf16(int rt, const SkinnyArgs& a, dim3 grid, int splits
 hipError_t skinny_launch_f16(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
 hipError_t skinny_launch_f32(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
 
+// ---- M = W + A B (merge.hpp): 16-bit types, r <= 128 --------------------------------------------
+struct MergeDesc {
+  const void *W = nullptr, *A = nullptr, *B = nullptr;
+  void* M = nullptr;
+  int64_t ldw = 0, lda = 0, ldb = 0, ldm = 0;
+  int64_t I = 0, O = 0, R = 0;
+};
+inline bool merge_ok(int dtype, int64_t r) { return dtype != DT_F32 && r <= 128; }
+hipError_t merge_run(int dtype, const MergeDesc& d, hipStream_t stream);
+struct MergeArgs;
+hipError_t merge_launch_bf16(const MergeArgs& a, hipStream_t s);
+hipError_t merge_launch_f16(const MergeArgs& a, hipStream_t s);
+
 // per-dtype launchers (one translation unit each)
 struct GemmArgs;
 hipError_t gemm_launch_bf16(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);

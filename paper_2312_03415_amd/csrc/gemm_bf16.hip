@@ -2,5 +2,6 @@
 #define RL_BK 64
 #define RL_FN gemm_launch_bf16
 #define RL_SKINNY_FN skinny_launch_bf16
+#define RL_MERGE_FN merge_launch_bf16
 #define RL_PIPE 1
 #include "gemm_launch.inc"

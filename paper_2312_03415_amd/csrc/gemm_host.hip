@@ -2,6 +2,7 @@
 #include "gemm.hpp"
 #include "gemm_engine.hpp"
 #include "skinny.hpp"
+#include "merge.hpp"
 
 namespace rl {
 
@@ -219,6 +220,18 @@ hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPla
     case DT_F32: return skinny_launch_f32(plan.rt, a, grid, plan.splits, stream);
     default: return hipErrorInvalidValue;
   }
+}
+
+// ---- M = W + A B ------------------------------------------------------------------------------------
+
+hipError_t merge_run(int dtype, const MergeDesc& d, hipStream_t stream) {
+  if (!merge_ok(dtype, d.R) || d.I < 1 || d.O < 1 || d.R < 1) return hipErrorInvalidValue;
+  MergeArgs a{};
+  a.W = d.W; a.A = d.A; a.B = d.B; a.M = d.M;
+  a.ldw = d.ldw; a.lda = d.lda; a.ldb = d.ldb; a.ldm = d.ldm;
+  a.I = (int)d.I; a.O = (int)d.O; a.R = (int)d.R;
+  a.blocks_per_wg = 1;
+  return dtype == DT_BF16 ? merge_launch_bf16(a, stream) : merge_launch_f16(a, stream);
 }
 
 }  // namespace rl

@@ -55,6 +55,23 @@ struct Builder {
     out->steps.push_back(s);
   }
 
+  // M = W + A B: the bandwidth-bound merge kernel when it applies (16-bit, r <= 128), else the tile
+  // GEMM with W as the addend
+  void merge(const char* what, Mat A, Mat B, Mat W, Mat M) {
+    if (!merge_ok(L.dtype, L.r)) {
+      gemm(what, 0, 0, L.i, L.o, L.r, A, B, M, &W);
+      return;
+    }
+    Step s;
+    s.what = what;
+    s.is_merge = true;
+    s.d.dtype = L.dtype;
+    s.mg.W = W.ptr; s.mg.A = A.ptr; s.mg.B = B.ptr; s.mg.M = const_cast<void*>(M.ptr);
+    s.mg.ldw = W.ld; s.mg.lda = A.ld; s.mg.ldb = B.ld; s.mg.ldm = M.ld;
+    s.mg.I = L.i; s.mg.O = L.o; s.mg.R = L.r;
+    out->steps.push_back(s);
+  }
+
   // Rank-r product C[M,N] = op(A) op(B) (N = r, or M = r with the output stored transposed) on the
   // streaming kernel; falls back to the tile GEMM when r is too large for it.
   struct Sk {
@@ -179,7 +196,7 @@ bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void*
     case 2: {  // forward2: X (W + AB)
       if (L.w_int4) return false;  // no dense buffer to merge AB into
       Mat M = b.scratch(i, o);
-      b.gemm("M = W + A B", 0, 0, i, o, r, op.A, op.B, M, &op.W);
+      b.merge("M = W + A B", op.A, op.B, op.W, M);
       b.gemm("Y = X M", 0, 0, n, o, i, op.X, M, op.Y);
       break;
     }
@@ -237,7 +254,7 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     case 4: {  // Algorithm 4
       if (L.w_int4) return false;
       Mat Z1 = b.scratch(i, o), Z2 = b.scratch(i, o);
-      if (dX) b.gemm("Z1 = W + A B", 0, 0, i, o, r, op.A, op.B, Z1, &op.W);
+      if (dX) b.merge("Z1 = W + A B", op.A, op.B, op.W, Z1);
       if (dA || dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
       z2_grads(b, op, i, o, r, Z2, dA, dB);
       if (dX) b.gemm("dX = dY Z1^T", 0, 1, n, i, o, op.dY, Z1, op.dX);
@@ -246,7 +263,7 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     case 5: {  // Algorithm 5
       if (L.w_int4) return false;
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r), Z3 = b.scratch(i, o);
-      if (dX) b.gemm("Z3 = W + A B", 0, 0, i, o, r, op.A, op.B, Z3, &op.W);
+      if (dX) b.merge("Z3 = W + A B", op.A, op.B, op.W, Z3);
       rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA, dB, dA, dB);
       if (dX) b.gemm("dX = dY Z3^T", 0, 1, n, i, o, op.dY, Z3, op.dX);
       break;

@@ -25,6 +25,8 @@ struct LayerDims {
 };
 
 struct Step {
+  bool is_merge = false;  // M = W + A B on the merge kernel (mg); otherwise see nsk
+  MergeDesc mg;
   int nsk = 0;  // 0: one tile-GEMM launch (d, plan); 1 or 2: streaming-kernel launch of sk[0..nsk-1]
   GemmDesc d;
   GemmPlan plan;

@@ -44,6 +44,8 @@ int64_t table1_flops(int is_bwd, int v, int64_t n, int64_t i, int64_t o, int64_t
 static double step_time_us(const Step& s) {
   const ModelConstants& mc = model_constants();
   const double e = (double)dtype_size(s.d.dtype);
+  if (s.is_merge)
+    return e * 2.0 * (double)s.mg.I * (double)s.mg.O / (mc.merge_tbps * 1e12) * 1e6 + mc.merge_fix_us + mc.launch_us;
   if (s.nsk > 0) {
     double us = mc.stream_fix_us + mc.launch_us;
     double outs = 0;
