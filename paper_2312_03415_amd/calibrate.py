@@ -8,8 +8,9 @@ events around a batch of calls on one stream, rotating operand sets so that the 
 Cache does not serve them, on problems long enough that the GPU and not the caller's launch rate
 sets the time.  Per tile shape and operand layout two contraction lengths give the
 time per K tile and the fixed cost of a round of workgroups; a third run with an addend gives the
-fixed cost with D; short second segments give the pipelined kernel's slow-tile cost; the streaming
-kernel is timed on both orientations of the big operand; a tiny problem gives the launch cost.
+fixed cost with D; the streaming kernel is timed on both orientations of the big operand; the
+W + AB kernel on two sizes through the merged forward's own step timing; a tiny problem gives the
+launch cost.
 """
 import argparse
 import os
@@ -101,11 +102,28 @@ def main():
             tiles[fam][cfg] = dict(tk=tk, fix=sum(fix) / 3.0, fix_d=fix_d)
             print(fam, NAMES[cfg], [round(v, 3) for v in tk], round(tiles[fam][cfg]["fix"], 2), round(fix_d, 2), flush=True)
 
-    # slow-tile cost of the pipelined kernel: a 64-wide second segment = one more (slow) K tile per round
-    t0 = gemm_time(bf, "NT", 8192, 4096, 4096, 7)
-    t1 = gemm_time(bf, "NT", 8192, 4096, 4096, 7, K2=64)
-    slow = max((t1 - t0) / 2.0 - tiles[0][7]["tk"][1], 0.0)
-    print("slow_tile_us", round(slow, 2), flush=True)
+    slow = 0.0  # partial and second-segment K tiles cost what any other K tile costs
+
+    # W + AB kernel: per-step event times of the merged forward on two sizes -> rate and fixed cost
+    def merge_time(i, o, r=32, n=256, sets=4):
+        X = torch.randn(n, i, device="cuda").to(bf)
+        As = [torch.randn(i, r, device="cuda").to(bf) for _ in range(sets)]
+        Bs = [torch.randn(r, o, device="cuda").to(bf) for _ in range(sets)]
+        Ws = [torch.randn(i, o, device="cuda").to(bf) for _ in range(sets)]
+        Yb = torch.empty(n, o, device="cuda", dtype=bf)
+        wss = [rl.new_workspace(2, -1, n, i, o, r, rl.RL_BF16) for _ in range(sets)]
+        rl.runlora_profile_enable(4096)
+        for k in range(20):
+            rl.runlora_forward(2, X, Ws[k % sets], As[k % sets], Bs[k % sets], Yb, rl.new_saved(), workspace=wss[k % sets])
+        torch.cuda.synchronize()
+        rec = rl.runlora_profile_collect(4096)
+        rl.runlora_profile_disable()
+        m = sorted(x["us"] for x in rec[8:] if "W + A B" in x["what"])
+        return m[len(m) // 2]
+    tm_b, tm_s = merge_time(8192, 8192), merge_time(4096, 4096)
+    merge_tbps = 2.0 * 2.0 * (8192.0 * 8192 - 4096.0 * 4096) / (tm_b - tm_s) / 1e6
+    merge_fix = max(tm_s - 2.0 * 2.0 * 4096 * 4096 / merge_tbps / 1e6 - launch, 0.0)
+    print("merge_tbps", round(merge_tbps, 2), "fix", round(merge_fix, 2), flush=True)
 
     # streaming kernel: two sizes per orientation -> rate and fixed cost
     def stream(layout, M, K, sets):
@@ -139,7 +157,7 @@ def main():
             rows.append("           %s,  // %s" % (row(t), NAMES[cfg]))
         lines.append("       {\n" + "\n".join(rows) + "\n       }")
     body = ",\n".join(lines)
-    text = open(args.out).read()
+    text = open(os.path.join(HERE, "csrc", "model_constants.hpp")).read()  # keep the struct definitions
     head = text[:text.index("inline const ModelConstants& model_constants()")]
     out = head + """inline const ModelConstants& model_constants() {
   static const ModelConstants c = {
@@ -150,12 +168,14 @@ def main():
       %.2f,
       %.2f,
       %.2f,
+      %.2f,
+      %.2f,
   };
   return c;
 }
 
 }  // namespace rl
-""" % (body, slow, rates[0], rates[1], sum(fixes) / 2.0, reduce_tbps, launch)
+""" % (body, slow, rates[0], rates[1], sum(fixes) / 2.0, reduce_tbps, launch, merge_tbps, merge_fix)
     with open(args.out, "w") as fh:
         fh.write(out)
     print("wrote", args.out)

@@ -45,9 +45,9 @@ static double step_time_us(const Step& s) {
   const ModelConstants& mc = model_constants();
   const double e = (double)dtype_size(s.d.dtype);
   if (s.is_merge)
-    return e * 2.0 * (double)s.mg.I * (double)s.mg.O / (mc.merge_tbps * 1e12) * 1e6 + mc.merge_fix_us + mc.launch_us;
+    return e * 2.0 * (double)s.mg.I * (double)s.mg.O / (mc.merge_tbps * 1e12) * 1e6 + mc.merge_fix_us;
   if (s.nsk > 0) {
-    double us = mc.stream_fix_us + mc.launch_us;
+    double us = mc.stream_fix_us;  // the measured intercepts already hold the cost of the launch itself
     double outs = 0;
     for (int w = 0; w < s.nsk; ++w) {
       const SkinnyDesc& k = s.sk[w];
@@ -79,8 +79,7 @@ static double step_time_us(const Step& s) {
   double slow = 0;
   (void)kt1;  // the matrix-core kernel runs partial and second-segment K tiles at the speed of any other
   const bool addend = d.D != nullptr && p.splits == 1;
-  double us = rounds * (ktiles * tm.tk_us[lay] * share + (addend ? tm.tfix_d_us : tm.tfix_us) + slow * mc.slow_tile_us) +
-              mc.launch_us;
+  double us = rounds * (ktiles * tm.tk_us[lay] * share + (addend ? tm.tfix_d_us : tm.tfix_us) + slow * mc.slow_tile_us);
   if (p.splits > 1)
     us += (double)d.M * d.N * (4.0 * (p.splits + 1) + (d.D ? e : 0.0) + e) / (mc.reduce_tbps * 1e12) * 1e6 + mc.launch_us;
   return us;
@@ -149,6 +148,14 @@ extern "C" int runlora_select_by(int criterion, int64_t n, int64_t i, int64_t o,
   for (int v = 1; v <= bmax; ++v) {
     double c = criterion == 0 ? (double)table1_flops(1, v, n, i, o, r) : model_time_us(1, v, L);
     if (v == 1 || c < cb) { cb = c; bb = v; }
+  }
+  // The default chain (keeps XA, no fusion) is a legal pair too; under the time criterion it is
+  // returned when the model says it beats the best RunLoRA pair (large r at few tokens, where the
+  // recomputation of XA in Algorithms 1 and 5 is not free).  Table 1 does not list it, so the FLOP
+  // criterion never returns it.
+  if (criterion == 1) {
+    const double c0 = model_time_us(0, 0, L) + model_time_us(1, 0, L);
+    if (c0 < cf + cb) { bf = 0; bb = 0; }
   }
   *fwd = bf;
   *bwd = bb;

@@ -72,7 +72,7 @@ def test_select_time_model_returns_legal_pairs():
     for n in (128, 1024, 8192, 16384):
         for r in (8, 64, 256):
             f, b = rl.runlora_select(n, 4096, 4096, r, rl.RL_F16)
-            assert f in (1, 2) and b in (1, 2, 3, 4, 5)
+            assert (f in (1, 2) and b in (1, 2, 3, 4, 5)) or (f, b) == (0, 0)
             assert rl.runlora_model_time_us(0, f, n, 4096, 4096, r, rl.RL_F16) > 0
     assert rl.runlora_model_time_us(0, 7, 128, 64, 64, 8, rl.RL_F16) < 0
     f, b = ctypes.c_int(), ctypes.c_int()
