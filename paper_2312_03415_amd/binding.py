@@ -86,6 +86,10 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(
             f"{LIB_PATH} not found: build it with `python -m paper_2312_03415_amd.build` (no CPU fallback exists)")
+    # torch ships its own copy of the HIP runtime; importing it first makes the library's dependency
+    # resolve to that copy, so that both sides share one runtime (and one view of the device) whatever
+    # the caller's import order
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     tp, sp, op = ctypes.POINTER(rl_tensor_t), ctypes.POINTER(rl_saved_t), ctypes.POINTER(rl_opts_t)
     i64, ci, ip = ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_int)

@@ -42,7 +42,11 @@ struct GemmPlan {
   int nbm = 1, nbn = 1;
   int splits = 1;            // > 1: fp32 partials + fixed-order reduce
   int tiles_per_split = 1;
-  size_t partial_bytes = 0;  // scratch needed when splits > 1
+  size_t partial_bytes = 0;  // scratch needed when splits > 1 (or by the tail launch)
+  // > 0: the output columns [tail_n0, N) are a launch of their own, planned by gemm_plan on that
+  // sub-problem (a few tiles with the contraction split), so that the main launch is whole rounds of
+  // one tile per compute unit instead of ending on a mostly idle round
+  int64_t tail_n0 = 0;
 };
 
 // Tile shape and K split for a problem; depends on shapes and dtype only (never on pointers), so

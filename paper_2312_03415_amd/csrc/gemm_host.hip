@@ -62,6 +62,23 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   p.splits = (ktiles + p.tiles_per_split - 1) / p.tiles_per_split;  // no empty slice
   if (p.splits < 1) p.splits = 1;
   p.partial_bytes = p.splits > 1 ? (size_t)p.splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+  // Tile quantisation: with one 256x256 tile per compute unit and round, a grid of e.g. 32 x 43 tiles
+  // ends on a round that is 3/8 full.  If whole tile columns can be cut off such that the rest is an
+  // exact number of rounds and the cut-off part is small enough to be split along K, run that part
+  // as a launch of its own (half a round with the contraction in two, plus its reduce).
+  if (force_cfg < 0 && force_splits <= 0 && p.cfg == CFG_MC4 && p.splits == 1 && tiles > 256 && ktiles >= 64) {
+    for (int t = p.nbn - 1; t >= 1 && t >= p.nbn - 16; --t) {
+      const int64_t main_tiles = (int64_t)p.nbm * t, tail_tiles = (int64_t)p.nbm * (p.nbn - t);
+      if (tail_tiles > 128) break;
+      if (main_tiles % 256 != 0 || tail_tiles < 32) continue;
+      const GemmPlan tail = gemm_plan(dtype, M, N - (int64_t)t * p.bn, K0, K1);
+      if (tail.splits < 2) break;
+      p.tail_n0 = (int64_t)t * p.bn;
+      p.nbn = t;
+      p.partial_bytes = tail.partial_bytes;
+      break;
+    }
+  }
   return p;
 }
 
@@ -73,6 +90,28 @@ GemmPlan gemm_plan_int4(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1)
 
 hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream) {
   if (d.M <= 0 || d.N <= 0) return hipErrorInvalidValue;
+  if (plan.tail_n0 > 0) {
+    // columns [0, tail_n0) with this plan, columns [tail_n0, N) as their own problem
+    if (plan.tail_n0 >= d.N) return hipErrorInvalidValue;
+    const size_t esz = d.dtype == DT_F32 ? 4 : 2;
+    GemmDesc dm = d, dt = d;
+    GemmPlan pm = plan;
+    pm.tail_n0 = 0;
+    pm.partial_bytes = 0;
+    dm.N = plan.tail_n0;
+    dt.N = d.N - plan.tail_n0;
+    for (int s = 0; s < d.nseg; ++s) {
+      const int64_t off = d.b_kcontig ? plan.tail_n0 * d.ldb[s] : plan.tail_n0;
+      dt.B[s] = static_cast<const char*>(d.B[s]) + (size_t)off * esz;
+    }
+    dt.C = static_cast<char*>(d.C) + (size_t)plan.tail_n0 * esz;
+    if (d.D) dt.D = static_cast<const char*>(d.D) + (size_t)plan.tail_n0 * esz;
+    hipError_t e = gemm_run(dm, pm, nullptr, stream);
+    if (e != hipSuccess) return e;
+    const GemmPlan pt = gemm_plan(d.dtype, d.M, dt.N, d.K[0], d.nseg > 1 ? d.K[1] : 0);
+    if (pt.tail_n0 > 0 || pt.partial_bytes > plan.partial_bytes) return hipErrorInvalidValue;
+    return gemm_run(dt, pt, scratch, stream);
+  }
   if (plan.splits > 1 && scratch == nullptr) return hipErrorInvalidValue;
   int cfg = plan.cfg;
   if (d.Bscale != nullptr && cfg != CFG_BIG && cfg != CFG_MID) return hipErrorInvalidValue;  // see gemm_plan_int4

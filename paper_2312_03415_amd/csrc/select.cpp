@@ -35,31 +35,21 @@ int64_t table1_flops(int is_bwd, int v, int64_t n, int64_t i, int64_t o, int64_t
   }
 }
 
-// Time of one launch.
-//  Streaming kernel: bytes / measured streaming rate + a fixed cost (+ the partials' round trip
-//  and the reduce launch when the contraction is also split over workgroups).
-//  Tile GEMM: workgroups run in rounds of (compute units x resident workgroups); a round costs
-//  (K tiles x measured time per K tile) + a fixed prologue/epilogue; a split contraction adds the
-//  write and re-read of the fp32 partials and the reduce launch.
-static double step_time_us(const Step& s) {
+// Tile GEMM: workgroups run in rounds of (compute units x resident workgroups); a round costs
+// (K tiles x measured time per K tile) + a fixed prologue/epilogue; a split contraction adds the
+// write and re-read of the fp32 partials and the reduce launch; a plan with cut-off tail columns is
+// two launches.
+static double gemm_time_us(const GemmDesc& d, const GemmPlan& p) {
   const ModelConstants& mc = model_constants();
-  const double e = (double)dtype_size(s.d.dtype);
-  if (s.is_merge)
-    return e * 2.0 * (double)s.mg.I * (double)s.mg.O / (mc.merge_tbps * 1e12) * 1e6 + mc.merge_fix_us;
-  if (s.nsk > 0) {
-    double us = mc.stream_fix_us;  // the measured intercepts already hold the cost of the launch itself
-    double outs = 0;
-    for (int w = 0; w < s.nsk; ++w) {
-      const SkinnyDesc& k = s.sk[w];
-      const double bytes = e * ((double)k.M * k.K + (double)k.K * k.N + (double)k.M * k.N);
-      us += bytes / (mc.stream_tbps[k.a_strided ? 1 : 0] * 1e12) * 1e6;
-      outs += (double)k.M * k.N;
-    }
-    if (s.skplan.splits > 1) us += 4.0 * outs * (s.skplan.splits + 1) / (mc.reduce_tbps * 1e12) * 1e6 + mc.stream_fix_us + mc.launch_us;
-    return us;
+  const double e = (double)dtype_size(d.dtype);
+  if (p.tail_n0 > 0) {
+    GemmDesc dm = d, dt = d;
+    GemmPlan pm = p;
+    pm.tail_n0 = 0;
+    dm.N = p.tail_n0;
+    dt.N = d.N - p.tail_n0;
+    return gemm_time_us(dm, pm) + gemm_time_us(dt, gemm_plan(d.dtype, d.M, dt.N, d.K[0], d.nseg > 1 ? d.K[1] : 0));
   }
-  const GemmDesc& d = s.d;
-  const GemmPlan& p = s.plan;
   const TileModel& tm = mc.tile[d.dtype == DT_F32 ? 1 : 0][p.cfg];
   const int lay = d.a_strided ? 2 : (d.b_kcontig ? 1 : 0);
   const double wgs = (double)p.nbm * p.nbn * p.splits;
@@ -83,6 +73,32 @@ static double step_time_us(const Step& s) {
   if (p.splits > 1)
     us += (double)d.M * d.N * (4.0 * (p.splits + 1) + (d.D ? e : 0.0) + e) / (mc.reduce_tbps * 1e12) * 1e6 + mc.launch_us;
   return us;
+}
+
+// Time of one launch.
+//  Streaming kernel: bytes / measured streaming rate + a fixed cost (+ the partials' round trip
+//  and the reduce launch when the contraction is also split over workgroups).
+//  Tile GEMM: workgroups run in rounds of (compute units x resident workgroups); a round costs
+//  (K tiles x measured time per K tile) + a fixed prologue/epilogue; a split contraction adds the
+//  write and re-read of the fp32 partials and the reduce launch.
+static double step_time_us(const Step& s) {
+  const ModelConstants& mc = model_constants();
+  const double e = (double)dtype_size(s.d.dtype);
+  if (s.is_merge)
+    return e * 2.0 * (double)s.mg.I * (double)s.mg.O / (mc.merge_tbps * 1e12) * 1e6 + mc.merge_fix_us;
+  if (s.nsk > 0) {
+    double us = mc.stream_fix_us;  // the measured intercepts already hold the cost of the launch itself
+    double outs = 0;
+    for (int w = 0; w < s.nsk; ++w) {
+      const SkinnyDesc& k = s.sk[w];
+      const double bytes = e * ((double)k.M * k.K + (double)k.K * k.N + (double)k.M * k.N);
+      us += bytes / (mc.stream_tbps[k.a_strided ? 1 : 0] * 1e12) * 1e6;
+      outs += (double)k.M * k.N;
+    }
+    if (s.skplan.splits > 1) us += 4.0 * outs * (s.skplan.splits + 1) / (mc.reduce_tbps * 1e12) * 1e6 + mc.stream_fix_us + mc.launch_us;
+    return us;
+  }
+  return gemm_time_us(s.d, s.plan);
 }
 
 double model_time_us(int is_bwd, int variant, const LayerDims& L) {

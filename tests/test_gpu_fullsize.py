@@ -53,7 +53,7 @@ def test_opt13b_mlp_layer(which):
     check_layer(L, sorted({sel, (0, 0), (2, 5), (1, 1)}))
 
 
-@pytest.mark.parametrize("name", ["q", "down"])
+@pytest.mark.parametrize("name", ["q", "gate", "down"])
 def test_llama7b_layer(name):
     L = [x for x in synth.config_llama7b(32, "bf16") if x.name == name][0]
     sel = rl.runlora_select(L.n, L.i, L.o, L.r, rl.RL_BF16)
