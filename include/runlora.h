@@ -8,6 +8,11 @@
  * in each of the algebraically equivalent computation graphs the paper lists, plus the selector
  * that picks a (forward, backward) pair per shape.
  *
+ * Beyond the paper's layer (which has neither): an optional LoRA scale s and an optional frozen
+ * bias b of the base layer, Y = X W + 1 b^T + s (X A) B; the gradients of Eq. 3 then carry the
+ * factor s on their adapter terms (dA = s X^T dY B^T, dB = s A^T X^T dY, dX = dY W^T + s dY B^T A^T)
+ * and b, being frozen like W, has none.  See rl_opts_t.
+ *
  * Notation (Table 1 caption): n = b*s tokens, i = d_in, o = d_out, r = LoRA rank.
  * All tensors are dense row-major DEVICE buffers described by rl_tensor_t:
  *     X [n,i]  W [i,o]  A [i,r]  B [r,o]  Y,dY [n,o]  dX [n,i]  dA [i,r]  dB [r,o]
@@ -28,8 +33,8 @@
  *     RL_INT4_G64 is allowed for W only (see rl_tensor_t), with RL_F16 / RL_BF16 activations: W is
  *     dequantised inside the GEMMs that read it (q * scale, rounded to the activation type) and
  *     never written out densely.  The graphs that need W + AB as a matrix (RL_FWD2, RL_BWD4,
- *     RL_BWD5) return RL_ERR_UNSUPPORTED for an int4 W.  Accumulation is fp32 throughout; each
- *     result is rounded once (nearest even) to the storage type.
+ *     RL_BWD5, RL_BWD7, RL_BWD8) return RL_ERR_UNSUPPORTED for an int4 W.  Accumulation is fp32
+ *     throughout; each result is rounded once (nearest even) to the storage type.
  *   - Alignment: data pointers 16-byte aligned; ld (elements between rows) >= cols and a
  *     multiple of 8 (16-bit types) or 4 (fp32); i, o and r multiples of 8 (16-bit) or 4 (fp32);
  *     n is arbitrary (>= 1).  Anything else returns RL_ERR_ALIGN / RL_ERR_SHAPE.
@@ -78,8 +83,10 @@ typedef enum {
 } rl_fwd_variant_t;
 
 /*
- * Backward computation graphs.  1..5 are Algorithms 1-5 of Section 2 (backward1..backward5).
- * Where an algorithm ends with dX = dY W^T + Z1 A^T the two products run as one GEMM over the
+ * Backward computation graphs.  1..5 are Algorithms 1-5 of Section 2 (backward1..backward5); 6..8
+ * are items 6-8 of the section's list of the eight bracketings of Eq. 3, which the paper leaves out
+ * because Table 1 never ranks them first (the selector never returns them either).
+ * Where a graph ends with dX = dY W^T + Z1 A^T the two products run as one GEMM over the
  * concatenated contraction [dY|Z1] [W^T;A^T].
  */
 typedef enum {
@@ -89,7 +96,10 @@ typedef enum {
   RL_BWD2 = 2,
   RL_BWD3 = 3,
   RL_BWD4 = 4,
-  RL_BWD5 = 5
+  RL_BWD5 = 5,
+  RL_BWD6 = 6, /* dA = (X^T dY) B^T;  dB = (A^T X^T) dY;  dX = dY W^T + (dY B^T) A^T */
+  RL_BWD7 = 7, /* dA = (X^T dY) B^T;  dB = (A^T X^T) dY;  dX = dY (W^T + B^T A^T)    */
+  RL_BWD8 = 8  /* dA = X^T (dY B^T);  dB = A^T (X^T dY);  dX = dY (W^T + B^T A^T)    */
 } rl_bwd_variant_t;
 
 /*
@@ -112,11 +122,19 @@ typedef struct {
 
 /*
  * What a forward leaves for its backward (Section 2: RunLoRA forwards keep X but not XA).
- * Filled by runlora_forward; read by runlora_backward.  X is borrowed: the caller keeps the
- * buffer alive and unchanged until the backward has run.
+ * Zero the struct, set the fields named below if wanted, and pass it to runlora_forward, which
+ * fills the rest; runlora_backward reads it.  X is borrowed: the caller keeps the buffer alive and
+ * unchanged until the backward has run.
  *   T  caller-provided [n,r] buffer (ldt elements per row, same dtype as X).  Set T/ldt BEFORE
- *      calling runlora_forward(RL_FWD_DEFAULT, ...), which fills it with XA; other variants
+ *      calling runlora_forward(RL_FWD_DEFAULT, ...), which fills it with s XA; other variants
  *      ignore it and set it to NULL.
+ *   M  optional caller-provided [i,o] buffer (ldm elements per row, same dtype as X).  Set M/ldm
+ *      BEFORE calling runlora_forward(RL_FWD2, ...): W + s AB is then formed there instead of in
+ *      the workspace and left for the backward, and RL_BWD4 / 5 / 7 / 8 read it instead of forming
+ *      it again (one pass over W saved, i*o elements held meanwhile).  Valid only while W, A and B
+ *      are what the forward saw.  NULL: nothing is kept.  Other forward variants set it to NULL.
+ *   scale  the forward's LoRA scale (rl_opts_t.scale), applied again by the backward.
+ * runlora_saved_bytes() tells how many bytes a forward keeps besides X.
  */
 typedef struct {
   int32_t fwd_variant, dtype;
@@ -125,17 +143,30 @@ typedef struct {
   int64_t ldx;
   void* T;
   int64_t ldt;
+  void* M;
+  int64_t ldm;
+  float scale;
 } rl_saved_t;
 
 /*
- * Per-call options.  workspace is device scratch of at least runlora_workspace_bytes() bytes for
- * the variant and shape of the call, 256-byte aligned; its contents are undefined afterwards.
- * Two calls that share a workspace must be ordered on one stream.
+ * Per-call options (zero the struct first).  workspace is device scratch of at least
+ * runlora_workspace_bytes() bytes for the variant and shape of the call, 256-byte aligned; its
+ * contents are undefined afterwards.  Two calls that share a workspace must be ordered on one
+ * stream.
+ *   scale  runlora_forward only: the LoRA scale s of Y = XW + s (XA) B (alpha / r in common use);
+ *          0 means 1, the paper's layer.  The forward records it in *saved and the backward takes
+ *          it from there.  It is applied in fp32 where a rank-r factor or W + s AB is formed
+ *          (s XA, s dY B^T, s Z2 B^T, s A^T Z2), before that factor is rounded to the storage type.
+ *   bias   runlora_forward only: device pointer to the base layer's frozen bias, o elements of
+ *          the activation dtype, 16-byte aligned, added in fp32 by the GEMM that writes Y; NULL =
+ *          no bias.  Ignored by runlora_backward and runlora_gemm (rl_gemm_t has its own).
  */
 typedef struct {
   void* stream;
   void* workspace;
   size_t workspace_bytes;
+  float scale;
+  const void* bias;
 } rl_opts_t;
 
 /*
@@ -166,7 +197,9 @@ int runlora_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved
 int runlora_select(int64_t n_tokens, int64_t d_in, int64_t d_out, int64_t r, int dtype,
                    int* fwd_variant, int* bwd_variant);
 
-/* Same, with the criterion explicit: 0 = Table 1 FLOPs (ties -> lower id), 1 = time model. */
+/* Same, with the criterion explicit: 0 = Table 1 FLOPs (ties -> lower id), 1 = time model,
+ * 2 = time model for a caller that lets forward2 keep W + AB for the backward (rl_saved_t.M):
+ * pairs of forward2 with backward4 / 5 are then priced without the second W + AB pass. */
 int runlora_select_by(int criterion, int64_t n_tokens, int64_t d_in, int64_t d_out, int64_t r,
                       int dtype, int* fwd_variant, int* bwd_variant);
 
@@ -181,6 +214,13 @@ int64_t runlora_flops(int is_bwd, int variant, int64_t n, int64_t i, int64_t o, 
  * negative for an unknown variant. */
 double runlora_model_time_us(int is_bwd, int variant, int64_t n, int64_t i, int64_t o, int64_t r,
                              int dtype);
+
+/*
+ * Bytes a forward variant keeps for its backward besides X itself: n*r elements for the default
+ * chain's T = XA, nothing for forward1 / forward2 (the memory saving of Section 2), plus i*o
+ * elements if forward2 is asked to keep W + AB (keep_merged != 0).  0 for an unknown variant.
+ */
+size_t runlora_saved_bytes(int fwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype, int keep_merged);
 
 /* Scratch bytes needed by a forward variant (bwd < 0), a backward variant (fwd < 0), or the
  * larger of the two, for a dense W of the layer dtype.  0 for an unknown variant or dtype. */
@@ -207,6 +247,9 @@ size_t runlora_workspace_bytes_w(int fwd, int bwd, int64_t n, int64_t i, int64_t
  *   trans_out  1 = store C transposed, as [N,M] with ldc >= M (streaming kernel only); else 0
  *   splits     0 = heuristic, n > 0 = split the contraction n ways (fp32 partials in the
  *              workspace, summed in a fixed order)
+ *   alpha      C = alpha * (the products) + D + bias; 0 means 1
+ *   bias       NULL, or a row vector of N elements added to every row (16-byte aligned; not with
+ *              the streaming kernel)
  * Same dtype / alignment rules as the layer calls (M arbitrary when A is [M,K]; every other
  * dimension a multiple of 8, or 4 for fp32).  Workspace: runlora_gemm_workspace_bytes().
  */
@@ -217,6 +260,8 @@ typedef struct {
   void* C;
   int64_t lda, ldb, lda2, ldb2, ldc, ldd;
   int32_t trans_out;
+  float alpha;
+  const void* bias;
 } rl_gemm_t;
 int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts);
 size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g);

@@ -2,7 +2,8 @@
 
 Only tests, the smoke check and the bench's cpu_baseline leg may import this package.  It
 shares nothing with the HIP path and never imports it.  The arithmetic lives in
-runlora_oracle.c (plain C, naive loops); this module only marshals numpy arrays into it.
+runlora_oracle.c (plain C, naive loops); this module marshals numpy arrays into it (the scaled
+layer at the end reduces to the paper's layer by a substitution, written out there).
 
 Shapes (paper's notation, Section 2): X [n,i], W [i,o], A [i,r], B [r,o], Y/dY [n,o],
 dX [n,i], dA [i,r], dB [r,o]; everything float64, C-contiguous.
@@ -156,4 +157,29 @@ def reference_rows(Xrows, dYrows, W, A, B):
     o, r = W.shape[1], A.shape[1]
     Y, dX = np.empty((rows, o)), np.empty((rows, i))
     lib().orc_reference_rows(rows, i, o, r, _p(Xrows), _p(dYrows), _p(W), _p(A), _p(B), _p(Y), _p(dX))
+    return Y, dX
+
+
+# ---- the layer with a LoRA scale and a frozen bias (not in the paper, which has s = 1, no bias) ----
+# Y = XW + 1 b^T + s (XA) B is Eq. 1 evaluated on B' = sB, plus the bias row.  Eq. 3 on B' then gives
+# dX and dA of the scaled layer as they are, and dB = s dB' by the chain rule through B' = sB; the
+# bias is frozen like W and has no gradient.
+
+def scaled_forward(X, W, A, B, scale=1.0, bias=None):
+    Y = reference_forward(X, W, A, float(scale) * _f64(B))
+    if bias is not None:
+        Y = Y + _f64(bias).reshape(1, -1)
+    return Y
+
+
+def scaled_backward(X, W, A, B, dY, scale=1.0):
+    dX, dA, dBp = reference_backward(X, W, A, float(scale) * _f64(B), dY)
+    return dX, dA, float(scale) * dBp
+
+
+def scaled_rows(Xrows, dYrows, W, A, B, scale=1.0, bias=None):
+    """Y and dX of the scaled layer on a subset of token rows."""
+    Y, dX = reference_rows(Xrows, dYrows, W, A, float(scale) * _f64(B))
+    if bias is not None:
+        Y = Y + _f64(bias).reshape(1, -1)
     return Y, dX

@@ -19,9 +19,10 @@ LIB_PATH = os.path.join(HERE, "librunlora.so")
 
 RL_F32, RL_F16, RL_BF16, RL_INT4_G64 = 0, 1, 2, 3
 FWD_DEFAULT, FWD1, FWD2 = 0, 1, 2
-BWD_DEFAULT, BWD1, BWD2, BWD3, BWD4, BWD5 = 0, 1, 2, 3, 4, 5
+BWD_DEFAULT, BWD1, BWD2, BWD3, BWD4, BWD5, BWD6, BWD7, BWD8 = 0, 1, 2, 3, 4, 5, 6, 7, 8
 FWD_VARIANTS = (FWD_DEFAULT, FWD1, FWD2)
-BWD_VARIANTS = (BWD_DEFAULT, BWD1, BWD2, BWD3, BWD4, BWD5)
+BWD_VARIANTS = (BWD_DEFAULT, BWD1, BWD2, BWD3, BWD4, BWD5, BWD6, BWD7, BWD8)
+BWD_MERGED = (BWD4, BWD5, BWD7, BWD8)  # the graphs that read W + AB as a matrix
 
 RL_OK = 0
 RL_ERR_NULL, RL_ERR_SHAPE, RL_ERR_DTYPE, RL_ERR_VARIANT, RL_ERR_SAVED_MISMATCH = -1, -2, -3, -4, -5
@@ -29,7 +30,8 @@ RL_ERR_ALIGN, RL_ERR_ALIAS, RL_ERR_WORKSPACE, RL_ERR_UNSUPPORTED, RL_ERR_HIP = -
 
 EXPORTS = (
     "runlora_forward", "runlora_backward", "runlora_select", "runlora_select_by", "runlora_flops",
-    "runlora_model_time_us", "runlora_workspace_bytes", "runlora_workspace_bytes_w", "runlora_strerror", "runlora_last_hip_error",
+    "runlora_model_time_us", "runlora_workspace_bytes", "runlora_workspace_bytes_w", "runlora_saved_bytes",
+    "runlora_strerror", "runlora_last_hip_error",
     "runlora_version", "runlora_gemm", "runlora_gemm_workspace_bytes",
     "runlora_profile_enable", "runlora_profile_collect", "runlora_profile_disable", "runlora_probe_mfma",
 )
@@ -45,11 +47,13 @@ class rl_saved_t(ctypes.Structure):
     _fields_ = [("fwd_variant", ctypes.c_int32), ("dtype", ctypes.c_int32), ("n", ctypes.c_int64),
                 ("i", ctypes.c_int64), ("o", ctypes.c_int64), ("r", ctypes.c_int64),
                 ("X", ctypes.c_void_p), ("ldx", ctypes.c_int64), ("T", ctypes.c_void_p),
-                ("ldt", ctypes.c_int64)]
+                ("ldt", ctypes.c_int64), ("M", ctypes.c_void_p), ("ldm", ctypes.c_int64),
+                ("scale", ctypes.c_float)]
 
 
 class rl_opts_t(ctypes.Structure):
-    _fields_ = [("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+    _fields_ = [("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("scale", ctypes.c_float), ("bias", ctypes.c_void_p)]
 
 
 class rl_gemm_t(ctypes.Structure):
@@ -59,7 +63,8 @@ class rl_gemm_t(ctypes.Structure):
                 ("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("A2", ctypes.c_void_p), ("B2", ctypes.c_void_p),
                 ("D", ctypes.c_void_p), ("C", ctypes.c_void_p),
                 ("lda", ctypes.c_int64), ("ldb", ctypes.c_int64), ("lda2", ctypes.c_int64), ("ldb2", ctypes.c_int64),
-                ("ldc", ctypes.c_int64), ("ldd", ctypes.c_int64), ("trans_out", ctypes.c_int32)]
+                ("ldc", ctypes.c_int64), ("ldd", ctypes.c_int64), ("trans_out", ctypes.c_int32),
+                ("alpha", ctypes.c_float), ("bias", ctypes.c_void_p)]
 
 
 class rl_step_time_t(ctypes.Structure):
@@ -109,6 +114,8 @@ def lib():
     L.runlora_workspace_bytes.restype = ctypes.c_size_t
     L.runlora_workspace_bytes_w.argtypes = [ci, ci, i64, i64, i64, i64, ci, ci]
     L.runlora_workspace_bytes_w.restype = ctypes.c_size_t
+    L.runlora_saved_bytes.argtypes = [ci, i64, i64, i64, i64, ci, ci]
+    L.runlora_saved_bytes.restype = ctypes.c_size_t
     L.runlora_strerror.argtypes = [ci]
     L.runlora_strerror.restype = ctypes.c_char_p
     L.runlora_last_hip_error.argtypes = []
@@ -184,24 +191,31 @@ def tensor_desc(t):
     return rl_tensor_t(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), dtype_code(t.dtype), None, 0)
 
 
-def _opts(workspace, stream):
+def _opts(workspace, stream, scale=None, bias=None):
     import torch
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    return rl_opts_t(stream, ws_ptr, ws_bytes)
+    if bias is not None and (bias.dim() != 1 or bias.stride(0) != 1):
+        raise ValueError("bias must be a contiguous 1-D tensor")
+    return rl_opts_t(stream, ws_ptr, ws_bytes, 0.0 if scale is None else float(scale),
+                     bias.data_ptr() if bias is not None else None)
 
 
 def _ref(desc):
     return ctypes.byref(desc) if desc is not None else None
 
 
-def runlora_forward(variant, X, W, A, B, Y, saved, workspace=None, stream=None):
-    """Y = XW + (XA)B in forward graph `variant`; fills `saved` (rl_saved_t).  For FWD_DEFAULT set
-    saved.T / saved.ldt to an [n,r] buffer first (see new_saved)."""
+def runlora_forward(variant, X, W, A, B, Y, saved, workspace=None, stream=None, scale=None, bias=None):
+    """Y = XW (+ bias) + scale (XA)B in forward graph `variant`; fills `saved` (rl_saved_t).  For
+    FWD_DEFAULT set saved.T / saved.ldt to an [n,r] buffer first, for FWD2 optionally saved.M /
+    saved.ldm to an [i,o] buffer that keeps W + scale AB for the backward (see new_saved).
+    scale None = 1 (the paper's layer); bias: 1-D tensor [o] of the activation dtype or None."""
+    if bias is not None and (bias.dtype != X.dtype or bias.numel() != Y.shape[1]):
+        raise ValueError("bias must have d_out elements of the activation dtype")
     dx, dw, da, db, dy = (tensor_desc(t) for t in (X, W, A, B, Y))
-    o = _opts(workspace, stream)
+    o = _opts(workspace, stream, scale, bias)
     _check(lib().runlora_forward(variant, _ref(dx), _ref(dw), _ref(da), _ref(db), _ref(dy), ctypes.byref(saved),
                                  ctypes.byref(o)))
     return Y
@@ -219,7 +233,8 @@ def runlora_backward(variant, dY, saved, W, A, B, dX, dA, dB, workspace=None, st
 
 def runlora_select(n_tokens, d_in, d_out, r, dtype, criterion=None):
     """(fwd, bwd) for a layer shape.  criterion None = library default (time model unless
-    RUNLORA_CRITERION=flops), 0 = Table 1 FLOPs, 1 = time model."""
+    RUNLORA_CRITERION=flops), 0 = Table 1 FLOPs, 1 = time model, 2 = time model when forward2 keeps
+    W + AB for the backward."""
     f, b = ctypes.c_int(-1), ctypes.c_int(-1)
     if criterion is None:
         _check(lib().runlora_select(n_tokens, d_in, d_out, r, dtype, ctypes.byref(f), ctypes.byref(b)))
@@ -242,9 +257,15 @@ def runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype, w_dtype=None):
     return int(lib().runlora_workspace_bytes_w(fwd, bwd, n, i, o, r, dtype, w_dtype))
 
 
+def runlora_saved_bytes(fwd, n, i, o, r, dtype, keep_merged=False):
+    """Bytes forward graph `fwd` keeps for the backward besides X."""
+    return int(lib().runlora_saved_bytes(fwd, n, i, o, r, dtype, int(bool(keep_merged))))
+
+
 def runlora_gemm(A, B, C, a_strided=False, b_kcontig=False, A2=None, B2=None, D=None, tile_cfg=-1, splits=0,
-                 workspace=None, stream=None, trans_out=False):
-    """C = op(A) op(B) (+ op(A2) op(B2)) (+ D) through the library's tile GEMM (see runlora.h)."""
+                 workspace=None, stream=None, trans_out=False, alpha=None, bias=None):
+    """C = alpha (op(A) op(B) (+ op(A2) op(B2))) (+ D) (+ bias) through the library's tile GEMM (see
+    runlora.h)."""
     import torch
     M = A.shape[1] if a_strided else A.shape[0]
     K = A.shape[0] if a_strided else A.shape[1]
@@ -256,7 +277,8 @@ def runlora_gemm(A, B, C, a_strided=False, b_kcontig=False, A2=None, B2=None, D=
                   A.data_ptr(), B.data_ptr(), A2.data_ptr() if A2 is not None else None,
                   B2.data_ptr() if B2 is not None else None, D.data_ptr() if D is not None else None, C.data_ptr(),
                   A.stride(0), B.stride(0), A2.stride(0) if A2 is not None else 0,
-                  B2.stride(0) if B2 is not None else 0, C.stride(0), D.stride(0) if D is not None else 0, int(trans_out))
+                  B2.stride(0) if B2 is not None else 0, C.stride(0), D.stride(0) if D is not None else 0, int(trans_out),
+                  0.0 if alpha is None else float(alpha), bias.data_ptr() if bias is not None else None)
     need = int(lib().runlora_gemm_workspace_bytes(ctypes.byref(g)))
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=C.device)
@@ -295,11 +317,16 @@ def runlora_probe_mfma(random_data, device="cuda"):
 
 # ---- conveniences on top of the ABI (device memory only) --------------------------------------
 
-def new_saved(T=None):
+def new_saved(T=None, M=None):
+    """A zeroed rl_saved_t; T: [n,r] buffer for FWD_DEFAULT's XA; M: [i,o] buffer in which FWD2 keeps
+    W + AB for the backward."""
     s = rl_saved_t()
     if T is not None:
         s.T = T.data_ptr()
         s.ldt = T.stride(0)
+    if M is not None:
+        s.M = M.data_ptr()
+        s.ldm = M.stride(0)
     return s
 
 

@@ -198,9 +198,28 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
       overlap(ry, range_of(A->data, i, A->ld, r, esz)) || overlap(ry, range_of(B->data, r, B->ld, o, esz)))
     return RL_ERR_ALIAS;
 
-  LayerDims L{n, i, o, r, dt, w_int4};
+  const float scale = (opts && opts->scale != 0.f) ? opts->scale : 1.f;
+  LayerDims L{n, i, o, r, dt, w_int4, scale};
   FwdOperands op;
   op.X = mat(X); op.W = weight_mat(W, o, w_int4); op.A = mat(A); op.B = mat(B); op.Y = mat(Y);
+  if (opts && opts->bias) {
+    if ((reinterpret_cast<uintptr_t>(opts->bias) & 15) != 0) return RL_ERR_ALIGN;
+    if (overlap(ry, range_of(opts->bias, 1, o, o, esz))) return RL_ERR_ALIAS;
+    op.bias = opts->bias;
+  }
+  if (variant == RL_FWD2 && saved->M) {  // keep W + s AB for the backward in the caller's buffer
+    const int64_t q = dtype == RL_F32 ? 4 : 8;
+    if (saved->ldm < o) return RL_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(saved->M) & 15) != 0 || saved->ldm % q != 0) return RL_ERR_ALIGN;
+    Range rm = range_of(saved->M, i, saved->ldm, o, esz);
+    if (overlap(rm, ry) || overlap(rm, range_of(X->data, n, X->ld, i, esz)) ||
+        overlap(rm, weight_range(W, i, o, esz, w_int4)) || overlap(rm, range_of(A->data, i, A->ld, r, esz)) ||
+        overlap(rm, range_of(B->data, r, B->ld, o, esz)))
+      return RL_ERR_ALIAS;
+    op.M.ptr = saved->M;
+    op.M.ld = saved->ldm;
+    op.keep_M = true;
+  }
   if (variant == RL_FWD_DEFAULT) {
     if (!saved->T) return RL_ERR_NULL;
     const int64_t q = dtype == RL_F32 ? 4 : 8;
@@ -225,7 +244,9 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
   saved->n = n; saved->i = i; saved->o = o; saved->r = r;
   saved->X = X->data;
   saved->ldx = X->ld;
+  saved->scale = scale;
   if (variant != RL_FWD_DEFAULT) { saved->T = nullptr; saved->ldt = 0; }
+  if (variant != RL_FWD2) { saved->M = nullptr; saved->ldm = 0; }
   return RL_OK;
 }
 
@@ -233,7 +254,7 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
                                 const rl_tensor_t* A, const rl_tensor_t* B, rl_tensor_t* dX, rl_tensor_t* dA,
                                 rl_tensor_t* dB, const rl_opts_t* opts) {
   if (!dY || !saved || !W || !A || !B) return RL_ERR_NULL;
-  if (variant < RL_BWD_DEFAULT || variant > RL_BWD5) return RL_ERR_VARIANT;
+  if (variant < RL_BWD_DEFAULT || variant > RL_BWD8) return RL_ERR_VARIANT;
   const int dtype = dY->dtype;
   const int dt = internal_dtype(dtype);
   if (dt < 0) return RL_ERR_DTYPE;
@@ -243,7 +264,8 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   if ((rc = check_dims(n, i, o, r, dtype)) != RL_OK) return rc;
   if ((rc = check_tensor(dY, n, o, dtype)) != RL_OK) return rc;
   if ((rc = check_weight(W, i, o, dtype, &w_int4)) != RL_OK) return rc;
-  if (w_int4 && (variant == RL_BWD4 || variant == RL_BWD5)) return RL_ERR_UNSUPPORTED;
+  if (w_int4 && (variant == RL_BWD4 || variant == RL_BWD5 || variant == RL_BWD7 || variant == RL_BWD8))
+    return RL_ERR_UNSUPPORTED;
   if ((rc = check_tensor(A, i, r, dtype)) != RL_OK) return rc;
   if ((rc = check_tensor(B, r, o, dtype)) != RL_OK) return rc;
   if (dX && (rc = check_tensor(dX, n, i, dtype)) != RL_OK) return rc;
@@ -261,25 +283,34 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
     if (saved->fwd_variant != RL_FWD_DEFAULT || !saved->T || saved->ldt < r) return RL_ERR_SAVED_MISMATCH;
     if ((reinterpret_cast<uintptr_t>(saved->T) & 15) != 0 || saved->ldt % q != 0) return RL_ERR_ALIGN;
   }
+  // W + s AB kept by forward2 serves the graphs that would form it again
+  const bool merged_bwd = variant == RL_BWD4 || variant == RL_BWD5 || variant == RL_BWD7 || variant == RL_BWD8;
+  const bool use_M = merged_bwd && saved->fwd_variant == RL_FWD2 && saved->M != nullptr;
+  if (use_M) {
+    if (saved->ldm < o) return RL_ERR_SAVED_MISMATCH;
+    if ((reinterpret_cast<uintptr_t>(saved->M) & 15) != 0 || saved->ldm % q != 0) return RL_ERR_ALIGN;
+  }
   const size_t esz = dtype_size(dt);
-  Range in[6] = {range_of(dY->data, n, dY->ld, o, esz), range_of(saved->X, n, saved->ldx, i, esz),
+  Range in[7] = {range_of(dY->data, n, dY->ld, o, esz), range_of(saved->X, n, saved->ldx, i, esz),
                  weight_range(W, i, o, esz, w_int4), range_of(A->data, i, A->ld, r, esz),
                  range_of(B->data, r, B->ld, o, esz),
-                 (variant == RL_BWD_DEFAULT) ? range_of(saved->T, n, saved->ldt, r, esz) : Range{nullptr, nullptr}};
+                 (variant == RL_BWD_DEFAULT) ? range_of(saved->T, n, saved->ldt, r, esz) : Range{nullptr, nullptr},
+                 use_M ? range_of(saved->M, i, saved->ldm, o, esz) : Range{nullptr, nullptr}};
   Range outr[3];
   int nout = 0;
   if (dX) outr[nout++] = range_of(dX->data, n, dX->ld, i, esz);
   if (dA) outr[nout++] = range_of(dA->data, i, dA->ld, r, esz);
   if (dB) outr[nout++] = range_of(dB->data, r, dB->ld, o, esz);
   for (int a = 0; a < nout; ++a) {
-    for (int b = 0; b < 6; ++b)
+    for (int b = 0; b < 7; ++b)
       if (in[b].lo && overlap(outr[a], in[b])) return RL_ERR_ALIAS;
     for (int b = a + 1; b < nout; ++b)
       if (overlap(outr[a], outr[b])) return RL_ERR_ALIAS;
   }
 
-  LayerDims L{n, i, o, r, dt, w_int4};
+  LayerDims L{n, i, o, r, dt, w_int4, saved->scale != 0.f ? saved->scale : 1.f};
   BwdOperands op;
+  if (use_M) { op.M.ptr = saved->M; op.M.ld = saved->ldm; op.have_M = true; }
   op.dY = mat(dY); op.W = weight_mat(W, o, w_int4); op.A = mat(A); op.B = mat(B);
   op.X.ptr = saved->X; op.X.ld = saved->ldx;
   op.T.ptr = saved->T; op.T.ld = saved->ldt;
@@ -293,6 +324,18 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   if ((rc = check_workspace(sch, opts)) != RL_OK) return rc;
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
   return run_schedule(sch, ws, stream);
+}
+
+extern "C" size_t runlora_saved_bytes(int fwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype, int keep_merged) {
+  const int dt = internal_dtype(dtype);
+  if (dt < 0 || n < 1 || i < 1 || o < 1 || r < 1) return 0;
+  const size_t e = dtype_size(dt);
+  switch (fwd) {
+    case RL_FWD_DEFAULT: return (size_t)n * (size_t)r * e;  // T = XA
+    case RL_FWD1: return 0;
+    case RL_FWD2: return keep_merged ? (size_t)i * (size_t)o * e : 0;
+    default: return 0;
+  }
 }
 
 extern "C" size_t runlora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype) {
@@ -378,6 +421,12 @@ static int check_gemm(const rl_gemm_t* g, GemmDesc* d, GemmPlan* plan) {
   d->A[0] = g->A; d->B[0] = g->B; d->lda[0] = g->lda; d->ldb[0] = g->ldb; d->K[0] = g->K;
   d->A[1] = g->A2; d->B[1] = g->B2; d->lda[1] = g->lda2; d->ldb[1] = g->ldb2; d->K[1] = g->K2;
   d->C = g->C; d->ldc = g->ldc; d->D = g->D; d->ldd = g->ldd;
+  d->alpha = g->alpha != 0.f ? g->alpha : 1.f;
+  if (g->bias) {
+    if ((reinterpret_cast<uintptr_t>(g->bias) & 15) != 0) return RL_ERR_ALIGN;
+    if (g->tile_cfg == CFG_COUNT) return RL_ERR_UNSUPPORTED;  // the streaming kernel has no bias path
+    d->bias = g->bias;
+  }
   if (g->tile_cfg != CFG_COUNT) *plan = gemm_plan(dt, g->M, g->N, g->K, g->K2, g->tile_cfg, g->splits);
   return RL_OK;
 }
@@ -387,6 +436,7 @@ static void gemm_as_skinny(const rl_gemm_t* g, SkinnyDesc* k, SkinnyPlan* plan) 
   k->lda = g->lda; k->ldb = g->ldb; k->ldc = g->ldc;
   k->M = g->M; k->N = g->N; k->K = g->K;
   k->a_strided = g->a_strided; k->b_kcontig = g->b_kcontig; k->trans_out = g->trans_out;
+  k->alpha = g->alpha != 0.f ? g->alpha : 1.f;
   *plan = skinny_plan(internal_dtype(g->dtype), 1, k);
   if (g->splits > 0) {
     plan->splits = g->splits;

@@ -27,6 +27,9 @@ struct GemmDesc {
   // [rows/64, ldbs]; nullptr = dense.  16-bit types, generic engine only.
   const void* Bscale = nullptr;
   int64_t ldbs = 0;
+  // C = alpha * (sum of the products) + D + bias;  bias: row vector [N] of the dtype, or nullptr
+  float alpha = 1.f;
+  const void* bias = nullptr;
 };
 
 enum TileCfg {
@@ -70,6 +73,7 @@ struct SkinnyDesc {
   int64_t lda = 0, ldb = 0, ldc = 0;
   int64_t M = 0, N = 0, K = 0;
   int a_strided = 0, b_kcontig = 0, trans_out = 0;
+  float alpha = 1.f;  // C = alpha * op(A) op(B)
 };
 struct SkinnyPlan {
   int rt = 1;      // 32-column blocks per row block: N <= 32*rt
@@ -91,6 +95,7 @@ struct MergeDesc {
   void* M = nullptr;
   int64_t ldw = 0, lda = 0, ldb = 0, ldm = 0;
   int64_t I = 0, O = 0, R = 0;
+  float alpha = 1.f;  // M = W + alpha A B
 };
 inline bool merge_ok(int dtype, int64_t r) { return dtype != DT_F32 && r <= 128; }
 hipError_t merge_run(int dtype, const MergeDesc& d, hipStream_t stream);
@@ -104,6 +109,7 @@ hipError_t gemm_launch_bf16(int cfg, int al, int bl, const GemmArgs& a, dim3 gri
 hipError_t gemm_launch_f16(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);
 hipError_t gemm_launch_f32(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);
 hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int M, int N, void* C,
-                                int64_t ldc, const void* D, int64_t ldd, hipStream_t s);
+                                int64_t ldc, const void* D, int64_t ldd, float alpha, const void* bias,
+                                hipStream_t s);
 
 }  // namespace rl

@@ -49,6 +49,10 @@ struct GemmArgs {
   // value (nibble - 8) * scale[(row / 64) * ldbs + col], scales in fp16.  Bscale == nullptr: dense B.
   const void* Bscale;
   int64_t ldbs;
+  // C = alpha * (sum of the products) + D + bias: alpha scales the products only; bias is a row
+  // vector [N] in T added to every row (nullptr = none)
+  float alpha;
+  const void* bias;
 };
 
 // ---- per-type pieces --------------------------------------------------------------------------
@@ -94,6 +98,8 @@ struct Epilogue {
   int64_t ldd;
   float* partial;  // [splits][M][N] or nullptr
   int M, N, split;
+  float alpha;       // scales the accumulated products (not D, not bias); partials stay unscaled
+  const void* bias;  // [N] in T, or nullptr
 };
 
 template <typename T>
@@ -116,7 +122,9 @@ __device__ __forceinline__ void store_block(const Epilogue& ep, const f32x16& ac
       const int n = nbase + 8 * q + 4 * h;
       if (n >= ep.N) continue;
       f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      if (ep.alpha != 1.f) v *= ep.alpha;
       if (ep.D) v += *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.D) + (int64_t)m * ep.ldd + n);
+      if (ep.bias) v += *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.bias) + n);
       *reinterpret_cast<f32x4*>(static_cast<float*>(ep.C) + (int64_t)m * ep.ldc + n) = v;
     }
   } else {
@@ -127,14 +135,22 @@ __device__ __forceinline__ void store_block(const Epilogue& ep, const f32x16& ac
       for (int w = 0; w < 2; ++w) {
         const int q = 2 * qp + w;
         f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-        if (ep.D) {
+        if (ep.alpha != 1.f) v *= ep.alpha;
+        if (ep.D || ep.bias) {
           const int n = nbase + 8 * q + 4 * h;
           if (n < ep.N) {
             T d4[4];
-            *reinterpret_cast<i32x2*>(d4) =
-                *reinterpret_cast<const i32x2*>(static_cast<const T*>(ep.D) + (int64_t)m * ep.ldd + n);
+            if (ep.D) {
+              *reinterpret_cast<i32x2*>(d4) =
+                  *reinterpret_cast<const i32x2*>(static_cast<const T*>(ep.D) + (int64_t)m * ep.ldd + n);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
+              for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
+            }
+            if (ep.bias) {
+              *reinterpret_cast<i32x2*>(d4) = *reinterpret_cast<const i32x2*>(static_cast<const T*>(ep.bias) + n);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
+            }
           }
         }
         T o4[4] = {from_f32<T>(v[0]), from_f32<T>(v[1]), from_f32<T>(v[2]), from_f32<T>(v[3])};
@@ -377,7 +393,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
   }
 
   // ---- epilogue
-  Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, (int)blockIdx.y};
+  Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, (int)blockIdx.y, g.alpha, g.bias};
 #pragma unroll
   for (int a = 0; a < G::TM; ++a)
 #pragma unroll
@@ -385,11 +401,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
       store_block<T>(ep, acc[a][b], m0 + wm * G::WTM + a * 32 + (lane & 31), n0 + wn * G::WTN + b * 32, lane);
 }
 
-// Sum the split-K partials in slice order and round once: C = sum_z partial[z] (+ D).
+// Sum the split-K partials in slice order and round once: C = alpha * sum_z partial[z] (+ D) (+ bias).
 template <typename T>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits,
                                                             int M, int N, T* __restrict__ C, int64_t ldc,
-                                                            const T* __restrict__ D, int64_t ldd) {
+                                                            const T* __restrict__ D, int64_t ldd, float alpha,
+                                                            const T* __restrict__ bias) {
   const int64_t quads = (int64_t)M * N / 4;  // N is a multiple of 4
   for (int64_t qd = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; qd < quads;
        qd += (int64_t)gridDim.x * blockDim.x) {
@@ -400,9 +417,14 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
       f32x4 p = *reinterpret_cast<const f32x4*>(partial + (int64_t)z * M * N + e);
       s += p;
     }
+    if (alpha != 1.f) s *= alpha;
     if (D) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) s[k] += (float)D[(int64_t)m * ldd + n + k];
+    }
+    if (bias) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) s[k] += (float)bias[n + k];
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) C[(int64_t)m * ldc + n + k] = from_f32<T>(s[k]);

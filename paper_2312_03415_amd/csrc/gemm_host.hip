@@ -106,6 +106,7 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
     }
     dt.C = static_cast<char*>(d.C) + (size_t)plan.tail_n0 * esz;
     if (d.D) dt.D = static_cast<const char*>(d.D) + (size_t)plan.tail_n0 * esz;
+    if (d.bias) dt.bias = static_cast<const char*>(d.bias) + (size_t)plan.tail_n0 * esz;
     hipError_t e = gemm_run(dm, pm, nullptr, stream);
     if (e != hipSuccess) return e;
     const GemmPlan pt = gemm_plan(d.dtype, d.M, dt.N, d.K[0], d.nseg > 1 ? d.K[1] : 0);
@@ -148,6 +149,8 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   a.splits = plan.splits;
   a.Bscale = d.Bscale;
   a.ldbs = d.ldbs;
+  a.alpha = d.alpha;
+  a.bias = plan.splits > 1 ? nullptr : d.bias;
   dim3 grid((unsigned)(plan.nbm * plan.nbn), (unsigned)plan.splits, 1);
   const int al = d.a_strided ? 1 : 0, bl = d.b_kcontig ? 1 : 0;
   hipError_t e;
@@ -159,12 +162,14 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   }
   if (e != hipSuccess) return e;
   if (plan.splits > 1)
-    e = splitk_reduce_launch(d.dtype, scratch, plan.splits, (int)d.M, (int)d.N, d.C, d.ldc, d.D, d.ldd, stream);
+    e = splitk_reduce_launch(d.dtype, scratch, plan.splits, (int)d.M, (int)d.N, d.C, d.ldc, d.D, d.ldd, d.alpha,
+                             d.bias, stream);
   return e;
 }
 
 hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int M, int N, void* C,
-                                int64_t ldc, const void* D, int64_t ldd, hipStream_t s) {
+                                int64_t ldc, const void* D, int64_t ldd, float alpha, const void* bias,
+                                hipStream_t s) {
   const int64_t quads = (int64_t)M * N / 4;
   int blocks = (int)((quads + 255) / 256);
   if (blocks > 4096) blocks = 4096;
@@ -172,15 +177,18 @@ hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int
   switch (dtype) {
     case DT_BF16:
       hipLaunchKernelGGL(splitk_reduce_kernel<__bf16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
-                         static_cast<__bf16*>(C), ldc, static_cast<const __bf16*>(D), ldd);
+                         static_cast<__bf16*>(C), ldc, static_cast<const __bf16*>(D), ldd, alpha,
+                         static_cast<const __bf16*>(bias));
       break;
     case DT_F16:
       hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
-                         static_cast<_Float16*>(C), ldc, static_cast<const _Float16*>(D), ldd);
+                         static_cast<_Float16*>(C), ldc, static_cast<const _Float16*>(D), ldd, alpha,
+                         static_cast<const _Float16*>(bias));
       break;
     case DT_F32:
       hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
-                         static_cast<float*>(C), ldc, static_cast<const float*>(D), ldd);
+                         static_cast<float*>(C), ldc, static_cast<const float*>(D), ldd, alpha,
+                         static_cast<const float*>(bias));
       break;
     default: return hipErrorInvalidValue;
   }
@@ -233,6 +241,7 @@ hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPla
     P.lda = d[w].lda; P.ldb = d[w].ldb; P.ldc = d[w].ldc;
     P.M = (int)d[w].M; P.N = (int)d[w].N; P.K = (int)d[w].K;
     P.a_strided = d[w].a_strided; P.b_kcontig = d[w].b_kcontig; P.trans_out = d[w].trans_out;
+    P.alpha = d[w].alpha;
     P.row_blocks = (int)((d[w].M + 31) / 32);
     {
       const int64_t esz = dtype == DT_F32 ? 4 : 2;
@@ -270,6 +279,7 @@ hipError_t merge_run(int dtype, const MergeDesc& d, hipStream_t stream) {
   a.ldw = d.ldw; a.lda = d.lda; a.ldb = d.ldb; a.ldm = d.ldm;
   a.I = (int)d.I; a.O = (int)d.O; a.R = (int)d.R;
   a.blocks_per_wg = 1;
+  a.alpha = d.alpha;
   return dtype == DT_BF16 ? merge_launch_bf16(a, stream) : merge_launch_f16(a, stream);
 }
 

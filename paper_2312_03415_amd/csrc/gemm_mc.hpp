@@ -433,7 +433,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
     }
 
     // ---- epilogue (the next work item's first tiles keep arriving meanwhile)
-    Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split};
+    Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split, g.alpha, g.bias};
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll

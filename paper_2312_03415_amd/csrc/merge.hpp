@@ -1,4 +1,4 @@
-// M = W + A B for the merged-weight graphs (forward2, Eq. 2; Z1 / Z3 of Algorithms 4 and 5 of arxiv
+// M = W + alpha A B for the merged-weight graphs (forward2, Eq. 2; Z1 / Z3 of Algorithms 4 and 5 of arxiv
 // 2312.03415): [i,o] = [i,o] + [i,r][r,o] with r <= 128, bf16 / fp16.
 //
 // The product is tiny (2 i o r FLOPs); the kernel reads W once and writes M once, so it is bound by
@@ -22,6 +22,7 @@ struct MergeArgs {
   int64_t ldw, lda, ldb, ldm;
   int I, O, R;
   int blocks_per_wg;  // 32-row blocks each workgroup walks (gridDim.y covers ceil(I/32) of them)
+  float alpha;        // the layer's LoRA scale (1 for the paper's layer)
 };
 
 template <int KSTEPS, int CB>
@@ -127,8 +128,8 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs g) {
       T o8[8];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        o8[e] = from_f32<T>((float)w8[e] + s0[e]);
-        o8[4 + e] = from_f32<T>((float)w8[4 + e] + s1[e]);
+        o8[e] = from_f32<T>((float)w8[e] + g.alpha * s0[e]);
+        o8[4 + e] = from_f32<T>((float)w8[4 + e] + g.alpha * s1[e]);
       }
       if (col_ok && row < g.I) *reinterpret_cast<i32x4*>(Mp + (int64_t)row * g.ldm + n0 + pcol) = *reinterpret_cast<i32x4*>(o8);
     }

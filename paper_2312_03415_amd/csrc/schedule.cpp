@@ -29,11 +29,13 @@ struct Builder {
   // b_is_w: B is the layer's frozen W (int4 when L.w_int4)
   void gemm(const char* what, int a_strided, int b_kcontig, int64_t M, int64_t N, int64_t K, Mat A, Mat B,
             Mat C, const Mat* D = nullptr, int64_t K2 = 0, const Mat* A2 = nullptr, const Mat* B2 = nullptr,
-            bool b_is_w = false) {
+            bool b_is_w = false, float alpha = 1.f, const void* bias = nullptr) {
     Step s;
     s.what = what;
     GemmDesc& d = s.d;
     d.dtype = L.dtype;
+    d.alpha = alpha;
+    d.bias = bias;
     d.a_strided = a_strided;
     d.b_kcontig = b_kcontig;
     d.M = M;
@@ -59,7 +61,7 @@ struct Builder {
   // GEMM with W as the addend
   void merge(const char* what, Mat A, Mat B, Mat W, Mat M) {
     if (!merge_ok(L.dtype, L.r)) {
-      gemm(what, 0, 0, L.i, L.o, L.r, A, B, M, &W);
+      gemm(what, 0, 0, L.i, L.o, L.r, A, B, M, &W, 0, nullptr, nullptr, false, L.scale);
       return;
     }
     Step s;
@@ -69,6 +71,7 @@ struct Builder {
     s.mg.W = W.ptr; s.mg.A = A.ptr; s.mg.B = B.ptr; s.mg.M = const_cast<void*>(M.ptr);
     s.mg.ldw = W.ld; s.mg.lda = A.ld; s.mg.ldb = B.ld; s.mg.ldm = M.ld;
     s.mg.I = L.i; s.mg.O = L.o; s.mg.R = L.r;
+    s.mg.alpha = L.scale;
     out->steps.push_back(s);
   }
 
@@ -78,9 +81,11 @@ struct Builder {
     int a_strided, b_kcontig;
     int64_t M, N, K;
     Mat A, B, C;
+    bool scaled = false;  // this product carries the layer's LoRA scale
   };
-  static SkinnyDesc to_skinny(const Sk& g) {
+  SkinnyDesc to_skinny(const Sk& g) const {
     SkinnyDesc d;
+    d.alpha = g.scaled ? L.scale : 1.f;
     if (g.N <= g.M || g.a_strided == 0) {
       d.A = g.A.ptr; d.lda = g.A.ld; d.B = g.B.ptr; d.ldb = g.B.ld; d.C = const_cast<void*>(g.C.ptr); d.ldc = g.C.ld;
       d.M = g.M; d.N = g.N; d.K = g.K; d.a_strided = g.a_strided; d.b_kcontig = g.b_kcontig; d.trans_out = 0;
@@ -106,7 +111,8 @@ struct Builder {
   }
   void skinny(const char* what, const Sk& g) {
     if (!sk_ok(g)) {
-      gemm(what, g.a_strided, g.b_kcontig, g.M, g.N, g.K, g.A, g.B, g.C);
+      gemm(what, g.a_strided, g.b_kcontig, g.M, g.N, g.K, g.A, g.B, g.C, nullptr, 0, nullptr, nullptr, false,
+           g.scaled ? L.scale : 1.f);
       return;
     }
     Step s;
@@ -156,7 +162,7 @@ struct Builder {
 // (Algorithms 1 and 5 share these four statements).
 void rank_r_pass(Builder& b, const BwdOperands& op, int64_t n, int64_t i, int64_t o, int64_t r, Mat Z1, Mat Z2,
                  bool need_Z1, bool need_Z2, bool dA, bool dB) {
-  const Builder::Sk z1{0, 1, n, r, o, op.dY, op.B, Z1}, z2{0, 0, n, r, i, op.X, op.A, Z2};
+  const Builder::Sk z1{0, 1, n, r, o, op.dY, op.B, Z1, true}, z2{0, 0, n, r, i, op.X, op.A, Z2, true};
   if (need_Z1 && need_Z2) b.skinny2("Z1 = dY B^T ; Z2 = X A", "Z1 = dY B^T", z1, "Z2 = X A", z2);
   else if (need_Z1) b.skinny("Z1 = dY B^T", z1);
   else if (need_Z2) b.skinny("Z2 = X A", z2);
@@ -168,7 +174,7 @@ void rank_r_pass(Builder& b, const BwdOperands& op, int64_t n, int64_t i, int64_
 
 // dA = Z2 B^T and dB = A^T Z2 (Algorithms 3 and 4), one launch when both are wanted
 void z2_grads(Builder& b, const BwdOperands& op, int64_t i, int64_t o, int64_t r, Mat Z2, bool dA, bool dB) {
-  const Builder::Sk ga{0, 1, i, r, o, Z2, op.B, op.dA}, gb{1, 0, r, o, i, op.A, Z2, op.dB};
+  const Builder::Sk ga{0, 1, i, r, o, Z2, op.B, op.dA, true}, gb{1, 0, r, o, i, op.A, Z2, op.dB, true};
   if (dA && dB) b.skinny2("dA = Z2 B^T ; dB = A^T Z2", "dA = Z2 B^T", ga, "dB = A^T Z2", gb);
   else if (dA) b.skinny("dA = Z2 B^T", ga);
   else if (dB) b.skinny("dB = A^T Z2", gb);
@@ -182,22 +188,22 @@ bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void*
   const int64_t n = L.n, i = L.i, o = L.o, r = L.r;
   switch (variant) {
     case 0: {  // default chain: T kept, one kernel per product
-      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, op.T});
-      b.gemm("Y = X W", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, 0, nullptr, nullptr, true);
+      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, op.T, true});
+      b.gemm("Y = X W", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, 0, nullptr, nullptr, true, 1.f, op.bias);
       b.gemm("Y += T B", 0, 0, n, o, r, op.T, op.B, op.Y, &op.Y);
       break;
     }
     case 1: {  // forward1: (XW) + ((XA)B), the sum folded into one contraction over [X|T]
       Mat T = b.scratch(n, r);
-      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T});
-      b.gemm("Y = [X|T] [W;B]", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, r, &T, &op.B, true);
+      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T, true});
+      b.gemm("Y = [X|T] [W;B]", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, r, &T, &op.B, true, 1.f, op.bias);
       break;
     }
     case 2: {  // forward2: X (W + AB)
       if (L.w_int4) return false;  // no dense buffer to merge AB into
-      Mat M = b.scratch(i, o);
+      Mat M = op.keep_M ? op.M : b.scratch(i, o);
       b.merge("M = W + A B", op.A, op.B, op.W, M);
-      b.gemm("Y = X M", 0, 0, n, o, i, op.X, M, op.Y);
+      b.gemm("Y = X M", 0, 0, n, o, i, op.X, M, op.Y, nullptr, 0, nullptr, nullptr, false, 1.f, op.bias);
       break;
     }
     default:
@@ -216,7 +222,7 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     case 0: {  // backward of the default chain (uses the kept T = XA)
       Mat Z1 = b.scratch(n, r);
       // one kernel per product, as autograd would run them
-      if (dA || dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1});
+      if (dA || dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1, true});
       if (dB) b.skinny("dB = T^T dY", {1, 0, r, o, n, op.T, op.dY, op.dB});
       if (dA) b.skinny("dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA});
       if (dX) {
@@ -233,19 +239,19 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     }
     case 2: {  // Algorithm 2
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(i, o);
-      if (dA || dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1});
+      if (dA || dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1, true});
       if (dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
       if (dA && dB)
         b.skinny2("dA = X^T Z1 ; dB = A^T Z2", "dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA}, "dB = A^T Z2",
-                  {1, 0, r, o, i, op.A, Z2, op.dB});
+                  {1, 0, r, o, i, op.A, Z2, op.dB, true});
       else if (dA) b.skinny("dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA});
-      else if (dB) b.skinny("dB = A^T Z2", {1, 0, r, o, i, op.A, Z2, op.dB});
+      else if (dB) b.skinny("dB = A^T Z2", {1, 0, r, o, i, op.A, Z2, op.dB, true});
       if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A, true);
       break;
     }
     case 3: {  // Algorithm 3
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(i, o);
-      if (dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1});
+      if (dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1, true});
       if (dA || dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
       z2_grads(b, op, i, o, r, Z2, dA, dB);
       if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A, true);
@@ -253,8 +259,8 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     }
     case 4: {  // Algorithm 4
       if (L.w_int4) return false;
-      Mat Z1 = b.scratch(i, o), Z2 = b.scratch(i, o);
-      if (dX) b.merge("Z1 = W + A B", op.A, op.B, op.W, Z1);
+      Mat Z1 = op.have_M ? op.M : b.scratch(i, o), Z2 = b.scratch(i, o);
+      if (dX && !op.have_M) b.merge("Z1 = W + A B", op.A, op.B, op.W, Z1);
       if (dA || dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
       z2_grads(b, op, i, o, r, Z2, dA, dB);
       if (dX) b.gemm("dX = dY Z1^T", 0, 1, n, i, o, op.dY, Z1, op.dX);
@@ -262,10 +268,49 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     }
     case 5: {  // Algorithm 5
       if (L.w_int4) return false;
-      Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r), Z3 = b.scratch(i, o);
-      if (dX) b.merge("Z3 = W + A B", op.A, op.B, op.W, Z3);
+      Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r), Z3 = op.have_M ? op.M : b.scratch(i, o);
+      if (dX && !op.have_M) b.merge("Z3 = W + A B", op.A, op.B, op.W, Z3);
       rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA, dB, dA, dB);
       if (dX) b.gemm("dX = dY Z3^T", 0, 1, n, i, o, op.dY, Z3, op.dX);
+      break;
+    }
+    // Items 6-8 of the list of eight bracketings in Section 2 (the paper drops them because Table 1
+    // never ranks them first; they are built from the same launches as Algorithms 1-5)
+    case 6: {  // dA = (X^T dY) B^T, dB = (A^T X^T) dY, dX = dY W^T + (dY B^T) A^T
+      Mat Z1 = b.scratch(n, r), T = b.scratch(n, r), Z2 = b.scratch(i, o);
+      const Builder::Sk z1{0, 1, n, r, o, op.dY, op.B, Z1, true}, t{0, 0, n, r, i, op.X, op.A, T, true};
+      if (dX && dB) b.skinny2("Z1 = dY B^T ; T = X A", "Z1 = dY B^T", z1, "T = X A", t);
+      else if (dX) b.skinny("Z1 = dY B^T", z1);
+      else if (dB) b.skinny("T = X A", t);
+      if (dA) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
+      if (dA) b.skinny("dA = Z2 B^T", {0, 1, i, r, o, Z2, op.B, op.dA, true});
+      if (dB) b.skinny("dB = T^T dY", {1, 0, r, o, n, T, op.dY, op.dB});
+      if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A, true);
+      break;
+    }
+    case 7: {  // dA = (X^T dY) B^T, dB = (A^T X^T) dY, dX = dY (W^T + B^T A^T)
+      if (L.w_int4) return false;
+      Mat T = b.scratch(n, r), Z2 = b.scratch(i, o), M = op.have_M ? op.M : b.scratch(i, o);
+      if (dX && !op.have_M) b.merge("M = W + A B", op.A, op.B, op.W, M);
+      if (dB) b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T, true});
+      if (dA) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
+      if (dA) b.skinny("dA = Z2 B^T", {0, 1, i, r, o, Z2, op.B, op.dA, true});
+      if (dB) b.skinny("dB = T^T dY", {1, 0, r, o, n, T, op.dY, op.dB});
+      if (dX) b.gemm("dX = dY M^T", 0, 1, n, i, o, op.dY, M, op.dX);
+      break;
+    }
+    case 8: {  // dA = X^T (dY B^T), dB = A^T (X^T dY), dX = dY (W^T + B^T A^T)
+      if (L.w_int4) return false;
+      Mat Z1 = b.scratch(n, r), Z2 = b.scratch(i, o), M = op.have_M ? op.M : b.scratch(i, o);
+      if (dX && !op.have_M) b.merge("M = W + A B", op.A, op.B, op.W, M);
+      if (dA) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1, true});
+      if (dB) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
+      if (dA && dB)
+        b.skinny2("dA = X^T Z1 ; dB = A^T Z2", "dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA}, "dB = A^T Z2",
+                  {1, 0, r, o, i, op.A, Z2, op.dB, true});
+      else if (dA) b.skinny("dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA});
+      else if (dB) b.skinny("dB = A^T Z2", {1, 0, r, o, i, op.A, Z2, op.dB, true});
+      if (dX) b.gemm("dX = dY M^T", 0, 1, n, i, o, op.dY, M, op.dX);
       break;
     }
     default:

@@ -22,6 +22,10 @@ struct LayerDims {
   int64_t n = 0, i = 0, o = 0, r = 0;
   int dtype = DT_BF16;
   bool w_int4 = false;  // W is int4: its products run on the generic engine, merged graphs do not exist
+  // LoRA scale s of Y = XW + s (XA) B.  It is applied where a rank-r factor or the merged weight is
+  // formed (T = s XA, Z1 = s dY B^T, M = W + s AB, dA = s Z2 B^T, dB = s A^T Z2), so that every later
+  // product of the graph is the paper's, unchanged.
+  float scale = 1.f;
 };
 
 struct Step {
@@ -43,10 +47,15 @@ struct Schedule {
 
 struct FwdOperands {
   Mat X, W, A, B, Y, T;  // T: caller's buffer for the default chain (kept for the backward)
+  const void* bias = nullptr;  // frozen bias of the base layer [o], added by the GEMM that writes Y
+  Mat M;                       // forward2 with keep_M: W + s AB goes here (caller's buffer) and stays
+  bool keep_M = false;
 };
 struct BwdOperands {
   Mat dY, X, W, A, B, T, dX, dA, dB;
   bool want_dX = true, want_dA = true, want_dB = true;
+  Mat M;                // have_M: W + s AB as forward2 left it; the merged graphs read it instead of
+  bool have_M = false;  // forming it again
 };
 
 // ws_base may be null (sizing / modelling).  Returns false for an unknown variant.

@@ -101,7 +101,8 @@ static double step_time_us(const Step& s) {
   return gemm_time_us(s.d, s.plan);
 }
 
-double model_time_us(int is_bwd, int variant, const LayerDims& L) {
+// have_M: the backward finds W + AB kept by forward2 and does not form it again
+double model_time_us(int is_bwd, int variant, const LayerDims& L, bool have_M = false) {
   Schedule sch;
   bool ok;
   if (!is_bwd) {
@@ -109,6 +110,7 @@ double model_time_us(int is_bwd, int variant, const LayerDims& L) {
     ok = build_forward(variant, L, op, nullptr, &sch);
   } else {
     BwdOperands op;
+    op.have_M = have_M;
     ok = build_backward(variant, L, op, nullptr, &sch);
   }
   if (!ok) return -1.0;
@@ -139,7 +141,7 @@ extern "C" double runlora_model_time_us(int is_bwd, int variant, int64_t n, int6
                                         int dtype) {
   int dt = to_internal_dtype(dtype);
   if (dt < 0 || n < 1 || i < 1 || o < 1 || r < 1) return -1.0;
-  if (variant < 0 || variant > (is_bwd ? 5 : 2)) return -1.0;
+  if (variant < 0 || variant > (is_bwd ? 8 : 2)) return -1.0;
   LayerDims L{n, i, o, r, dt};
   return model_time_us(is_bwd, variant, L);
 }
@@ -150,7 +152,7 @@ extern "C" int runlora_select_by(int criterion, int64_t n, int64_t i, int64_t o,
   if (n < 1 || i < 1 || o < 1 || r < 1) return RL_ERR_SHAPE;
   int dt = to_internal_dtype(dtype);
   if (dt < 0) return RL_ERR_DTYPE;
-  if (criterion != 0 && criterion != 1) return RL_ERR_VARIANT;
+  if (criterion < 0 || criterion > 2) return RL_ERR_VARIANT;
   const bool int4 = (dtype == RL_INT4_G64);
   // an int4 W has no dense buffer to merge AB into: forward1 and backward1..3 only
   const int fmax = int4 ? 1 : 2, bmax = int4 ? 3 : 5;
@@ -169,7 +171,16 @@ extern "C" int runlora_select_by(int criterion, int64_t n, int64_t i, int64_t o,
   // returned when the model says it beats the best RunLoRA pair (large r at few tokens, where the
   // recomputation of XA in Algorithms 1 and 5 is not free).  Table 1 does not list it, so the FLOP
   // criterion never returns it.
-  if (criterion == 1) {
+  if (criterion >= 1) {
+    // With W + AB kept by forward2 the search is no longer separable: forward2 paired with
+    // backward4 / 5 saves the second merge pass, which may beat the separately best pair.
+    if (criterion == 2 && !int4) {
+      const double f2 = model_time_us(0, 2, L);
+      for (int v = 4; v <= 5; ++v) {
+        const double c = f2 + model_time_us(1, v, L, true);
+        if (c < cf + cb) { cf = f2; cb = c - f2; bf = 2; bb = v; }
+      }
+    }
     const double c0 = model_time_us(0, 0, L) + model_time_us(1, 0, L);
     if (c0 < cf + cb) { bf = 0; bb = 0; }
   }

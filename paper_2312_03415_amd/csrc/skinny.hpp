@@ -32,6 +32,7 @@ struct SkinnyProblem {
   int row_blocks;       // ceil(M / 32)
   int a_bytes, b_bytes; // extent of A and B in bytes (< 2 GiB): the range the loads are checked against
   int tiles_per_split;  // K tiles of this problem per gridDim.y slice
+  float alpha;          // C = alpha * op(A) op(B) (the LoRA scale, applied where a rank-r factor is formed)
 };
 
 struct SkinnyArgs {
@@ -221,8 +222,11 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
     for (int w = 1; w < NWV; ++w) s += red[((w * RT + b) * 32 + m) * 32 + nn];
     if (m0 + m < M && n < N) {
       if (P.partial) {
-        P.partial[((int64_t)blockIdx.y * M + (m0 + m)) * N + n] = s;
-      } else if (!trans) {
+        P.partial[((int64_t)blockIdx.y * M + (m0 + m)) * N + n] = s;  // unscaled: the reduce applies alpha
+        continue;
+      }
+      s *= P.alpha;
+      if (!trans) {
         static_cast<T*>(P.C)[(int64_t)(m0 + m) * P.ldc + n] = from_f32<T>(s);
       } else {
         static_cast<T*>(P.C)[(int64_t)n * P.ldc + (m0 + m)] = from_f32<T>(s);
@@ -264,6 +268,7 @@ __global__ __launch_bounds__(256) void skinny_reduce_kernel(SkinnyArgs g, int sp
       const float* src = P.partial + (int64_t)m * P.N + n;
       float s = src[0];
       for (int z = 1; z < splits; ++z) s += src[(int64_t)z * total];
+      s *= P.alpha;
       if (!P.trans_out) static_cast<T*>(P.C)[(int64_t)m * P.ldc + n] = from_f32<T>(s);
       else static_cast<T*>(P.C)[(int64_t)n * P.ldc + m] = from_f32<T>(s);
     }

@@ -75,10 +75,40 @@ def test_select_time_model_returns_legal_pairs():
             assert (f in (1, 2) and b in (1, 2, 3, 4, 5)) or (f, b) == (0, 0)
             assert rl.runlora_model_time_us(0, f, n, 4096, 4096, r, rl.RL_F16) > 0
     assert rl.runlora_model_time_us(0, 7, 128, 64, 64, 8, rl.RL_F16) < 0
+    assert rl.runlora_model_time_us(1, 8, 128, 64, 64, 8, rl.RL_F16) > 0      # items 6-8 are modelled too
+    assert rl.runlora_model_time_us(1, 9, 128, 64, 64, 8, rl.RL_F16) < 0
     f, b = ctypes.c_int(), ctypes.c_int()
     assert rl.lib().runlora_select(0, 8, 8, 8, rl.RL_F16, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_SHAPE
     assert rl.lib().runlora_select(8, 8, 8, 8, 77, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_DTYPE
     assert rl.lib().runlora_select(8, 8, 8, 8, rl.RL_F16, None, ctypes.byref(b)) == rl.RL_ERR_NULL
+
+
+def test_select_with_kept_merged_weight():
+    """Criterion 2 prices forward2 + backward4/5 without the second W + AB pass: it may only move the
+    choice towards such a pair, never to a slower one under the plain model."""
+    for n in (128, 1024, 4096, 16384):
+        for i, o, r in ((4096, 4096, 64), (8192, 2048, 16), (4096, 11008, 128), (4096, 4096, 1024)):
+            f1, b1 = rl.runlora_select(n, i, o, r, rl.RL_BF16, criterion=1)
+            f2, b2 = rl.runlora_select(n, i, o, r, rl.RL_BF16, criterion=2)
+            assert (f2, b2) == (f1, b1) or (f2 == 2 and b2 in (4, 5)), (n, i, o, r)
+    f, b = ctypes.c_int(), ctypes.c_int()
+    assert rl.lib().runlora_select_by(3, 8, 8, 8, 8, rl.RL_F16, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_VARIANT
+    # an int4 W has no merged graphs whatever the criterion
+    f2, b2 = rl.runlora_select(16384, 4096, 4096, 64, rl.RL_INT4_G64, criterion=2)
+    assert f2 in (0, 1) and b2 in (0, 1, 2, 3)
+
+
+def test_saved_bytes_is_the_memory_claim_of_section2():
+    """The default chain keeps XA (n r elements) for its backward, RunLoRA's forwards keep nothing
+    besides X (Section 2); forward2 asked to keep W + AB holds i o elements."""
+    n, i, o, r = 8192, 4096, 11008, 128
+    assert rl.runlora_saved_bytes(0, n, i, o, r, rl.RL_BF16) == n * r * 2
+    assert rl.runlora_saved_bytes(0, n, i, o, r, rl.RL_F32) == n * r * 4
+    assert rl.runlora_saved_bytes(1, n, i, o, r, rl.RL_BF16) == 0
+    assert rl.runlora_saved_bytes(2, n, i, o, r, rl.RL_BF16) == 0
+    assert rl.runlora_saved_bytes(2, n, i, o, r, rl.RL_BF16, keep_merged=True) == i * o * 2
+    assert rl.runlora_saved_bytes(1, n, i, o, r, rl.RL_BF16, keep_merged=True) == 0
+    assert rl.runlora_saved_bytes(5, n, i, o, r, rl.RL_BF16) == 0
 
 
 def test_workspace_bytes_cover_intermediates():
@@ -169,7 +199,9 @@ def test_backward_rejects_bad_arguments_before_touching_the_gpu():
         return L.runlora_backward(variant, br(dY), br(saved), br(W), br(A), br(B), br(dX) if dX else None, br(dA),
                                   br(dB), br(opts) if opts else None)
 
-    assert call(6) == rl.RL_ERR_VARIANT
+    assert call(9) == rl.RL_ERR_VARIANT
+    assert call(-1) == rl.RL_ERR_VARIANT
+    assert call(6) == rl.RL_ERR_WORKSPACE                 # items 6-8 of Section 2's list are legal graphs
     assert call(0) == rl.RL_ERR_SAVED_MISMATCH            # default backward needs the default forward's T
     s2 = rl.rl_saved_t(1, dt, n + 1, i, o, r, base + 7 * step, i, None, 0)
     assert call(1, saved=s2) == rl.RL_ERR_SAVED_MISMATCH

@@ -1,0 +1,139 @@
+"""GPU parity of what the library offers beyond the paper's plain layer (Section 2 has scale 1, no
+bias, nothing but X kept): the LoRA scale s and the frozen bias b of Y = XW + 1 b^T + s (XA) B in
+every computation graph, and W + s AB kept by forward2 for the merged backward graphs.  Oracle: the
+fp64 reference on B' = sB (see oracle.scaled_forward / scaled_backward)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL, layer_on_device, relerr, to_device, to_f64, torch_dtype
+from paper_2312_03415_amd import binding as rl
+from paper_2312_03415_amd import synth
+from test_gpu_parity import legal_pairs
+
+pytestmark = pytest.mark.gpu
+
+
+def bias_for(L, stream=9):
+    b64 = synth.normal(synth.BASE_SEED + L.index, stream, (L.o,))
+    st = synth.store(b64, L.dtype)
+    return to_device(st, L.dtype), synth.widen(st, L.dtype)
+
+
+def run_scaled(L, dev, fwd, bwd, scale, bias, keep_M=False):
+    import torch
+    td = torch_dtype(L.dtype)
+    code = rl.dtype_from_name(L.dtype)
+    nan = float("nan")
+    Y = torch.full((L.n, L.o), nan, dtype=td, device="cuda")
+    T = torch.full((L.n, L.r), nan, dtype=td, device="cuda") if fwd == rl.FWD_DEFAULT else None
+    M = torch.full((L.i, L.o), nan, dtype=td, device="cuda") if keep_M else None
+    saved = rl.new_saved(T, M)
+    ws = rl.new_workspace(fwd, bwd, L.n, L.i, L.o, L.r, code)
+    rl.runlora_forward(fwd, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=ws, scale=scale, bias=bias)
+    ws.fill_(0xFF)  # whatever the forward left in the workspace must not matter to the backward
+    dX = torch.full((L.n, L.i), nan, dtype=td, device="cuda")
+    dA = torch.full((L.i, L.r), nan, dtype=td, device="cuda")
+    dB = torch.full((L.r, L.o), nan, dtype=td, device="cuda")
+    rl.runlora_backward(bwd, dev["dY"], saved, dev["W"], dev["A"], dev["B"], dX, dA, dB, workspace=ws)
+    torch.cuda.synchronize()
+    out = {"Y": to_f64(Y), "dX": to_f64(dX), "dA": to_f64(dA), "dB": to_f64(dB)}
+    if M is not None:
+        out["M"] = to_f64(M)
+    return out, saved
+
+
+def scaled_reference(host, scale, bias64):
+    Y = oracle.scaled_forward(host["X"], host["W"], host["A"], host["B"], scale, bias64)
+    dX, dA, dB = oracle.scaled_backward(host["X"], host["W"], host["A"], host["B"], host["dY"], scale)
+    return {"Y": Y, "dX": dX, "dA": dA, "dB": dB}
+
+
+@pytest.mark.parametrize("dtype,r", [("bf16", 24), ("f16", 8), ("f32", 12), ("bf16", 160), ("f32", 136)])
+def test_scale_and_bias_all_pairs(dtype, r):
+    """Ragged shape, every legal forward x backward pair (backward6-8 included), s = 0.37 and a bias.
+    r > 128 sends the rank-r products and W + s AB to the tile GEMM (scale in its epilogue and in the
+    split-K reduce) instead of the streaming and merge kernels."""
+    L = synth.Layer("scaled", 333, 264, 392, r, dtype, 31)
+    dev, host = layer_on_device(L)
+    bias_dev, bias64 = bias_for(L)
+    scale = 0.37
+    want = scaled_reference(host, scale, bias64)
+    for f, b in legal_pairs():
+        print(f"case scaled layer={L} fwd={f} bwd={b}", flush=True)
+        got, _ = run_scaled(L, dev, f, b, scale, bias_dev)
+        for k in ("Y", "dX", "dA", "dB"):
+            err = relerr(got[k], want[k])
+            assert err < TOL[dtype], (f, b, k, err)
+
+
+def test_scale_two_is_exact_against_doubled_B():
+    """s = 2 is exact in every format: scaling in the kernels must give bit for bit what the plain
+    layer gives on B' = 2B (and dB = 2 dB'), graph by graph."""
+    L = synth.Layer("pow2", 200, 136, 264, 16, "bf16", 32)
+    dev, _ = layer_on_device(L)
+    dev2 = dict(dev)
+    dev2["B"] = dev["B"] * 2
+    for f, b in [(0, 0), (1, 1), (2, 5), (1, 3), (2, 4), (1, 6), (1, 7), (1, 8)]:
+        got, _ = run_scaled(L, dev, f, b, 2.0, None)
+        ref, _ = run_scaled(L, dev2, f, b, None, None)
+        for k in ("Y", "dX", "dA"):
+            assert np.array_equal(got[k], ref[k]), (f, b, k)
+        assert np.array_equal(got["dB"], 2.0 * ref["dB"]), (f, b, "dB")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_forward2_keeps_merged_weight_for_the_backward(dtype):
+    """forward2 leaves M = W + s AB in the caller's buffer; backward4/5/7/8 read it and return the
+    same bits as when they form it themselves."""
+    L = synth.Layer("keepM", 300, 264, 136, 16, dtype, 33)
+    dev, host = layer_on_device(L)
+    scale = 0.5
+    want = scaled_reference(host, scale, None)
+    Mwant = host["W"] + scale * oracle.matmul(host["A"], host["B"])
+    for b in rl.BWD_MERGED:
+        kept, saved = run_scaled(L, dev, rl.FWD2, b, scale, None, keep_M=True)
+        assert saved.M is not None and saved.fwd_variant == rl.FWD2
+        assert relerr(kept["M"], Mwant) < TOL[dtype]
+        plain, saved2 = run_scaled(L, dev, rl.FWD2, b, scale, None, keep_M=False)
+        assert saved2.M is None
+        for k in ("Y", "dX", "dA", "dB"):
+            assert relerr(kept[k], want[k]) < TOL[dtype], (b, k)
+            assert np.array_equal(kept[k], plain[k]), (b, k)
+    # a graph that does not use M ignores it; other forwards clear the field
+    got, _ = run_scaled(L, dev, rl.FWD2, rl.BWD1, scale, None, keep_M=True)
+    for k in ("Y", "dX", "dA", "dB"):
+        assert relerr(got[k], want[k]) < TOL[dtype], k
+    _, s1 = run_scaled(L, dev, rl.FWD1, rl.BWD5, scale, None, keep_M=True)
+    assert s1.M is None
+
+
+@pytest.mark.parametrize("cfg,splits,dtype", [(7, 1, "bf16"), (7, 3, "bf16"), (1, 1, "f16"), (0, 2, "f32"), (3, 1, "f32")])
+def test_gemm_alpha_and_bias(cfg, splits, dtype):
+    """C = alpha (A B) + D + bias through each engine's epilogue and through the split-K reduce."""
+    import torch
+    M, N, K = 300, 520, 392
+    td = torch_dtype(dtype)
+    a64, b64 = synth.normal(5, 1, (M, K)), synth.normal(5, 2, (K, N), 1.0 / K)
+    d64, bias64 = synth.normal(5, 3, (M, N)), synth.normal(5, 4, (N,))
+    st = {k: synth.store(v, dtype) for k, v in (("A", a64), ("B", b64), ("D", d64), ("bias", bias64))}
+    dev = {k: to_device(v, dtype) for k, v in st.items()}
+    host = {k: synth.widen(v, dtype) for k, v in st.items()}
+    C = torch.full((M, N), float("nan"), dtype=td, device="cuda")
+    rl.runlora_gemm(dev["A"], dev["B"], C, D=dev["D"], tile_cfg=cfg, splits=splits, alpha=-1.75, bias=dev["bias"])
+    torch.cuda.synchronize()
+    want = -1.75 * oracle.matmul(host["A"], host["B"]) + host["D"] + host["bias"][None, :]
+    assert relerr(to_f64(C), want) < TOL[dtype]
+
+
+def test_streaming_kernel_alpha():
+    import torch
+    M, N, K = 1000, 24, 2056
+    st = {k: synth.store(v, "bf16") for k, v in (("A", synth.normal(6, 1, (M, K))), ("B", synth.normal(6, 2, (K, N), 1.0 / K)))}
+    dev = {k: to_device(v, "bf16") for k, v in st.items()}
+    host = {k: synth.widen(v, "bf16") for k, v in st.items()}
+    for splits in (1, 4):
+        C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        rl.runlora_gemm(dev["A"], dev["B"], C, tile_cfg=8, splits=splits, alpha=0.3)
+        torch.cuda.synchronize()
+        assert relerr(to_f64(C), 0.3 * oracle.matmul(host["A"], host["B"])) < TOL["bf16"], splits

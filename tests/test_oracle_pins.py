@@ -160,6 +160,40 @@ def test_gradients_match_finite_differences(shape):
             assert rel(got[k], want[k]) < 1e-7, (v, k)
 
 
+def test_scaled_layer_gradients_match_finite_differences():
+    """Y = XW + 1 b^T + s (XA) B with s = 0.37: the oracle's substitution B' = sB, dB = s dB' against
+    central differences of the loss written with numpy alone."""
+    X, W, A, B, G = draw(5, 7, 6, 3, seed=13)
+    s, bias, h = 0.37, synth.normal(13, 9, (6,)), 1e-6
+
+    def loss(X, A, B):
+        return float(np.sum((X @ W + bias[None, :] + s * ((X @ A) @ B)) * G))
+
+    def fd(name):
+        base = {"X": X, "A": A, "B": B}
+        g = np.zeros_like(base[name])
+        for idx in np.ndindex(*g.shape):
+            p = {k: v.copy() for k, v in base.items()}
+            m = {k: v.copy() for k, v in base.items()}
+            p[name][idx] += h
+            m[name][idx] -= h
+            g[idx] = (loss(p["X"], p["A"], p["B"]) - loss(m["X"], m["A"], m["B"])) / (2 * h)
+        return g
+
+    assert rel(oracle.scaled_forward(X, W, A, B, s, bias), X @ W + bias[None, :] + s * ((X @ A) @ B)) < 1e-14
+    dX, dA, dB = oracle.scaled_backward(X, W, A, B, G, s)
+    assert rel(dX, fd("X")) < 1e-7 and rel(dA, fd("A")) < 1e-7 and rel(dB, fd("B")) < 1e-7
+    # s = 1 without bias is the paper's layer; s = 0 switches the adapter off
+    for got, want in zip(oracle.scaled_backward(X, W, A, B, G, 1.0), oracle.reference_backward(X, W, A, B, G)):
+        assert np.array_equal(got, want)
+    assert np.array_equal(oracle.scaled_forward(X, W, A, B), oracle.reference_forward(X, W, A, B))
+    dX0, dA0, dB0 = oracle.scaled_backward(X, W, A, B, G, 0.0)
+    assert rel(dX0, G @ W.T) < 1e-14 and np.all(dA0 == 0.0) and np.all(dB0 == 0.0)
+    rows = np.array([0, 3, 4])
+    Yr, dXr = oracle.scaled_rows(X[rows], G[rows], W, A, B, s, bias)
+    assert rel(Yr, oracle.scaled_forward(X, W, A, B, s, bias)[rows]) < 1e-14 and rel(dXr, dX[rows]) < 1e-14
+
+
 # ---- all computation graphs agree ---------------------------------------------------------------
 
 @pytest.mark.parametrize("shape", SHAPES)
