@@ -1,0 +1,146 @@
+"""torch.autograd front end of the library: a LoRA linear layer whose forward and backward run in
+the computation graphs runlora_select picks for its shape (arxiv 2312.03415, Section 2), and a
+helper that swaps it in for the nn.Linear modules of a model (Section 3 applies RunLoRA to every
+attention and MLP linear).
+
+Nothing is computed here: tensors are flattened to [n, d] views, buffers are allocated with torch,
+and every product runs inside the HIP library through binding.runlora_forward / runlora_backward.
+
+    layer = RunLoRALinear.from_linear(nn_linear, r=16, alpha=32)     # W frozen, A and B trainable
+    y = layer(x)                                                     # x [..., d_in] -> [..., d_out]
+    wrap_linears(model, r=16, alpha=32, targets=("q_proj", "v_proj"))
+"""
+import math
+
+import torch
+from torch import nn
+
+from . import binding as rl
+
+# one scratch buffer per device, shared by every layer (calls on a device are ordered on its current
+# stream and nothing lives in the workspace between two calls)
+_workspaces = {}
+
+
+def _workspace(device, nbytes):
+    ws = _workspaces.get(device)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        _workspaces[device] = ws
+    return ws
+
+
+class RunLoRAFunction(torch.autograd.Function):
+    """y = x W + bias + scale (x A) B with W and bias frozen; gradients for x, A and B (Eq. 1, Eq. 3).
+
+    pair = (forward variant, backward variant) as runlora_select returns them; keep_merged lets
+    forward2 hold W + scale AB for a merged backward (i*o elements kept until the backward ran).
+    """
+
+    @staticmethod
+    def forward(ctx, x, W, A, B, bias, scale, pair, keep_merged):
+        fwd, bwd = pair
+        i, o = W.shape
+        r = A.shape[1]
+        x2 = x.reshape(-1, i)
+        if x2.stride(-1) != 1 or x2.stride(0) % 8 != 0 or x2.data_ptr() % 16 != 0:
+            x2 = x2.contiguous()
+        n = x2.shape[0]
+        code = rl.dtype_code(x.dtype)
+        y = torch.empty((n, o), dtype=x.dtype, device=x.device)
+        T = torch.empty((n, r), dtype=x.dtype, device=x.device) if fwd == rl.FWD_DEFAULT else None
+        M = None
+        if keep_merged and fwd == rl.FWD2 and bwd in rl.BWD_MERGED:
+            M = torch.empty((i, o), dtype=x.dtype, device=x.device)
+        saved = rl.new_saved(T, M)
+        ws = _workspace(x.device, rl.runlora_workspace_bytes(fwd, bwd, n, i, o, r, code))
+        rl.runlora_forward(fwd, x2, W, A, B, y, saved, workspace=ws, scale=scale, bias=bias)
+        ctx.saved = saved
+        ctx.bwd = bwd
+        ctx.keep = (T, M)          # buffers *saved points into
+        ctx.x_shape = x.shape
+        ctx.save_for_backward(x2, W, A, B)
+        return y.view(*x.shape[:-1], o)
+
+    @staticmethod
+    def backward(ctx, dy):
+        x2, W, A, B = ctx.saved_tensors
+        i, o = W.shape
+        r = A.shape[1]
+        n = x2.shape[0]
+        dy2 = dy.reshape(n, o)
+        if dy2.stride(-1) != 1 or dy2.stride(0) % 8 != 0 or dy2.data_ptr() % 16 != 0:
+            dy2 = dy2.contiguous()
+        need_x, _, need_a, need_b = ctx.needs_input_grad[:4]
+        dx = torch.empty((n, i), dtype=x2.dtype, device=x2.device) if need_x else None
+        dA = torch.empty_like(A) if need_a else None
+        dB = torch.empty_like(B) if need_b else None
+        code = rl.dtype_code(dy.dtype)
+        ws = _workspace(dy.device, rl.runlora_workspace_bytes(-1, ctx.bwd, n, i, o, r, code))
+        rl.runlora_backward(ctx.bwd, dy2, ctx.saved, W, A, B, dx, dA, dB, workspace=ws)
+        if dx is not None:
+            dx = dx.view(ctx.x_shape)
+        return dx, None, dA, dB, None, None, None, None
+
+
+class RunLoRALinear(nn.Module):
+    """LoRA-augmented linear layer: frozen W [d_in, d_out] (the orientation of Eq. 1, Y = XW) and
+    optional frozen bias, trainable A [d_in, r] and B [r, d_out], scale = alpha / r.
+
+    The (forward, backward) pair is chosen per token count by runlora_select the first time that
+    count is seen (criterion 2 when keep_merged), or fixed with pair=(f, b).
+    """
+
+    def __init__(self, weight, r, alpha=None, bias=None, pair=None, keep_merged=False):
+        super().__init__()
+        d_in, d_out = weight.shape
+        self.d_in, self.d_out, self.r = d_in, d_out, r
+        self.scale = 1.0 if alpha is None else float(alpha) / r
+        self.weight = nn.Parameter(weight.contiguous(), requires_grad=False)
+        self.bias = nn.Parameter(bias.contiguous(), requires_grad=False) if bias is not None else None
+        # the usual LoRA start: A random, B zero, so that the layer starts as the frozen one
+        self.lora_A = nn.Parameter(torch.randn(d_in, r, dtype=weight.dtype, device=weight.device) / math.sqrt(d_in))
+        self.lora_B = nn.Parameter(torch.zeros(r, d_out, dtype=weight.dtype, device=weight.device))
+        self.pair = pair
+        self.keep_merged = keep_merged
+        self._pairs = {}
+
+    @classmethod
+    def from_linear(cls, linear, r, alpha=None, pair=None, keep_merged=False):
+        """nn.Linear keeps its weight as [d_out, d_in]; the layer holds the transposed copy."""
+        w = linear.weight.detach().t().contiguous()
+        b = linear.bias.detach() if linear.bias is not None else None
+        return cls(w, r, alpha, b, pair, keep_merged)
+
+    def pair_for(self, n_tokens):
+        if self.pair is not None:
+            return self.pair
+        p = self._pairs.get(n_tokens)
+        if p is None:
+            code = rl.dtype_code(self.weight.dtype)
+            p = rl.runlora_select(n_tokens, self.d_in, self.d_out, self.r, code, criterion=2 if self.keep_merged else None)
+            self._pairs[n_tokens] = p
+        return p
+
+    def forward(self, x):
+        n = x.numel() // self.d_in
+        return RunLoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.bias, self.scale,
+                                     self.pair_for(n), self.keep_merged)
+
+    def extra_repr(self):
+        return f"d_in={self.d_in}, d_out={self.d_out}, r={self.r}, scale={self.scale:g}, bias={self.bias is not None}"
+
+
+def wrap_linears(model, r, alpha=None, targets=None, pair=None, keep_merged=False):
+    """Replace nn.Linear submodules of `model` by RunLoRALinear (all of them, or those whose attribute
+    name is in `targets`); every other parameter of the model is frozen.  Returns the replaced names."""
+    replaced = []
+    for name, module in list(model.named_modules()):
+        for child_name, child in list(module.named_children()):
+            if isinstance(child, nn.Linear) and (targets is None or child_name in targets):
+                setattr(module, child_name, RunLoRALinear.from_linear(child, r, alpha, pair, keep_merged))
+                replaced.append(f"{name}.{child_name}" if name else child_name)
+    for pname, p in model.named_parameters():
+        if not (pname.endswith("lora_A") or pname.endswith("lora_B")):
+            p.requires_grad_(False)
+    return replaced

@@ -1,0 +1,135 @@
+"""The torch.autograd front end (module.py) on the GPU: a RunLoRALinear's outputs and gradients against
+the fp64 oracle of the scaled layer, gradient flow through a stack of layers, the memory kept between
+forward and backward (Section 2: RunLoRA's forwards do not keep XA), and the nn.Linear replacement."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL, relerr, to_device, to_f64, torch_dtype
+from paper_2312_03415_amd import binding as rl
+from paper_2312_03415_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def make_layer(d_in, d_out, r, dtype, alpha, with_bias, pair=None, keep_merged=False, seed=41):
+    from paper_2312_03415_amd.module import RunLoRALinear
+    import torch
+    st = {"W": synth.store(synth.normal(seed, 2, (d_in, d_out), 1.0 / d_in), dtype),
+          "A": synth.store(synth.normal(seed, 3, (d_in, r), 1.0 / d_in), dtype),
+          "B": synth.store(synth.normal(seed, 4, (r, d_out), 0.1 / r), dtype),
+          "bias": synth.store(synth.normal(seed, 9, (d_out,)), dtype)}
+    host = {k: synth.widen(v, dtype) for k, v in st.items()}
+    layer = RunLoRALinear(to_device(st["W"], dtype), r, alpha, to_device(st["bias"], dtype) if with_bias else None,
+                          pair=pair, keep_merged=keep_merged)
+    with torch.no_grad():
+        layer.lora_A.copy_(to_device(st["A"], dtype))
+        layer.lora_B.copy_(to_device(st["B"], dtype))
+    if not with_bias:
+        host["bias"] = None
+    return layer, host
+
+
+@pytest.mark.parametrize("dtype,pair", [("bf16", None), ("bf16", (0, 0)), ("f16", (2, 5)), ("f32", (1, 3)), ("bf16", (2, 4))])
+def test_layer_matches_oracle(dtype, pair):
+    import torch
+    b, s, d_in, d_out, r, alpha = 3, 50, 264, 136, 8, 20.0
+    layer, host = make_layer(d_in, d_out, r, dtype, alpha, True, pair, keep_merged=pair in ((2, 5), (2, 4)))
+    xs = synth.store(synth.normal(42, 1, (b * s, d_in)), dtype)
+    gs = synth.store(synth.normal(42, 5, (b * s, d_out)), dtype)
+    x = to_device(xs, dtype).view(b, s, d_in).requires_grad_(True)
+    y = layer(x)
+    assert y.shape == (b, s, d_out)
+    y.backward(to_device(gs, dtype).view(b, s, d_out))
+    torch.cuda.synchronize()
+    X, G = synth.widen(xs, dtype), synth.widen(gs, dtype)
+    scale = alpha / r
+    Yw = oracle.scaled_forward(X, host["W"], host["A"], host["B"], scale, host["bias"])
+    dXw, dAw, dBw = oracle.scaled_backward(X, host["W"], host["A"], host["B"], G, scale)
+    tol = TOL[dtype]
+    assert relerr(to_f64(y.reshape(-1, d_out)), Yw) < tol
+    assert relerr(to_f64(x.grad.reshape(-1, d_in)), dXw) < tol
+    assert relerr(to_f64(layer.lora_A.grad), dAw) < tol
+    assert relerr(to_f64(layer.lora_B.grad), dBw) < tol
+    assert layer.weight.grad is None and layer.bias.grad is None
+
+
+def test_gradients_flow_through_a_stack():
+    """Two layers with a nonlinearity between them: the chain rule through both (x.grad, and the first
+    layer's adapter gradients, which need the second layer's dX) against the same stack in fp64 torch."""
+    import torch
+    n, d, h, r = 96, 72, 136, 8
+    l1, h1 = make_layer(d, h, r, "f32", 16.0, True, seed=51)
+    l2, h2 = make_layer(h, d, r, "f32", 16.0, False, seed=52)
+    xs = synth.store(synth.normal(53, 1, (n, d)), "f32")
+    x = to_device(xs, "f32").requires_grad_(True)
+    out = l2(torch.tanh(l1(x)))
+    out.square().sum().backward()
+    torch.cuda.synchronize()
+
+    t64 = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    X, A1, B1, A2, B2 = t64(synth.widen(xs, "f32")), t64(h1["A"]), t64(h1["B"]), t64(h2["A"]), t64(h2["B"])
+    W1, W2, b1 = torch.tensor(h1["W"]), torch.tensor(h2["W"]), torch.tensor(h1["bias"])
+    s = 16.0 / r
+    hid = torch.tanh(X @ W1 + b1 + s * (X @ A1) @ B1)
+    ref = hid @ W2 + s * (hid @ A2) @ B2
+    ref.square().sum().backward()
+    for got, want, name in ((x.grad, X.grad, "x"), (l1.lora_A.grad, A1.grad, "A1"), (l1.lora_B.grad, B1.grad, "B1"),
+                            (l2.lora_A.grad, A2.grad, "A2"), (l2.lora_B.grad, B2.grad, "B2")):
+        assert relerr(to_f64(got), want.numpy()) < 1e-4, name
+
+
+def test_memory_kept_between_forward_and_backward():
+    """What stays allocated after the forward, beyond the output: n*r elements for the default chain's
+    XA, nothing for forward1/forward2, i*o elements when forward2 keeps W + AB."""
+    import torch
+    n, d_in, d_out, r = 4096, 1024, 2048, 64
+    code = rl.RL_BF16
+    xs = to_device(synth.store(synth.normal(61, 1, (n, d_in)), "bf16"), "bf16").requires_grad_(True)
+    held = {}
+    for name, pair, keep in (("default", (0, 0), False), ("fwd1", (1, 1), False), ("fwd2", (2, 5), False), ("fwd2+M", (2, 5), True)):
+        layer, _ = make_layer(d_in, d_out, r, "bf16", None, False, pair, keep)
+        layer(xs).sum().backward()      # warm: workspace and autograd buffers exist
+        layer.zero_grad(); xs.grad = None
+        torch.cuda.synchronize()
+        before = torch.cuda.memory_allocated()
+        y = layer(xs)
+        torch.cuda.synchronize()
+        held[name] = torch.cuda.memory_allocated() - before - y.numel() * 2
+        y.sum().backward()
+        del y
+    assert held["fwd1"] == 0 and held["fwd2"] == 0
+    assert held["default"] == rl.runlora_saved_bytes(0, n, d_in, d_out, r, code) == n * r * 2
+    assert held["fwd2+M"] == rl.runlora_saved_bytes(2, n, d_in, d_out, r, code, keep_merged=True) == d_in * d_out * 2
+
+
+def test_wrap_linears_replaces_and_freezes():
+    import torch
+    from torch import nn
+    from paper_2312_03415_amd.module import RunLoRALinear, wrap_linears
+
+    class Block(nn.Module):
+        def __init__(self):
+            super().__init__()
+            self.q_proj = nn.Linear(64, 64, bias=False)
+            self.up = nn.Linear(64, 136)
+            self.down = nn.Linear(136, 64)
+            self.norm = nn.LayerNorm(64)
+
+        def forward(self, x):
+            return self.norm(x + self.down(torch.relu(self.up(self.q_proj(x)))))
+
+    torch.manual_seed(0)
+    model = Block().cuda()
+    x = torch.randn(5, 40, 64, device="cuda")
+    want = model(x)
+    names = wrap_linears(model, r=8, alpha=16, targets=("q_proj", "down"))
+    assert sorted(names) == ["down", "q_proj"]
+    assert isinstance(model.q_proj, RunLoRALinear) and isinstance(model.down, RunLoRALinear) and isinstance(model.up, nn.Linear)
+    trainable = sorted(n for n, p in model.named_parameters() if p.requires_grad)
+    assert trainable == ["down.lora_A", "down.lora_B", "q_proj.lora_A", "q_proj.lora_B"]
+    got = model(x)                      # B = 0 at the start: the wrapped model is the original one
+    assert relerr(to_f64(got.reshape(-1, 64)), to_f64(want.reshape(-1, 64))) < 1e-5
+    got.square().mean().backward()
+    assert model.q_proj.lora_B.grad is not None and model.q_proj.lora_B.grad.abs().sum().item() > 0
+    assert model.q_proj._pairs and list(model.q_proj._pairs) == [200]
