@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--rank", type=int, default=None, help="LoRA rank override (llama7b: 8/32/128)")
     ap.add_argument("--sets", type=int, default=3, help="rotating input/output sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--keep-merged", action="store_true",
+                    help="let forward2 keep W + AB for backward4/5 (i*o elements held per layer; pairs chosen for that)")
+    ap.add_argument("--pair", default=None, help="force one 'fwd,bwd' pair on every layer instead of runlora_select")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a 1 GiB device copy five times (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -106,8 +109,12 @@ def main():
             t["dX"] = torch.empty((L.n, L.i), dtype=tdt, device=dev)
             t["dA"] = torch.empty((L.i, L.r), dtype=tdt, device=dev)
             t["dB"] = torch.empty((L.r, L.o), dtype=tdt, device=dev)
+            t["M"] = torch.empty((L.i, L.o), dtype=tdt, device=dev) if args.keep_merged else None
             sets.append(t)
-        fwd, bwd = rl.runlora_select(L.n, L.i, L.o, L.r, code)
+        if args.pair:
+            fwd, bwd = (int(v) for v in args.pair.split(","))
+        else:
+            fwd, bwd = rl.runlora_select(L.n, L.i, L.o, L.r, code, criterion=2 if args.keep_merged else None)
         ws_bytes = max(rl.runlora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code),
                        rl.runlora_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code))
         ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
@@ -117,7 +124,7 @@ def main():
         for st in state:
             t = st["sets"][k % args.sets]
             fwd, bwd = (0, 0) if default_chain else st["pair"]
-            saved = rl.new_saved(t["T"] if fwd == 0 else None)
+            saved = rl.new_saved(t["T"] if fwd == 0 else None, t["M"] if fwd == 2 and bwd in rl.BWD_MERGED else None)
             rl.runlora_forward(fwd, t["X"], t["W"], t["A"], t["B"], t["Y"], saved, workspace=st["ws"])
             rl.runlora_backward(bwd, t["dY"], saved, t["W"], t["A"], t["B"], t["dX"], t["dA"], t["dB"],
                                 workspace=st["ws"])
@@ -216,7 +223,8 @@ def main():
         "ms_per_step": round(sec_sel * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": wl_name, "layers": [dict(name=L.name, n=L.n, d_in=L.i, d_out=L.o, r=L.r) for L in layers],
-                   "pairs": {st["L"].name: list(st["pair"]) for st in state}, "input_sets": args.sets},
+                   "pairs": {st["L"].name: list(st["pair"]) for st in state}, "input_sets": args.sets,
+                   "keep_merged": bool(args.keep_merged)},
         "ms_per_step_default_chain": round(sec_def * 1e3, 4),
         "speedup_over_default_chain": round(sec_def / sec_sel, 4),
         "time_reduction_pct": round(100.0 * (sec_def - sec_sel) / sec_def, 2),
