@@ -261,7 +261,11 @@ hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPla
     }
     blocks += P.row_blocks;
   }
-  dim3 grid((unsigned)blocks, (unsigned)plan.splits, 1);
+  // one slot list per XCD: ceil(R0/8) + ceil(R1/8) workgroups on each (see skinny_kernel)
+  int64_t per_xcd = 0;
+  for (int w = 0; w < nprob; ++w) per_xcd += (a.p[w].row_blocks + 7) / 8;
+  (void)blocks;
+  dim3 grid((unsigned)(8 * per_xcd), (unsigned)plan.splits, 1);
   switch (dtype) {
     case DT_BF16: return skinny_launch_bf16(plan.rt, a, grid, plan.splits, stream);
     case DT_F16: return skinny_launch_f16(plan.rt, a, grid, plan.splits, stream);

@@ -239,19 +239,23 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
 template <typename T, int RT, int NWV, int AL, int BL0, int BL1>
 __global__ __launch_bounds__(NWV * 64) void skinny_kernel(SkinnyArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  // Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Renumber
-  // so that neighbouring row blocks run on the same XCD: a [K,M] operand is read in 64-byte column
-  // strips, and the two strips that share a 128-byte line should be fetched through one L2.
-  int bx = blockIdx.x;
-  {
-    const int total = gridDim.x;
-    const int x = bx & 7, slot = bx >> 3, q = total >> 3, rem = total & 7;
-    bx = x * q + (x < rem ? x : rem) + slot;
+  // Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2 and its own
+  // path to memory.  Renumber so that (a) neighbouring row blocks of a problem run on the same XCD: a
+  // [K,M] operand is read in 64-byte column strips, and the two strips that share a 128-byte line
+  // should be fetched through one L2; and (b) each problem of a paired launch is spread over all
+  // eight XCDs in proportion: XCD x takes the x-th eighth of problem 0's row blocks, then the x-th
+  // eighth of problem 1's.  (Dealing the ids out problem after problem would put a long problem on
+  // half of the XCDs and leave the other half idle once the short one is done.)  The grid holds
+  // 8 * (ceil(R0/8) + ceil(R1/8)) workgroups; the few without a row block leave at once.
+  const int x = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int R0 = g.p[0].row_blocks, R1 = g.nprob > 1 ? g.p[1].row_blocks : 0;
+  const int n0 = R0 / 8 + (x < (R0 & 7) ? 1 : 0), s0 = x * (R0 / 8) + (x < (R0 & 7) ? x : (R0 & 7));
+  if (slot < n0) {
+    skinny_body<T, RT, NWV, AL, BL0>(g.p[0], s0 + slot, smem_raw);
+    return;
   }
-  if (g.nprob > 1 && bx >= g.p[0].row_blocks)
-    skinny_body<T, RT, NWV, AL, BL1>(g.p[1], bx - g.p[0].row_blocks, smem_raw);
-  else
-    skinny_body<T, RT, NWV, AL, BL0>(g.p[0], bx, smem_raw);
+  const int n1 = R1 / 8 + (x < (R1 & 7) ? 1 : 0), s1 = x * (R1 / 8) + (x < (R1 & 7) ? x : (R1 & 7));
+  if (slot - n0 < n1) skinny_body<T, RT, NWV, AL, BL1>(g.p[1], s1 + (slot - n0), smem_raw);
 }
 
 // Second stage for a K split over workgroups: C = sum over slices (in slice order) of the fp32
