@@ -137,3 +137,39 @@ def test_streaming_kernel_alpha():
         rl.runlora_gemm(dev["A"], dev["B"], C, tile_cfg=8, splits=splits, alpha=0.3)
         torch.cuda.synchronize()
         assert relerr(to_f64(C), 0.3 * oracle.matmul(host["A"], host["B"])) < TOL["bf16"], splits
+
+
+def test_layer_calls_can_be_captured_in_a_hip_graph():
+    """The library allocates nothing, never synchronises and records no memset: a forward + backward
+    captured once must give the eager bits on every replay, with eager work on other inputs between
+    the replays (the shared workspace is overwritten in between on purpose)."""
+    import torch
+    L = synth.Layer("graph", 333, 264, 392, 16, "bf16", 35)
+    dev, _ = layer_on_device(L)
+    other, _ = layer_on_device(synth.Layer("graph2", 333, 264, 392, 16, "bf16", 36))
+    code = rl.dtype_from_name(L.dtype)
+    for fwd, bwd in [(1, 1), (2, 5), (0, 0), (1, 3)]:
+        ws = rl.new_workspace(fwd, bwd, L.n, L.i, L.o, L.r, code)
+        mk = lambda *shape: torch.full(shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+        out = {"Y": mk(L.n, L.o), "dX": mk(L.n, L.i), "dA": mk(L.i, L.r), "dB": mk(L.r, L.o)}
+        T = mk(L.n, L.r) if fwd == 0 else None
+
+        def run(d):
+            saved = rl.new_saved(T)
+            rl.runlora_forward(fwd, d["X"], d["W"], d["A"], d["B"], out["Y"], saved, workspace=ws)
+            rl.runlora_backward(bwd, d["dY"], saved, d["W"], d["A"], d["B"], out["dX"], out["dA"], out["dB"], workspace=ws)
+
+        run(dev)                       # eager: reference bits (and one-time kernel attribute set-up)
+        torch.cuda.synchronize()
+        want = {k: v.clone() for k, v in out.items()}
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run(dev)
+        for _ in range(3):
+            run(other)                 # eager work in between: other values in the outputs and the workspace
+            torch.cuda.synchronize()
+            assert not torch.equal(out["Y"], want["Y"])
+            g.replay()
+            torch.cuda.synchronize()
+            for k in out:
+                assert torch.equal(out[k], want[k]), (fwd, bwd, k)
