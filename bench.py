@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="opt13b", choices=["opt13b", "llama7b"])
+    ap.add_argument("--workload", default="opt13b", choices=["opt13b", "llama7b", "qlora"])
     ap.add_argument("--rank", type=int, default=None, help="LoRA rank override (llama7b: 8/32/128)")
     ap.add_argument("--sets", type=int, default=3, help="rotating input/output sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -82,9 +82,15 @@ def main():
         if args.rank:
             layers = [synth.Layer(L.name, L.n, L.i, L.o, args.rank, L.dtype, L.index) for L in layers]
         wl_name = "OPT-1.3B-shaped MLP pair, tokens 8x512=4096, fc1 2048x8192 + fc2 8192x2048, r=%d" % layers[0].r
-    else:
+    elif args.workload == "llama7b":
         layers = synth.config_llama7b(args.rank or 32, "bf16")
         wl_name = "Llama-7B-shaped block, tokens 4x2048=8192, q/k/v/o + gate/up + down, r=%d" % layers[0].r
+    else:
+        layers = synth.config_qlora()
+        if args.rank:
+            layers = [synth.Layer(L.name, L.n, L.i, L.o, args.rank, L.dtype, L.index) for L in layers]
+        wl_name = "frozen W 5120x13824 as int4 (groups of 64, fp16 scales), tokens 4096, r=%d, bf16 activations" % layers[0].r
+    int4 = args.workload == "qlora"
     dtype = layers[0].dtype
     code = rl.dtype_from_name(dtype)
     tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dtype]
@@ -101,9 +107,13 @@ def main():
         st = synth.layer_inputs(L)
         host_inputs.append(st)
         base = {k: to_dev(v) for k, v in st.items()}
+        if int4:  # the frozen weight in its 4-bit form; the dense copy is only the CPU baseline's
+            q, scale = synth.int4_weight(L)
+            base["W"] = rl.Int4Weight.from_host(q, scale)
+            st["W"] = synth.store(q.astype(np.float64) * np.repeat(scale.astype(np.float64), 64, axis=0)[:L.i], dtype)
         sets = []
         for s in range(args.sets):
-            t = {k: (v if s == 0 else v.clone()) for k, v in base.items()}
+            t = {k: (v if (s == 0 or k == "W" and int4) else v.clone()) for k, v in base.items()}
             t["Y"] = torch.empty((L.n, L.o), dtype=tdt, device=dev)
             t["T"] = torch.empty((L.n, L.r), dtype=tdt, device=dev)
             t["dX"] = torch.empty((L.n, L.i), dtype=tdt, device=dev)
@@ -114,9 +124,11 @@ def main():
         if args.pair:
             fwd, bwd = (int(v) for v in args.pair.split(","))
         else:
-            fwd, bwd = rl.runlora_select(L.n, L.i, L.o, L.r, code, criterion=2 if args.keep_merged else None)
-        ws_bytes = max(rl.runlora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code),
-                       rl.runlora_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code))
+            fwd, bwd = rl.runlora_select(L.n, L.i, L.o, L.r, rl.RL_INT4_G64 if int4 else code,
+                                         criterion=2 if args.keep_merged else None)
+        wd = rl.RL_INT4_G64 if int4 else None
+        ws_bytes = max(rl.runlora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code, wd),
+                       rl.runlora_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code, wd))
         ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
         state.append(dict(L=L, sets=sets, pair=(fwd, bwd), ws=ws))
 
@@ -145,8 +157,8 @@ def main():
     # ---- useful FLOPs: the fewest any legal pair needs ---------------------------------------
     def useful_flops(L):
         best = None
-        for f in (0, 1, 2):
-            for b in (0, 1, 2, 3, 4, 5):
+        for f in ((0, 1) if int4 else (0, 1, 2)):          # an int4 W has no merged-weight graphs
+            for b in ((0, 1, 2, 3) if int4 else (0, 1, 2, 3, 4, 5)):
                 if b == 0 and f != 0:
                     continue
                 fl = rl.runlora_flops(0, f, L.n, L.i, L.o, L.r) + rl.runlora_flops(1, b, L.n, L.i, L.o, L.r)

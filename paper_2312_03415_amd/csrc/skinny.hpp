@@ -6,8 +6,9 @@
 // operand is used for only ~r FLOPs, so the kernel is HBM-bandwidth bound and is built for bytes in
 // flight rather than for MFMA occupancy.
 //
-//  - One workgroup = 8 wavefronts that share a block of 32 output rows and split the workgroup's K
-//    range between them (wave w takes K tiles w, w+8, ...).  Every wavefront runs its own
+//  - One workgroup = NWV (4) wavefronts that share a block of 32 output rows and split the
+//    workgroup's K range between them (wave w takes K tiles w, w+NWV, ...; 8 or 16 wavefronts per
+//    workgroup measured slower).  Every wavefront runs its own
 //    global -> register -> LDS -> MFMA pipeline on a private LDS region: no workgroup barrier in the
 //    loop, the next tile's loads are in flight while the current one is multiplied.
 //  - The waves' partial accumulators are summed through LDS in wave order and written once.  A grid
@@ -194,7 +195,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
     }
   }
 
-  // ---- sum the four waves' accumulators in wave order through LDS ------------------------------
+  // ---- sum the waves' accumulators in wave order through LDS ------------------------------
   __syncthreads();  // every wave is done with its staging region
   float* red = reinterpret_cast<float*>(smem_raw);
   {
