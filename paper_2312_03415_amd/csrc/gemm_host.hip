@@ -83,9 +83,10 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
 }
 
 GemmPlan gemm_plan_int4(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1) {
-  // an int4 B runs on the generic engine: 256x256 tiles when they fill the chip, else 128x128
+  // an int4 B runs on the matrix-core kernel when its 256x256 tiles fill the chip, else on the
+  // generic engine's 128x128 tiles
   const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  return gemm_plan(dtype, M, N, K0, K1, big_tiles >= 160 ? CFG_BIG : CFG_MID, 0);
+  return gemm_plan(dtype, M, N, K0, K1, big_tiles >= 160 ? CFG_MC3 : CFG_MID, 0);
 }
 
 hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream) {
@@ -115,7 +116,8 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   }
   if (plan.splits > 1 && scratch == nullptr) return hipErrorInvalidValue;
   int cfg = plan.cfg;
-  if (d.Bscale != nullptr && cfg != CFG_BIG && cfg != CFG_MID) return hipErrorInvalidValue;  // see gemm_plan_int4
+  if (d.Bscale != nullptr && cfg != CFG_BIG && cfg != CFG_MID && cfg != CFG_MC3) return hipErrorInvalidValue;  // see gemm_plan_int4
+  if (d.Bscale != nullptr && d.a_strided) return hipErrorInvalidValue;
   if (cfg == CFG_MC3 || cfg == CFG_MC4) {
     // the matrix-core kernel addresses each operand with 32-bit byte offsets, clamps a strided
     // operand's last columns to [dim-8, dim) and wants every K slice to hold at least one K tile

@@ -55,9 +55,18 @@ constexpr int mc_wait_imm(int vm, bool lgkm_zero) {
 }
 
 // The kernel body is a device function (the buffer-descriptor builtins exist only in device code).
-template <typename T, int AL, int BL, int NS>
+// BQ: B of segment 0 is int4 with fp16 group scales (GemmArgs::Bscale).  The B half of a K tile then
+// does not go to LDS by LDS-DMA: every lane fetches, for each of its four 16-byte LDS slots, the eight
+// 4-bit weights (one dword) and their eight scales (16 bytes) into registers during K step 0 of one
+// tile, and during K step 0 of the next tile writes the dequantised 16 bytes to the very slot the
+// LDS-DMA load of a dense B would have filled; the tile after that reads them.  Everything downstream (swizzle, fragment reads,
+// MFMAs) is unchanged.  The dense second segment of a K-concatenated product takes the same route
+// with its 16 bytes passed through, so that every K tile issues the same number of loads (the
+// waits count them).
+template <typename T, int AL, int BL, int NS, bool BQ = false>
 __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   using P = McTile<AL, BL, NS>;
+  static_assert(!BQ || (NS == 3 && AL == 0), "int4 B: 3-stage ring, A stored [M,K]");
   constexpr int BM = P::BM, BN = P::BN, BK = P::BK, IPW = P::IPW;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   unsigned char* smem = smem_raw;
@@ -138,6 +147,27 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   uint32_t kA = 0, kB = 0;            // byte offset of the cursor's tile (k origin) in its segment (uniform)
   uint32_t stepA = 0, stepB = 0;      // bytes from one K tile to the next in the current segment
   uint32_t offA[IPW], offB[IPW];      // per-lane byte offsets, one per instruction
+  // BQ: register route of the B half.  rsQ / offBq / kBq address the dword of eight 4-bit weights of
+  // each slot, rsS / offBs / kBs its eight fp16 scales; in the dense second segment both address the
+  // slot's 16 bytes of B itself.
+  auto plain_rsrc = [&](const void* base, uint64_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (uint32_t)bytes, 0x00020000);
+  };
+  const uint32_t ldbs2 = 2u * (uint32_t)g.ldbs;
+  __amdgpu_buffer_rsrc_t rsQ0 = rsB0, rsS0 = rsB0, rsD1 = rsB0, rsQ = rsB0, rsS = rsB0;
+  if constexpr (BQ) {
+    // W as the kernel sees it: [N, K0] with K contiguous (dY W^T) or [K0, N] (X W)
+    const uint64_t w_rows = P::B_STR ? (uint64_t)K0 : (uint64_t)g.N, w_cols = P::B_STR ? (uint64_t)g.N : (uint64_t)K0;
+    rsQ0 = plain_rsrc(g.B[0], ((w_rows - 1) * ldb0 + w_cols + 1) / 2);
+    rsS0 = plain_rsrc(g.Bscale, (((w_rows + 63) / 64 - 1) * (uint64_t)g.ldbs + w_cols) * 2);
+    rsD1 = plain_rsrc(g.B[1], extent_bytes(P::B_STR, g.N, K1, ldb1));
+    rsQ = rsQ0;
+    rsS = rsS0;
+  }
+  uint32_t kBq = 0, kBs = 0, stepBq = 0;
+  uint32_t offBq[IPW], offBs[IPW];
+  int cts = 0;       // K tile index of the cursor inside its segment
+  bool cq = false;   // the cursor's segment is the int4 one
 
   // Rebuild the state for tile cu of work item cw (tile origin cm0, cn0).  Rows / columns beyond the
   // matrix are clamped: they only feed outputs that are never stored.  In a partial tile the chunks
@@ -171,14 +201,33 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
       {
         const int row = P::B_STR ? (p >> 5) : (p >> 2);
         const int col = P::B_STR ? (((p & 31) ^ (4 * (row & 3))) << 3) : (((p & 3) ^ ((row >> 2) & 3)) << 3);
+        uint32_t elem, sc;  // element offset of the slot's first value in B; byte offset of its scales
         if constexpr (!P::B_STR) {
           int gr = cn0 + row; gr = gr < g.N ? gr : g.N - 1;
-          offB[j] = 2u * ((uint32_t)gr * ldb + (uint32_t)(col < kvalid ? col : 0)) + (kBias - 1024u * j);
+          const uint32_t c = (uint32_t)(col < kvalid ? col : 0);
+          elem = (uint32_t)gr * ldb + c;
+          sc = (uint32_t)(gr >> 6) * ldbs2 + 2u * c;
         } else {
           int gc = cn0 + col; gc = gc < g.N ? gc : g.N - 8;
-          offB[j] = 2u * ((uint32_t)(row < kvalid ? row : 0) * ldb + (uint32_t)gc) + (kBias - 1024u * j);
+          elem = (uint32_t)(row < kvalid ? row : 0) * ldb + (uint32_t)gc;
+          sc = 2u * (uint32_t)gc;
+        }
+        offB[j] = 2u * elem + (kBias - 1024u * j);
+        if constexpr (BQ) {
+          offBq[j] = seg == 0 ? elem / 2u : 2u * elem;
+          offBs[j] = seg == 0 ? sc : 2u * elem;
         }
       }
+    }
+    if constexpr (BQ) {
+      cq = seg == 0;
+      cts = ts;
+      rsQ = cq ? rsQ0 : rsD1;
+      rsS = cq ? rsS0 : rsD1;
+      // (wave-uniform by construction; said explicitly so that they stay in scalar registers)
+      stepBq = __builtin_amdgcn_readfirstlane(cq ? stepB / 4u : stepB);
+      kBq = __builtin_amdgcn_readfirstlane((uint32_t)ts * stepBq);
+      kBs = __builtin_amdgcn_readfirstlane(cq ? (P::B_STR ? (uint32_t)(ts >> 1) * ldbs2 : (uint32_t)ts * (2u * BK)) : kBq);
     }
     // the next tile index at which the state must be rebuilt again
     if (kvalid < BK) {
@@ -227,6 +276,40 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 #pragma unroll
     for (int j = 0; j < IPW; ++j) issue_B1(st, j);
   };
+  // BQ: the B half of the cursor's K tile into register set PAR, and a set into its LDS slots.
+  uint32_t rw[IPW];   // eight 4-bit weights per slot
+  i32x4 rsc[IPW];     // their eight fp16 scales (or, in the dense segment, the slot's 16 bytes of B)
+  bool setq = false, setq_next = false;  // the registers hold int4 weights (uniform)
+  auto load_B = [&](int j) {
+    if constexpr (BQ) {
+      // (the scalar offsets are wave-uniform; saying so keeps the loads free of per-lane loops)
+      rw[j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rsQ, offBq[j], __builtin_amdgcn_readfirstlane(kBq), 0);
+      rsc[j] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsS, offBs[j], __builtin_amdgcn_readfirstlane(kBs), 0));
+      if (j == 0) setq_next = cq;
+    }
+  };
+  // pair e2 (values 2 e2, 2 e2 + 1) of slot j; the fourth pair completes the slot and stores it
+  uint32_t dq[IPW];
+  auto commit_B = [&](int stage, int j, int e2) {
+    if constexpr (BQ) {
+      const uint32_t scp = (uint32_t)rsc[j][e2];
+      const uint32_t x = rw[j] ^ 0x88888888u;  // offset-binary nibble -> two's complement
+      const int q0 = (int)(x << (28 - 8 * e2)) >> 28, q1 = (int)(x << (24 - 8 * e2)) >> 28;
+      typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+      typedef float f32x2_t __attribute__((ext_vector_type(2)));
+      typedef T tx2_t __attribute__((ext_vector_type(2)));
+      const f16x2_t sp = __builtin_bit_cast(f16x2_t, scp);
+      // q * scale is exact in fp32 (4 bits x 11 bits); written as a fused multiply-add with +0 so that
+      // the fp16 scale feeds the mixed-precision FMA directly; one rounding to T, two values at a time
+      const f32x2_t f = {__builtin_fmaf((float)q0, (float)sp[0], 0.f), __builtin_fmaf((float)q1, (float)sp[1], 0.f)};
+      const uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, tx2_t));
+      dq[e2] = setq ? packed : scp;
+      if (e2 == 3) {
+        i32x4 v = {(int)dq[0], (int)dq[1], (int)dq[2], (int)dq[3]};
+        *reinterpret_cast<i32x4*>(smem + stage * P::STAGE_BYTES + P::A_BYTES + (wave * IPW + j) * 1024 + lane * 16) = v;
+      }
+    }
+  };
   // Move the cursor on.  Past the last work item it stays on the last tile, which is then fetched
   // again (into a stage nobody reads), so that the number of loads in flight, which the waits below
   // count, never changes.
@@ -236,6 +319,11 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
     if (cu != cnext) {
       kA += stepA;
       kB += stepB;
+      if constexpr (BQ) {
+        ++cts;
+        kBq = __builtin_amdgcn_readfirstlane(kBq + stepBq);
+        kBs = __builtin_amdgcn_readfirstlane(cq ? (P::B_STR ? (uint32_t)(cts >> 1) * ldbs2 : (uint32_t)cts * (2u * BK)) : kBq);
+      }
       return;
     }
     if (cu == cu_end) {
@@ -339,7 +427,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   // A wave issues at most one instruction per 4 cycles and an MFMA occupies the matrix core for 32, so
   // up to ~7 other instructions fit behind each MFMA; spreading them keeps the matrix core fed, and
   // spreading the loads keeps the four waves from flooding the address unit at the same moment.
-  auto kstep = [&](auto ksr_c, int bufc, int bufr, uint32_t soff, auto issue_one) {
+  auto kstep = [&](auto ksr_c, int bufc, int bufr, uint32_t soff, auto issue_one, auto behind) {
     wait_tr(bufc);
     MC_FENCE();
     int j = 0;
@@ -354,12 +442,14 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
         fb[bufr][q - 4] = read_frag_op(P::B_STR, fragB, soff, q - 4, ksr_c);
         MC_FENCE();
       }
+      behind(q);  // further work placed behind MFMA q (the int4 route's dequantisation)
       if (MC_VMEM_AT(q)) {
         issue_one(j++);
         MC_FENCE();
       }
     }
   };
+  auto nothing = [](int) {};
   // all of this wave's LDS reads are complete and at most `vm` of its loads are in flight; then
   // the workgroup barrier.  The empty asm statements keep the compiler from moving memory
   // accesses across it.
@@ -375,14 +465,37 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 
   // ---- prologue: fill the ring (the last tile only by its A half: the loop issues B halves in K
   // step 0 and A halves in K step 1), wait for the first tile
+  // loads per K tile and wave on the int4 route: 4 LDS-DMA (A) + 4 x (weights dword + scales)
+  constexpr int LPTQ = IPW + 2 * IPW;
+  if constexpr (!BQ) {
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s) {
-    issue_A(s);
-    issue_B(s);
+    for (int s = 0; s < NS - 1; ++s) {
+      issue_A(s);
+      issue_B(s);
+      cursor_advance();
+    }
+    issue_A(NS - 1);
+    MC_SYNC((NS - 2) * P::LPT + IPW);
+  } else {
+    // B of tile 0 goes to LDS at once; B of tile 1 waits in the registers for K step 0 of tile 0
+    issue_A(0);
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) load_B(j);
+    setq = setq_next;
     cursor_advance();
+#pragma unroll
+    for (int j = 0; j < IPW; ++j)
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) commit_B(0, j, e2);
+    issue_A(1);
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) load_B(j);
+    setq = setq_next;
+    cursor_advance();
+    issue_A(2);
+    // A of tile 0 is older than everything else issued here
+    MC_SYNC(2 * LPTQ);
   }
-  issue_A(NS - 1);
-  MC_SYNC((NS - 2) * P::LPT + IPW);
   {
     using K0c = std::integral_constant<int, 0>;
 #pragma unroll
@@ -414,12 +527,26 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
       }
       // K step 0 out of buffer 0; K step 1's fragments go to buffer 1; second half of the fetch
       // that the previous K step began
-      kstep(std::integral_constant<int, 1>{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES), [&](int j) { issue_B1(stp, j); });
+      if constexpr (!BQ) {
+        kstep(std::integral_constant<int, 1>{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES), [&](int j) { issue_B1(stp, j); }, nothing);
+      } else {
+        // int4 route: behind MFMA q, pair q % 4 of slot q / 4 of the next tile's B (fetched during
+        // the previous tile) is dequantised; a completed slot goes to the next tile's stage and its
+        // registers are refilled with the B half of the cursor's tile.
+        kstep(std::integral_constant<int, 1>{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES), [&](int j) { load_B(j); },
+              [&](int q) { commit_B(stn, q >> 2, q & 3); MC_FENCE(); });
+        setq = setq_next;
+      }
       cursor_advance();
       // Tile u+1 must have landed (own loads, then everyone's: loads return in order, so "at most
       // (NS-2) tiles' worth outstanding" means tile u+1 is in), and everyone must be done reading
-      // stage st before it is refilled.
-      MC_SYNC((NS - 2) * P::LPT);
+      // stage st before it is refilled.  (Int4 route: the loads issued after A of tile u+1 are the B
+      // halves of tiles u+1, u+2 and the A half of tile u+2.)
+      if constexpr (!BQ) {
+        MC_SYNC((NS - 2) * P::LPT);
+      } else {
+        MC_SYNC(2 * 2 * IPW + IPW);
+      }
       if (kvalid < BK) {
         wait_tr(1);
         mask_frags(1, 1, kvalid);
@@ -427,7 +554,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
       }
       // K step 1 out of buffer 1, with the next tile's first fragments and the first half of the
       // refill of stage st
-      kstep(std::integral_constant<int, 0>{}, 1, 0, (uint32_t)(stn * P::STAGE_BYTES), [&](int j) { issue_A1(st, j); });
+      kstep(std::integral_constant<int, 0>{}, 1, 0, (uint32_t)(stn * P::STAGE_BYTES), [&](int j) { issue_A1(st, j); }, nothing);
       stp = st;
       st = stn;
     }
@@ -447,9 +574,9 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 #undef MC_FENCE
 }
 
-template <typename T, int AL, int BL, int NS>
+template <typename T, int AL, int BL, int NS, bool BQ = false>
 __global__ __launch_bounds__(256, 1) void gemm_mc_kernel(GemmArgs g) {
-  gemm_mc_body<T, AL, BL, NS>(g);
+  gemm_mc_body<T, AL, BL, NS, BQ>(g);
 }
 
 }  // namespace rl

@@ -122,3 +122,27 @@ def test_int4_config_shape_sampled_rows():
     assert relerr(got["dA"], oracle.matmul(host["X"], Z1, ta=True)) < TOL["bf16"]
     Tm = oracle.matmul(host["X"], host["A"])
     assert relerr(got["dB"], oracle.matmul(Tm, host["dY"], ta=True)) < TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_int4_matrix_core_route_ragged(dtype):
+    """Large enough for the matrix-core kernel's int4 route (>= 160 tiles of 256x256) and ragged in
+    every direction: n not a multiple of the tile, d_in = 32*64 + 8 (a partial last K tile and a
+    partial last scale group for X W), d_out = 32*112 + 8 (the same for dY W^T), r = 24 (a partial K
+    tile in the dense second segment).  Y and dX on sampled rows (first and last row of every tile
+    row, plus random ones), dA and dB in full; also the default chain, whose dX GEMM has no second
+    segment."""
+    L = synth.Layer("int4mc", 3001, 2056, 3592, 24, dtype, 12)
+    dev, host = make_layer(L)
+    rows = np.unique(np.concatenate([np.arange(0, L.n, 256), np.arange(255, L.n, 256), [L.n - 1],
+                                     np.random.default_rng(6).integers(0, L.n, 24)]))
+    Yr, dXr = oracle.reference_rows(host["X"][rows], host["dY"][rows], host["W"], host["A"], host["B"])
+    dA = oracle.matmul(host["X"], oracle.matmul(host["dY"], host["B"], tb=True), ta=True)
+    dB = oracle.matmul(oracle.matmul(host["X"], host["A"]), host["dY"], ta=True)
+    for f, b in [(1, 1), (0, 0)]:
+        print(f"case int4 matrix-core dtype={dtype} fwd={f} bwd={b}", flush=True)
+        got = run_pair(L, dev, f, b)
+        assert not np.isnan(got["Y"]).any() and not np.isnan(got["dX"]).any()
+        assert relerr(got["Y"][rows], Yr) < TOL[dtype], (f, b)
+        assert relerr(got["dX"][rows], dXr) < TOL[dtype], (f, b)
+        assert relerr(got["dA"], dA) < TOL[dtype] and relerr(got["dB"], dB) < TOL[dtype]
