@@ -24,9 +24,10 @@ struct GemmDesc {
   const void* D = nullptr;  // optional addend, same dtype as C (may alias C)
   int64_t ldd = 0;
   // B[0] is symmetric int4 (packed nibbles, ldb[0] in elements) with fp16 group scales
-  // [rows/64, ldbs]; nullptr = dense.  16-bit types, generic engine only.
+  // [rows/64, ldbs]; nullptr = dense.  16-bit types, A stored [M,K].
   const void* Bscale = nullptr;
   int64_t ldbs = 0;
+  bool b_int4 = false;  // B[0] is int4 (set together with Bscale; also when only shapes are modelled)
   // C = alpha * (sum of the products) + D + bias;  bias: row vector [N] of the dtype, or nullptr
   float alpha = 1.f;
   const void* bias = nullptr;
@@ -56,9 +57,13 @@ struct GemmPlan {
 // the same plan sizes the workspace and drives the launch.  force_cfg / force_splits (>= 0 / > 0)
 // override the heuristics (used by the tuning sweeps and tests).
 GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg = -1,
-                   int force_splits = 0);
+                   int force_splits = 0, bool b_int4 = false);
 
-// Plan for a product whose B[0] is int4 (GemmDesc::Bscale): generic engine, two tile shapes.
+// Plan of the launch that computes the columns [main.tail_n0, N) cut off from `main`.
+GemmPlan gemm_tail_plan(const GemmPlan& main, int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1);
+
+// Plan for a product whose B[0] is int4 (GemmDesc::Bscale): matrix-core kernel or the generic
+// engine's 128x128 tile.
 GemmPlan gemm_plan_int4(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1);
 
 // Enqueue the product.  `scratch` must hold plan.partial_bytes when plan.splits > 1.

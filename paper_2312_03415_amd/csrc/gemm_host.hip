@@ -11,10 +11,15 @@ static const int kTileBN[CFG_COUNT] = {256, 128, 32, 64, 128, 128, 256, 256};
 static const int kTileBK16[CFG_COUNT] = {64, 64, 64, 64, 64, 64, 32, 32};  // K tile, 16-bit types
 
 GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg,
-                   int force_splits) {
+                   int force_splits, bool b_int4) {
   GemmPlan p;
   int cfg;
-  if (force_cfg >= 0 && force_cfg < CFG_COUNT) {
+  if (b_int4 && force_cfg < 0) {
+    // an int4 B runs on the matrix-core kernel (3-stage ring) when its 256x256 tiles fill the chip,
+    // else on the generic engine's 128x128 tiles
+    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    cfg = (big_tiles >= 160 || (big_tiles >= 80 && K0 + K1 >= 2048)) ? CFG_MC3 : CFG_MID;
+  } else if (force_cfg >= 0 && force_cfg < CFG_COUNT) {
     cfg = force_cfg;
     if ((cfg == CFG_MC3 || cfg == CFG_MC4) && dtype == DT_F32) cfg = CFG_BIG;  // 16-bit only
   } else if (M <= 32) {
@@ -66,27 +71,34 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   // ends on a round that is 3/8 full.  If whole tile columns can be cut off such that the rest is an
   // exact number of rounds and the cut-off part is small enough to be split along K, run that part
   // as a launch of its own (half a round with the contraction in two, plus its reduce).
-  if (force_cfg < 0 && force_splits <= 0 && p.cfg == CFG_MC4 && p.splits == 1 && tiles > 256 && ktiles >= 64) {
+  if (force_cfg < 0 && force_splits <= 0 && (p.cfg == CFG_MC4 || (b_int4 && p.cfg == CFG_MC3)) && p.splits == 1 &&
+      tiles > 256 && ktiles >= 64) {
     for (int t = p.nbn - 1; t >= 1 && t >= p.nbn - 16; --t) {
       const int64_t main_tiles = (int64_t)p.nbm * t, tail_tiles = (int64_t)p.nbm * (p.nbn - t);
       if (tail_tiles > 128) break;
       if (main_tiles % 256 != 0 || tail_tiles < 32) continue;
-      const GemmPlan tail = gemm_plan(dtype, M, N - (int64_t)t * p.bn, K0, K1);
-      if (tail.splits < 2) break;
       p.tail_n0 = (int64_t)t * p.bn;
       p.nbn = t;
-      p.partial_bytes = tail.partial_bytes;
+      p.partial_bytes = gemm_tail_plan(p, dtype, M, N, K0, K1).partial_bytes;
       break;
     }
   }
   return p;
 }
 
+GemmPlan gemm_tail_plan(const GemmPlan& main, int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1) {
+  // same kernel as the main launch, the contraction split so that (tiles x slices) is about one
+  // round of workgroups
+  const int64_t nt = N - main.tail_n0;
+  const int64_t tiles = (int64_t)main.nbm * ((nt + main.bn - 1) / main.bn);
+  int64_t splits = (256 + tiles - 1) / tiles;
+  if (splits < 2) splits = 2;
+  if (splits > 8) splits = 8;
+  return gemm_plan(dtype, M, nt, K0, K1, main.cfg, (int)splits);
+}
+
 GemmPlan gemm_plan_int4(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1) {
-  // an int4 B runs on the matrix-core kernel when its 256x256 tiles fill the chip, else on the
-  // generic engine's 128x128 tiles
-  const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  return gemm_plan(dtype, M, N, K0, K1, big_tiles >= 160 ? CFG_MC3 : CFG_MID, 0);
+  return gemm_plan(dtype, M, N, K0, K1, -1, 0, true);
 }
 
 hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream) {
@@ -103,14 +115,22 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
     dt.N = d.N - plan.tail_n0;
     for (int s = 0; s < d.nseg; ++s) {
       const int64_t off = d.b_kcontig ? plan.tail_n0 * d.ldb[s] : plan.tail_n0;
-      dt.B[s] = static_cast<const char*>(d.B[s]) + (size_t)off * esz;
+      if (s == 0 && d.Bscale != nullptr) {
+        // int4: two weights per byte; the scales of columns (B stored [K,N]) or of row groups
+        // (B stored [N,K]; tail_n0 is a multiple of 64) move along
+        dt.B[0] = static_cast<const char*>(d.B[0]) + (size_t)off / 2;
+        const int64_t soff = d.b_kcontig ? (plan.tail_n0 / 64) * d.ldbs : plan.tail_n0;
+        dt.Bscale = static_cast<const char*>(d.Bscale) + (size_t)soff * 2;
+      } else {
+        dt.B[s] = static_cast<const char*>(d.B[s]) + (size_t)off * esz;
+      }
     }
     dt.C = static_cast<char*>(d.C) + (size_t)plan.tail_n0 * esz;
     if (d.D) dt.D = static_cast<const char*>(d.D) + (size_t)plan.tail_n0 * esz;
     if (d.bias) dt.bias = static_cast<const char*>(d.bias) + (size_t)plan.tail_n0 * esz;
     hipError_t e = gemm_run(dm, pm, nullptr, stream);
     if (e != hipSuccess) return e;
-    const GemmPlan pt = gemm_plan(d.dtype, d.M, dt.N, d.K[0], d.nseg > 1 ? d.K[1] : 0);
+    const GemmPlan pt = gemm_tail_plan(plan, d.dtype, d.M, d.N, d.K[0], d.nseg > 1 ? d.K[1] : 0);
     if (pt.tail_n0 > 0 || pt.partial_bytes > plan.partial_bytes) return hipErrorInvalidValue;
     return gemm_run(dt, pt, scratch, stream);
   }

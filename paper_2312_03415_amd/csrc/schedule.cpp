@@ -47,6 +47,7 @@ struct Builder {
     d.ldc = C.ld;
     if (D) { d.D = D->ptr; d.ldd = D->ld; }
     if (b_is_w && L.w_int4) {
+      d.b_int4 = true;
       d.Bscale = B.scales;
       d.ldbs = B.lds;
       s.plan = gemm_plan_int4(L.dtype, M, N, K, K2);

@@ -48,7 +48,7 @@ static double gemm_time_us(const GemmDesc& d, const GemmPlan& p) {
     pm.tail_n0 = 0;
     dm.N = p.tail_n0;
     dt.N = d.N - p.tail_n0;
-    return gemm_time_us(dm, pm) + gemm_time_us(dt, gemm_plan(d.dtype, d.M, dt.N, d.K[0], d.nseg > 1 ? d.K[1] : 0));
+    return gemm_time_us(dm, pm) + gemm_time_us(dt, gemm_tail_plan(p, d.dtype, d.M, d.N, d.K[0], d.nseg > 1 ? d.K[1] : 0));
   }
   const TileModel& tm = mc.tile[d.dtype == DT_F32 ? 1 : 0][p.cfg];
   const int lay = d.a_strided ? 2 : (d.b_kcontig ? 1 : 0);
