@@ -57,12 +57,13 @@ constexpr int mc_wait_imm(int vm, bool lgkm_zero) {
 // The kernel body is a device function (the buffer-descriptor builtins exist only in device code).
 // BQ: B of segment 0 is int4 with fp16 group scales (GemmArgs::Bscale).  The B half of a K tile then
 // does not go to LDS by LDS-DMA: every lane fetches, for each of its four 16-byte LDS slots, the eight
-// 4-bit weights (one dword) and their eight scales (16 bytes) into registers during K step 0 of one
-// tile, and during K step 0 of the next tile writes the dequantised 16 bytes to the very slot the
-// LDS-DMA load of a dense B would have filled; the tile after that reads them.  Everything downstream (swizzle, fragment reads,
-// MFMAs) is unchanged.  The dense second segment of a K-concatenated product takes the same route
-// with its 16 bytes passed through, so that every K tile issues the same number of loads (the
-// waits count them).
+// 4-bit weights (one dword) and their eight scales (16 bytes) into registers, and one K tile later
+// writes the dequantised 16 bytes to the very slot the LDS-DMA load of a dense B would have filled, in
+// time for the tile after that.  The dequantisation runs one value behind each MFMA (sign-extending
+// bit-field extract, int -> float, mixed-precision FMA with the fp16 scale, packed conversion), two
+// slots per K step.  Everything downstream (swizzle, fragment reads, MFMAs) is unchanged.  The dense
+// second segment of a K-concatenated product takes the same route with its 16 bytes passed through,
+// so that every K tile issues the same number of loads (the waits count them).
 template <typename T, int AL, int BL, int NS, bool BQ = false>
 __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   using P = McTile<AL, BL, NS>;
@@ -252,20 +253,22 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   // over the MFMAs (a burst of loads from all four waves backs up the address unit and stalls issue).
   auto issue_A1 = [&](int st, int j) {  // j must be a constant after unrolling: it is the immediate offset
     unsigned char* sA = smem + st * P::STAGE_BYTES + wave * (IPW * 1024);
+    const uint32_t ukA = __builtin_amdgcn_readfirstlane(kA);  // wave-uniform: keeps the load free of a per-lane loop
     switch (j) {
-      case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[0], kA, 0, 0); break;
-      case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[1], kA, 1024, 0); break;
-      case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[2], kA, 2048, 0); break;
-      default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[3], kA, 3072, 0); break;
+      case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[0], ukA, 0, 0); break;
+      case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[1], ukA, 1024, 0); break;
+      case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[2], ukA, 2048, 0); break;
+      default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (mc_lds_void_t*)sA, 16, offA[3], ukA, 3072, 0); break;
     }
   };
   auto issue_B1 = [&](int st, int j) {
     unsigned char* sB = smem + st * P::STAGE_BYTES + P::A_BYTES + wave * (IPW * 1024);
+    const uint32_t ukB = __builtin_amdgcn_readfirstlane(kB);
     switch (j) {
-      case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[0], kB, 0, 0); break;
-      case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[1], kB, 1024, 0); break;
-      case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[2], kB, 2048, 0); break;
-      default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[3], kB, 3072, 0); break;
+      case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[0], ukB, 0, 0); break;
+      case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[1], ukB, 1024, 0); break;
+      case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[2], ukB, 2048, 0); break;
+      default: __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (mc_lds_void_t*)sB, 16, offB[3], ukB, 3072, 0); break;
     }
   };
   auto issue_A = [&](int st) {
@@ -276,35 +279,43 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 #pragma unroll
     for (int j = 0; j < IPW; ++j) issue_B1(st, j);
   };
-  // BQ: the B half of the cursor's K tile into register set PAR, and a set into its LDS slots.
+  // BQ: slot j of the B half of the cursor's K tile into registers, and one value of a slot on its
+  // way to LDS.  Slots 0,1 are refilled in K step 1 and slots 2,3 in the following K step 0 (the cursor
+  // does not move in between); one K tile later they are dequantised in the same two K steps, one
+  // value behind each MFMA, and stored to the stage of the tile that is multiplied next.
   uint32_t rw[IPW];   // eight 4-bit weights per slot
   i32x4 rsc[IPW];     // their eight fp16 scales (or, in the dense segment, the slot's 16 bytes of B)
-  bool setq = false, setq_next = false;  // the registers hold int4 weights (uniform)
+  bool q01 = false, q23 = false;  // slots 0,1 / 2,3 hold int4 weights (wave-uniform)
   auto load_B = [&](int j) {
     if constexpr (BQ) {
       // (the scalar offsets are wave-uniform; saying so keeps the loads free of per-lane loops)
       rw[j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rsQ, offBq[j], __builtin_amdgcn_readfirstlane(kBq), 0);
       rsc[j] = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsS, offBs[j], __builtin_amdgcn_readfirstlane(kBs), 0));
-      if (j == 0) setq_next = cq;
     }
   };
-  // pair e2 (values 2 e2, 2 e2 + 1) of slot j; the fourth pair completes the slot and stores it
   uint32_t dq[IPW];
-  auto commit_B = [&](int stage, int j, int e2) {
+  float dq_even = 0.f;
+  uint32_t dq_x = 0;
+  auto commit_B = [&](int stage, int j, int e, bool isq) {  // value e (0..7) of slot j
     if constexpr (BQ) {
-      const uint32_t scp = (uint32_t)rsc[j][e2];
-      const uint32_t x = rw[j] ^ 0x88888888u;  // offset-binary nibble -> two's complement
-      const int q0 = (int)(x << (28 - 8 * e2)) >> 28, q1 = (int)(x << (24 - 8 * e2)) >> 28;
-      typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
       typedef float f32x2_t __attribute__((ext_vector_type(2)));
       typedef T tx2_t __attribute__((ext_vector_type(2)));
-      const f16x2_t sp = __builtin_bit_cast(f16x2_t, scp);
+      const uint32_t scp = (uint32_t)rsc[j][e >> 1];
+      if (e == 0) dq_x = rw[j] ^ 0x88888888u;  // offset-binary nibbles -> two's complement, once per slot
+      const uint32_t x = dq_x;
+      const int qv = (int)(x << (28 - 4 * e)) >> 28;
+      const _Float16 sv = __builtin_bit_cast(_Float16, (unsigned short)((e & 1) ? (scp >> 16) : (scp & 0xFFFFu)));
       // q * scale is exact in fp32 (4 bits x 11 bits); written as a fused multiply-add with +0 so that
       // the fp16 scale feeds the mixed-precision FMA directly; one rounding to T, two values at a time
-      const f32x2_t f = {__builtin_fmaf((float)q0, (float)sp[0], 0.f), __builtin_fmaf((float)q1, (float)sp[1], 0.f)};
-      const uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, tx2_t));
-      dq[e2] = setq ? packed : scp;
-      if (e2 == 3) {
+      const float f = __builtin_fmaf((float)qv, (float)sv, 0.f);
+      if ((e & 1) == 0) {
+        dq_even = f;
+      } else {
+        const f32x2_t f2 = {dq_even, f};
+        const uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, tx2_t));
+        dq[e >> 1] = isq ? packed : scp;
+      }
+      if (e == 7) {
         i32x4 v = {(int)dq[0], (int)dq[1], (int)dq[2], (int)dq[3]};
         *reinterpret_cast<i32x4*>(smem + stage * P::STAGE_BYTES + P::A_BYTES + (wave * IPW + j) * 1024 + lane * 16) = v;
       }
@@ -465,8 +476,6 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 
   // ---- prologue: fill the ring (the last tile only by its A half: the loop issues B halves in K
   // step 0 and A halves in K step 1), wait for the first tile
-  // loads per K tile and wave on the int4 route: 4 LDS-DMA (A) + 4 x (weights dword + scales)
-  constexpr int LPTQ = IPW + 2 * IPW;
   if constexpr (!BQ) {
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) {
@@ -477,24 +486,32 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
     issue_A(NS - 1);
     MC_SYNC((NS - 2) * P::LPT + IPW);
   } else {
-    // B of tile 0 goes to LDS at once; B of tile 1 waits in the registers for K step 0 of tile 0
+    // B of tile 0 goes to LDS at once; then the steady state is set up: slots 0,1 of tile 1 in LDS
+    // and refilled with tile 2, slots 2,3 of tile 1 still in the registers
     issue_A(0);
 #pragma unroll
     for (int j = 0; j < IPW; ++j) load_B(j);
-    setq = setq_next;
+    q01 = q23 = cq;
     cursor_advance();
 #pragma unroll
     for (int j = 0; j < IPW; ++j)
 #pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) commit_B(0, j, e2);
+      for (int e = 0; e < 8; ++e) commit_B(0, j, e, q01);
     issue_A(1);
 #pragma unroll
     for (int j = 0; j < IPW; ++j) load_B(j);
-    setq = setq_next;
+    q01 = q23 = cq;
     cursor_advance();
     issue_A(2);
-    // A of tile 0 is older than everything else issued here
-    MC_SYNC(2 * LPTQ);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) commit_B(1, j, e, q01);
+    load_B(0);
+    load_B(1);
+    q01 = cq;
+    // A of tile 0 is older than everything else issued here (8 + 4 + 8 + 4 + 4 loads)
+    MC_SYNC(28);
   }
   {
     using K0c = std::integral_constant<int, 0>;
@@ -530,22 +547,23 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
       if constexpr (!BQ) {
         kstep(std::integral_constant<int, 1>{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES), [&](int j) { issue_B1(stp, j); }, nothing);
       } else {
-        // int4 route: behind MFMA q, pair q % 4 of slot q / 4 of the next tile's B (fetched during
+        // int4 route: behind MFMA q, value q % 8 of slot 2 + q / 8 of the next tile's B (fetched during
         // the previous tile) is dequantised; a completed slot goes to the next tile's stage and its
         // registers are refilled with the B half of the cursor's tile.
-        kstep(std::integral_constant<int, 1>{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES), [&](int j) { load_B(j); },
-              [&](int q) { commit_B(stn, q >> 2, q & 3); MC_FENCE(); });
-        setq = setq_next;
+        kstep(std::integral_constant<int, 1>{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES),
+              [&](int j) { if (j & 1) load_B(2 + (j >> 1)); },
+              [&](int q) { commit_B(stn, 2 + (q >> 3), q & 7, q23); MC_FENCE(); });
+        q23 = cq;
       }
       cursor_advance();
       // Tile u+1 must have landed (own loads, then everyone's: loads return in order, so "at most
       // (NS-2) tiles' worth outstanding" means tile u+1 is in), and everyone must be done reading
-      // stage st before it is refilled.  (Int4 route: the loads issued after A of tile u+1 are the B
-      // halves of tiles u+1, u+2 and the A half of tile u+2.)
+      // stage st before it is refilled.  (Int4 route: the loads issued after the last A load of tile
+      // u+1 are 2 + 4 + 8 + 4: see K step 1 below.)
       if constexpr (!BQ) {
         MC_SYNC((NS - 2) * P::LPT);
       } else {
-        MC_SYNC(2 * 2 * IPW + IPW);
+        MC_SYNC(18);
       }
       if (kvalid < BK) {
         wait_tr(1);
@@ -554,7 +572,16 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
       }
       // K step 1 out of buffer 1, with the next tile's first fragments and the first half of the
       // refill of stage st
-      kstep(std::integral_constant<int, 0>{}, 1, 0, (uint32_t)(stn * P::STAGE_BYTES), [&](int j) { issue_A1(st, j); }, nothing);
+      if constexpr (!BQ) {
+        kstep(std::integral_constant<int, 0>{}, 1, 0, (uint32_t)(stn * P::STAGE_BYTES), [&](int j) { issue_A1(st, j); }, nothing);
+      } else {
+        // int4 route: slots 0,1 of the tile after the next one (the cursor has moved on) likewise; their
+        // loads follow the A loads at MFMA 7 and 15
+        kstep(std::integral_constant<int, 0>{}, 1, 0, (uint32_t)(stn * P::STAGE_BYTES),
+              [&](int j) { issue_A1(st, j); if (j & 1) load_B(j >> 1); },
+              [&](int q) { commit_B(stp, q >> 3, q & 7, q01); MC_FENCE(); });
+        q01 = cq;
+      }
       stp = st;
       st = stn;
     }
