@@ -31,8 +31,8 @@ TILE_NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256
 # measured for the workload.
 TRAFFIC_BYTES = {
     # profiles/bench_opt13b_hbm_traffic.txt: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per launch
-    ("opt13b", "gemm_kernel<bf16,NN,256x256mc>"): int((116650 * 2.0 + 65920) * 1024),
-    ("opt13b", "gemm_kernel<bf16,NT,256x256mc>"): int((117222 * 2.0 + 66025) * 1024),
+    ("opt13b", "gemm_kernel<bf16,NN,256x256mc>"): int((116706 * 2.0 + 65793) * 1024),
+    ("opt13b", "gemm_kernel<bf16,NT,256x256mc>"): int((117245 * 2.0 + 65626) * 1024),
 }
 
 
