@@ -146,6 +146,7 @@ extern "C" double runlora_model_time_us(int is_bwd, int variant, int64_t n, int6
   if (dt < 0 || n < 1 || i < 1 || o < 1 || r < 1) return -1.0;
   if (variant < 0 || variant > (is_bwd ? 8 : 2)) return -1.0;
   LayerDims L{n, i, o, r, dt};
+  L.w_int4 = dtype == RL_INT4_G64;  // priced with the int4 route's plans; merged graphs then return -1
   return model_time_us(is_bwd, variant, L);
 }
 
@@ -160,6 +161,7 @@ extern "C" int runlora_select_by(int criterion, int64_t n, int64_t i, int64_t o,
   // an int4 W has no dense buffer to merge AB into: forward1 and backward1..3 only
   const int fmax = int4 ? 1 : 2, bmax = int4 ? 3 : 5;
   LayerDims L{n, i, o, r, dt};
+  L.w_int4 = int4;
   int bf = 1, bb = 1;
   double cf = 0, cb = 0;
   for (int v = 1; v <= fmax; ++v) {
