@@ -58,3 +58,12 @@ def test_llama7b_layer(name):
     L = [x for x in synth.config_llama7b(32, "bf16") if x.name == name][0]
     sel = rl.runlora_select(L.n, L.i, L.o, L.r, rl.RL_BF16)
     check_layer(L, sorted({sel, (0, 0)}))
+
+
+@pytest.mark.parametrize("r", [8, 128])
+def test_llama7b_q_other_ranks(r):
+    """The smallest and the largest rank of the Llama-7B configuration: r = 8 is a quarter of a K tile
+    in the concatenated contraction, r = 128 the widest rank-r product of the streaming kernel."""
+    L = [x for x in synth.config_llama7b(r, "bf16") if x.name == "q"][0]
+    sel = rl.runlora_select(L.n, L.i, L.o, L.r, rl.RL_BF16)
+    check_layer(L, sorted({sel, (1, 1), (2, 5)}))
