@@ -43,7 +43,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="opt13b", choices=["opt13b", "llama7b", "qlora"])
     ap.add_argument("--rank", type=int, default=None, help="LoRA rank override (llama7b: 8/32/128)")
-    ap.add_argument("--sets", type=int, default=3, help="rotating input/output sets")
+    ap.add_argument("--sets", type=int, default=4, help="rotating input/output sets (together beyond the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--keep-merged", action="store_true",
                     help="let forward2 keep W + AB for backward4/5 (i*o elements held per layer; pairs chosen for that)")
@@ -132,8 +132,8 @@ def main():
         ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
         state.append(dict(L=L, sets=sets, pair=(fwd, bwd), ws=ws))
 
-    def step(k, default_chain):
-        for st in state:
+    def step(k, default_chain, only=None):
+        for st in (state if only is None else [only]):
             t = st["sets"][k % args.sets]
             fwd, bwd = (0, 0) if default_chain else st["pair"]
             saved = rl.new_saved(t["T"] if fwd == 0 else None, t["M"] if fwd == 2 and bwd in rl.BWD_MERGED else None)
@@ -167,6 +167,27 @@ def main():
 
     f_useful = sum(useful_flops(L) for L in layers)
     value = f_useful / sec_sel / 1e12
+
+    # ---- per layer: forward + backward of the selected pair and of the default chain, median of
+    # `steps` iterations, HIP events on the launch stream around each iteration
+    def layer_ms(st, default_chain):
+        for k in range(args.warmup):
+            step(k, default_chain, st)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for k, (e0, e1) in enumerate(ev):
+            e0.record()
+            step(k, default_chain, st)
+            e1.record()
+        torch.cuda.synchronize()
+        ts = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+        return ts[len(ts) // 2]
+
+    per_layer = []
+    for st in state:
+        L = st["L"]
+        ms_sel, ms_def = layer_ms(st, False), layer_ms(st, True)
+        per_layer.append(dict(name=L.name, pair=list(st["pair"]), ms=round(ms_sel, 4), ms_default_chain=round(ms_def, 4),
+                              speedup=round(ms_def / ms_sel, 4), useful_tflops=round(useful_flops(L) / ms_sel / 1e9, 1)))
 
     # ---- per-kernel timings of an identical pass (HIP events recorded by the library on the
     # launch stream around every step) -> roofline of the dominant kernel
@@ -241,7 +262,7 @@ def main():
         "speedup_over_default_chain": round(sec_def / sec_sel, 4),
         "time_reduction_pct": round(100.0 * (sec_def - sec_sel) / sec_def, 2),
         "useful_gflop_per_step": round(f_useful / 1e9, 2),
-        "roofline": roofline, "kernels": per_kernel, "cpu_baseline": cpu,
+        "per_layer": per_layer, "roofline": roofline, "kernels": per_kernel, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 
