@@ -67,3 +67,32 @@ def test_llama7b_q_other_ranks(r):
     L = [x for x in synth.config_llama7b(r, "bf16") if x.name == "q"][0]
     sel = rl.runlora_select(L.n, L.i, L.o, L.r, rl.RL_BF16)
     check_layer(L, sorted({sel, (1, 1), (2, 5)}))
+
+
+def test_llama7b_gate_with_scale_and_bias():
+    """The 4096 -> 11008 layer (its Y GEMM is cut into a main launch and a split-K tail launch) with a
+    LoRA scale and a frozen bias: the bias must reach both launches and the tail's reduce."""
+    import torch
+    from helpers import to_device
+    L = [x for x in synth.config_llama7b(32, "bf16") if x.name == "gate"][0]
+    dev, host = layer_on_device(L)
+    bst = synth.store(synth.normal(synth.BASE_SEED, 99, (L.o,)), L.dtype)
+    bias_dev, bias64 = to_device(bst, L.dtype), synth.widen(bst, L.dtype)
+    scale = 0.25
+    rows = np.unique(np.concatenate([np.arange(0, L.n, 256), np.arange(255, L.n, 256),
+                                     np.random.default_rng(12).integers(0, L.n, 32)]))
+    Yr, dXr = oracle.scaled_rows(host["X"][rows], host["dY"][rows], host["W"], host["A"], host["B"], scale, bias64)
+    td = torch_dtype(L.dtype)
+    code = rl.dtype_from_name(L.dtype)
+    for fwd, bwd in [(1, 1), (2, 5)]:
+        Y = torch.full((L.n, L.o), float("nan"), dtype=td, device="cuda")
+        gX = torch.full((L.n, L.i), float("nan"), dtype=td, device="cuda")
+        ws = rl.new_workspace(fwd, bwd, L.n, L.i, L.o, L.r, code)
+        saved = rl.new_saved()
+        rl.runlora_forward(fwd, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=ws, scale=scale, bias=bias_dev)
+        rl.runlora_backward(bwd, dev["dY"], saved, dev["W"], dev["A"], dev["B"], gX, None, None, workspace=ws)
+        torch.cuda.synchronize()
+        idx = torch.from_numpy(rows).to("cuda")
+        assert relerr(to_f64(Y[idx]), Yr) < TOL[L.dtype], (fwd, bwd)
+        assert relerr(to_f64(gX[idx]), dXr) < TOL[L.dtype], (fwd, bwd)
+        assert not torch.isnan(Y).any() and not torch.isnan(gX).any()

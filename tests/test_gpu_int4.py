@@ -146,3 +146,31 @@ def test_int4_matrix_core_route_ragged(dtype):
         assert relerr(got["Y"][rows], Yr) < TOL[dtype], (f, b)
         assert relerr(got["dX"][rows], dXr) < TOL[dtype], (f, b)
         assert relerr(got["dA"], dA) < TOL[dtype] and relerr(got["dB"], dB) < TOL[dtype]
+
+
+def test_int4_matrix_core_route_with_scale_and_bias():
+    """The int4 route's epilogue and the dense second segment with a LoRA scale and a bias."""
+    import torch
+    L = synth.Layer("int4mcs", 3001, 2056, 3592, 24, "bf16", 13)
+    dev, host = make_layer(L)
+    bst = synth.store(synth.normal(synth.BASE_SEED, 98, (L.o,)), L.dtype)
+    bias_dev, bias64 = to_device(bst, L.dtype), synth.widen(bst, L.dtype)
+    scale = 0.5
+    rows = np.unique(np.concatenate([np.arange(0, L.n, 256), [L.n - 1], np.random.default_rng(7).integers(0, L.n, 24)]))
+    Yr, dXr = oracle.scaled_rows(host["X"][rows], host["dY"][rows], host["W"], host["A"], host["B"], scale, bias64)
+    code = rl.dtype_from_name(L.dtype)
+    Y = torch.full((L.n, L.o), float("nan"), dtype=torch.bfloat16, device="cuda")
+    gX = torch.full((L.n, L.i), float("nan"), dtype=torch.bfloat16, device="cuda")
+    gA = torch.full((L.i, L.r), float("nan"), dtype=torch.bfloat16, device="cuda")
+    gB = torch.full((L.r, L.o), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = rl.new_workspace(1, 1, L.n, L.i, L.o, L.r, code, w_dtype=rl.RL_INT4_G64)
+    saved = rl.new_saved()
+    rl.runlora_forward(1, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=ws, scale=scale, bias=bias_dev)
+    rl.runlora_backward(1, dev["dY"], saved, dev["W"], dev["A"], dev["B"], gX, gA, gB, workspace=ws)
+    torch.cuda.synchronize()
+    assert relerr(to_f64(Y)[rows], Yr) < TOL["bf16"] and relerr(to_f64(gX)[rows], dXr) < TOL["bf16"]
+    Z1 = scale * oracle.matmul(host["dY"], host["B"], tb=True)
+    assert relerr(to_f64(gA), oracle.matmul(host["X"], Z1, ta=True)) < TOL["bf16"]
+    Tm = scale * oracle.matmul(host["X"], host["A"])
+    assert relerr(to_f64(gB), oracle.matmul(Tm, host["dY"], ta=True)) < TOL["bf16"]
+
