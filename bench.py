@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--keep-merged", action="store_true",
                     help="let forward2 keep W + AB for backward4/5 (i*o elements held per layer; pairs chosen for that)")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="LoRA dropout probability (0 = the paper's setting); pairs are then (1,1), the only RunLoRA graphs that exist with it")
     ap.add_argument("--pair", default=None, help="force one 'fwd,bwd' pair on every layer instead of runlora_select")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a 1 GiB device copy five times (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -121,7 +123,9 @@ def main():
             t["dB"] = torch.empty((L.r, L.o), dtype=tdt, device=dev)
             t["M"] = torch.empty((L.i, L.o), dtype=tdt, device=dev) if args.keep_merged else None
             sets.append(t)
-        if args.pair:
+        if args.dropout > 0.0:
+            fwd, bwd = 1, 1
+        elif args.pair:
             fwd, bwd = (int(v) for v in args.pair.split(","))
         else:
             fwd, bwd = rl.runlora_select(L.n, L.i, L.o, L.r, rl.RL_INT4_G64 if int4 else code,
@@ -137,7 +141,8 @@ def main():
             t = st["sets"][k % args.sets]
             fwd, bwd = (0, 0) if default_chain else st["pair"]
             saved = rl.new_saved(t["T"] if fwd == 0 else None, t["M"] if fwd == 2 and bwd in rl.BWD_MERGED else None)
-            rl.runlora_forward(fwd, t["X"], t["W"], t["A"], t["B"], t["Y"], saved, workspace=st["ws"])
+            rl.runlora_forward(fwd, t["X"], t["W"], t["A"], t["B"], t["Y"], saved, workspace=st["ws"],
+                               dropout_p=args.dropout or None, dropout_seed=k)
             rl.runlora_backward(bwd, t["dY"], saved, t["W"], t["A"], t["B"], t["dX"], t["dA"], t["dB"],
                                 workspace=st["ws"])
 
@@ -257,7 +262,7 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": wl_name, "layers": [dict(name=L.name, n=L.n, d_in=L.i, d_out=L.o, r=L.r) for L in layers],
                    "pairs": {st["L"].name: list(st["pair"]) for st in state}, "input_sets": args.sets,
-                   "keep_merged": bool(args.keep_merged)},
+                   "keep_merged": bool(args.keep_merged), "lora_dropout": args.dropout},
         "ms_per_step_default_chain": round(sec_def * 1e3, 4),
         "speedup_over_default_chain": round(sec_def / sec_sel, 4),
         "time_reduction_pct": round(100.0 * (sec_def - sec_sel) / sec_def, 2),

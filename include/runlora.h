@@ -11,7 +11,9 @@
  * Beyond the paper's layer (which has neither): an optional LoRA scale s and an optional frozen
  * bias b of the base layer, Y = X W + 1 b^T + s (X A) B; the gradients of Eq. 3 then carry the
  * factor s on their adapter terms (dA = s X^T dY B^T, dB = s A^T X^T dY, dX = dY W^T + s dY B^T A^T)
- * and b, being frozen like W, has none.  See rl_opts_t.
+ * and b, being frozen like W, has none.  LoRA dropout on the adapter's input is available too (the
+ * paper's experiments run with dropout 0): Y = X W + 1 b^T + s/(1-p) ((X o m) A) B with a keep-mask m that
+ * forward and backward regenerate from a seed.  See rl_opts_t.
  *
  * Notation (Table 1 caption): n = b*s tokens, i = d_in, o = d_out, r = LoRA rank.
  * All tensors are dense row-major DEVICE buffers described by rl_tensor_t:
@@ -146,6 +148,7 @@ typedef struct {
   void* M;
   int64_t ldm;
   float scale;
+  uint32_t dropout_thr, dropout_seed; /* the forward's dropout (rl_opts_t), 0 = none */
 } rl_saved_t;
 
 /*
@@ -160,6 +163,14 @@ typedef struct {
  *   bias   runlora_forward only: device pointer to the base layer's frozen bias, o elements of
  *          the activation dtype, 16-byte aligned, added in fp32 by the GEMM that writes Y; NULL =
  *          no bias.  Ignored by runlora_backward and runlora_gemm (rl_gemm_t has its own).
+ *   dropout_p, dropout_seed   runlora_forward only: LoRA dropout on the adapter's input, 0 = none.
+ *          p is rounded to thr/256, thr = round(256 p) in [1, 255]; element (t, c) of X is kept iff
+ *          byte (c & 3) of H(t * (i/4) + (c >> 2)) is >= thr, where H(x) = mix(x ^ mix(seed ^ 0x9E3779B9))
+ *          and mix(x): x ^= x >> 16; x *= 0x7feb352d; x ^= x >> 15; x *= 0x846ca68b; x ^= x >> 16 (mod 2^32);
+ *          kept elements are scaled by 256/(256-thr).  The forward records thr and seed in *saved and
+ *          the backward regenerates the mask from them.  With dropout only RL_FWD_DEFAULT / RL_FWD1 and
+ *          RL_BWD_DEFAULT / RL_BWD1 exist (the others merge AB into W or form X^T dY; they return
+ *          RL_ERR_UNSUPPORTED), r must be <= 128 and n*i < 2^34.
  */
 typedef struct {
   void* stream;
@@ -167,6 +178,8 @@ typedef struct {
   size_t workspace_bytes;
   float scale;
   const void* bias;
+  float dropout_p;
+  uint32_t dropout_seed;
 } rl_opts_t;
 
 /*

@@ -183,3 +183,53 @@ def scaled_rows(Xrows, dYrows, W, A, B, scale=1.0, bias=None):
     if bias is not None:
         Y = Y + _f64(bias).reshape(1, -1)
     return Y, dX
+
+
+# ---- LoRA dropout on the adapter's input (not in the paper's experiments, which run with dropout 0) ----
+# The keep-mask is defined by a counter-based generator (stated in include/runlora.h), which both sides
+# implement on their own; everything after the mask is the plain definition
+#     Y  = XW + 1 b^T + s' ((X o m) A) B,      s' = s / (1 - p_q),  p_q = round(256 p) / 256
+#     dA = s' (X o m)^T dY B^T,   dB = s' ((X o m) A)^T dY,   dX = dY W^T + s' m o (dY B^T A^T).
+
+def _mix32(x):
+    x = np.asarray(x, dtype=np.uint32).copy()
+    x ^= x >> np.uint32(16)
+    x *= np.uint32(0x7FEB352D)
+    x ^= x >> np.uint32(15)
+    x *= np.uint32(0x846CA68B)
+    x ^= x >> np.uint32(16)
+    return x
+
+
+def dropout_mask(n, i, p, seed):
+    """(keep-mask [n, i] of 0.0 / 1.0, p_q): element (t, c) is kept iff byte c % 4 of
+    mix(group ^ mix(seed ^ 0x9E3779B9)), group = t * (i / 4) + c // 4, is >= round(256 p)."""
+    assert i % 4 == 0 and n * i < 2 ** 34
+    thr = min(max(int(p * 256.0 + 0.5), 1), 255)
+    with np.errstate(over="ignore"):
+        key = _mix32(np.uint32((int(seed) & 0xFFFFFFFF) ^ 0x9E3779B9))
+        groups = np.arange(n * (i // 4), dtype=np.uint64).astype(np.uint32)
+        h = _mix32(groups ^ key)
+    by = np.stack([(h >> np.uint32(8 * k)) & np.uint32(255) for k in range(4)], axis=1)   # [groups, 4]
+    return (by >= thr).astype(np.float64).reshape(n, i), thr / 256.0
+
+
+def dropout_forward(X, W, A, B, mask, p_q, scale=1.0, bias=None):
+    X, W, A, B, mask = map(_f64, (X, W, A, B, mask))
+    s = float(scale) / (1.0 - p_q)
+    Y = matmul(X, W) + s * matmul(matmul(X * mask, A), B)
+    if bias is not None:
+        Y = Y + _f64(bias).reshape(1, -1)
+    return Y
+
+
+def dropout_backward(X, W, A, B, dY, mask, p_q, scale=1.0):
+    X, W, A, B, dY, mask = map(_f64, (X, W, A, B, dY, mask))
+    s = float(scale) / (1.0 - p_q)
+    Xm = X * mask
+    Z1 = matmul(dY, B, tb=True)
+    dA = s * matmul(Xm, Z1, ta=True)
+    dB = s * matmul(matmul(Xm, A), dY, ta=True)
+    dX = matmul(dY, W, tb=True) + s * mask * matmul(Z1, A, tb=True)
+    return dX, dA, dB
+

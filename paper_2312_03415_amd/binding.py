@@ -48,12 +48,13 @@ class rl_saved_t(ctypes.Structure):
                 ("i", ctypes.c_int64), ("o", ctypes.c_int64), ("r", ctypes.c_int64),
                 ("X", ctypes.c_void_p), ("ldx", ctypes.c_int64), ("T", ctypes.c_void_p),
                 ("ldt", ctypes.c_int64), ("M", ctypes.c_void_p), ("ldm", ctypes.c_int64),
-                ("scale", ctypes.c_float)]
+                ("scale", ctypes.c_float), ("dropout_thr", ctypes.c_uint32), ("dropout_seed", ctypes.c_uint32)]
 
 
 class rl_opts_t(ctypes.Structure):
     _fields_ = [("stream", ctypes.c_void_p), ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-                ("scale", ctypes.c_float), ("bias", ctypes.c_void_p)]
+                ("scale", ctypes.c_float), ("bias", ctypes.c_void_p), ("dropout_p", ctypes.c_float),
+                ("dropout_seed", ctypes.c_uint32)]
 
 
 class rl_gemm_t(ctypes.Structure):
@@ -191,7 +192,7 @@ def tensor_desc(t):
     return rl_tensor_t(t.data_ptr(), t.shape[0], t.shape[1], t.stride(0), dtype_code(t.dtype), None, 0)
 
 
-def _opts(workspace, stream, scale=None, bias=None):
+def _opts(workspace, stream, scale=None, bias=None, dropout_p=None, dropout_seed=0):
     import torch
     if stream is None:
         stream = torch.cuda.current_stream().cuda_stream
@@ -200,22 +201,25 @@ def _opts(workspace, stream, scale=None, bias=None):
     if bias is not None and (bias.dim() != 1 or bias.stride(0) != 1):
         raise ValueError("bias must be a contiguous 1-D tensor")
     return rl_opts_t(stream, ws_ptr, ws_bytes, 0.0 if scale is None else float(scale),
-                     bias.data_ptr() if bias is not None else None)
+                     bias.data_ptr() if bias is not None else None, 0.0 if not dropout_p else float(dropout_p),
+                     int(dropout_seed) & 0xFFFFFFFF)
 
 
 def _ref(desc):
     return ctypes.byref(desc) if desc is not None else None
 
 
-def runlora_forward(variant, X, W, A, B, Y, saved, workspace=None, stream=None, scale=None, bias=None):
+def runlora_forward(variant, X, W, A, B, Y, saved, workspace=None, stream=None, scale=None, bias=None,
+                    dropout_p=None, dropout_seed=0):
     """Y = XW (+ bias) + scale (XA)B in forward graph `variant`; fills `saved` (rl_saved_t).  For
     FWD_DEFAULT set saved.T / saved.ldt to an [n,r] buffer first, for FWD2 optionally saved.M /
     saved.ldm to an [i,o] buffer that keeps W + scale AB for the backward (see new_saved).
-    scale None = 1 (the paper's layer); bias: 1-D tensor [o] of the activation dtype or None."""
+    scale None = 1 (the paper's layer); bias: 1-D tensor [o] of the activation dtype or None;
+    dropout_p / dropout_seed: LoRA dropout on the adapter's input (mask defined in runlora.h), None = off."""
     if bias is not None and (bias.dtype != X.dtype or bias.numel() != Y.shape[1]):
         raise ValueError("bias must have d_out elements of the activation dtype")
     dx, dw, da, db, dy = (tensor_desc(t) for t in (X, W, A, B, Y))
-    o = _opts(workspace, stream, scale, bias)
+    o = _opts(workspace, stream, scale, bias, dropout_p, dropout_seed)
     _check(lib().runlora_forward(variant, _ref(dx), _ref(dw), _ref(da), _ref(db), _ref(dy), ctypes.byref(saved),
                                  ctypes.byref(o)))
     return Y

@@ -166,6 +166,13 @@ int run_schedule(const Schedule& sch, char* ws, hipStream_t stream) {
   return RL_OK;
 }
 
+// key of the dropout mask (see drop_mix in gemm_engine.hpp; the same hash on the host)
+uint32_t drop_key_of(uint32_t seed) {
+  uint32_t x = seed ^ 0x9E3779B9u;
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+
 int check_workspace(const Schedule& sch, const rl_opts_t* opts) {
   if (sch.workspace_bytes == 0) return RL_OK;
   if (!opts || !opts->workspace || opts->workspace_bytes < sch.workspace_bytes) return RL_ERR_WORKSPACE;
@@ -200,6 +207,14 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
 
   const float scale = (opts && opts->scale != 0.f) ? opts->scale : 1.f;
   LayerDims L{n, i, o, r, dt, w_int4, scale};
+  if (opts && opts->dropout_p != 0.f) {
+    if (!(opts->dropout_p > 0.f && opts->dropout_p < 1.f)) return RL_ERR_SHAPE;
+    if (variant == RL_FWD2 || r > 128 || n * i >= (1LL << 34)) return RL_ERR_UNSUPPORTED;
+    int thr = (int)(opts->dropout_p * 256.f + 0.5f);
+    thr = thr < 1 ? 1 : (thr > 255 ? 255 : thr);
+    L.drop_thr = (uint32_t)thr;
+    L.drop_key = drop_key_of(opts->dropout_seed);
+  }
   FwdOperands op;
   op.X = mat(X); op.W = weight_mat(W, o, w_int4); op.A = mat(A); op.B = mat(B); op.Y = mat(Y);
   if (opts && opts->bias) {
@@ -245,6 +260,8 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
   saved->X = X->data;
   saved->ldx = X->ld;
   saved->scale = scale;
+  saved->dropout_thr = L.drop_thr;
+  saved->dropout_seed = L.drop_thr ? opts->dropout_seed : 0u;
   if (variant != RL_FWD_DEFAULT) { saved->T = nullptr; saved->ldt = 0; }
   if (variant != RL_FWD2) { saved->M = nullptr; saved->ldm = 0; }
   return RL_OK;
@@ -309,6 +326,12 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   }
 
   LayerDims L{n, i, o, r, dt, w_int4, saved->scale != 0.f ? saved->scale : 1.f};
+  if (saved->dropout_thr != 0u) {
+    if (saved->dropout_thr > 255u) return RL_ERR_SAVED_MISMATCH;
+    if (variant > RL_BWD1 || r > 128 || n * i >= (1LL << 34)) return RL_ERR_UNSUPPORTED;
+    L.drop_thr = saved->dropout_thr;
+    L.drop_key = drop_key_of(saved->dropout_seed);
+  }
   BwdOperands op;
   if (use_M) { op.M.ptr = saved->M; op.M.ld = saved->ldm; op.have_M = true; }
   op.dY = mat(dY); op.W = weight_mat(W, o, w_int4); op.A = mat(A); op.B = mat(B);

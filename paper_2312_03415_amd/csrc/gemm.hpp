@@ -31,6 +31,9 @@ struct GemmDesc {
   // C = alpha * (sum of the products) + D + bias;  bias: row vector [N] of the dtype, or nullptr
   float alpha = 1.f;
   const void* bias = nullptr;
+  // LoRA dropout (drop_thr != 0): zero output element (m, n) of alpha * (the products) where the mask
+  // drops element (m, n) of X; key and threshold as in gemm_engine.hpp, drop_cpr = columns of X / 4
+  uint32_t drop_thr = 0, drop_key = 0, drop_cpr = 0;
 };
 
 enum TileCfg {
@@ -79,6 +82,7 @@ struct SkinnyDesc {
   int64_t M = 0, N = 0, K = 0;
   int a_strided = 0, b_kcontig = 0, trans_out = 0;
   float alpha = 1.f;  // C = alpha * op(A) op(B)
+  uint32_t drop_thr = 0, drop_key = 0, drop_cpr = 0;  // != 0: A is X, masked by LoRA dropout on load
 };
 struct SkinnyPlan {
   int rt = 1;      // 32-column blocks per row block: N <= 32*rt
@@ -113,8 +117,9 @@ struct GemmArgs;
 hipError_t gemm_launch_bf16(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);
 hipError_t gemm_launch_f16(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);
 hipError_t gemm_launch_f32(int cfg, int al, int bl, const GemmArgs& a, dim3 grid, hipStream_t s);
+struct DropMask { uint32_t thr = 0, key = 0, cpr = 0; };
 hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int M, int N, void* C,
                                 int64_t ldc, const void* D, int64_t ldd, float alpha, const void* bias,
-                                hipStream_t s);
+                                DropMask drop, hipStream_t s);
 
 }  // namespace rl

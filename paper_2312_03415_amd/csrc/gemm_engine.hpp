@@ -53,6 +53,9 @@ struct GemmArgs {
   // vector [N] in T added to every row (nullptr = none)
   float alpha;
   const void* bias;
+  // drop_thr != 0: output element (m, n) of alpha * (the products) is zeroed where the dropout mask
+  // drops element (m, n) of X (the adapter's share of dX); drop_cpr = groups of four columns per row
+  uint32_t drop_thr, drop_key, drop_cpr;
 };
 
 // ---- per-type pieces --------------------------------------------------------------------------
@@ -85,6 +88,39 @@ template <> __device__ __forceinline__ float from_f32<float>(float v) { return v
 template <> __device__ __forceinline__ __bf16 from_f32<__bf16>(float v) { return (__bf16)v; }
 template <> __device__ __forceinline__ _Float16 from_f32<_Float16>(float v) { return (_Float16)v; }
 
+// ---- LoRA dropout mask (an option beyond the paper's layer, whose experiments run with dropout 0) ----
+// Element (t, c) of X [n, i] is kept iff byte (c & 3) of H(t * (i / 4) + (c >> 2)) is >= thr, where
+// H(x) = mix(x ^ key), mix = the 32-bit hash below, key = mix(seed ^ 0x9E3779B9) (computed on the host)
+// and thr = round(256 p): a counter-based generator, so that forward and backward, and the CPU oracle,
+// see the same mask without storing it.  One hash serves four consecutive columns.
+__device__ __forceinline__ uint32_t drop_mix(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+// keep-masks of the four columns of group g: 0xFFFFFFFF / 0 per column
+__device__ __forceinline__ void drop_keep4(uint32_t g, uint32_t key, uint32_t thr, uint32_t (&keep)[4]) {
+  const uint32_t h = drop_mix(g ^ key);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) keep[k] = ((h >> (8 * k)) & 255u) >= thr ? 0xFFFFFFFFu : 0u;
+}
+// a 16-byte chunk of X whose first column belongs to group g (8 columns = groups g, g+1 for 16-bit
+// types; 4 columns = group g for fp32) with the dropped elements zeroed
+template <typename T>
+__device__ __forceinline__ i32x4 drop_chunk(i32x4 v, uint32_t g, uint32_t key, uint32_t thr) {
+  uint32_t k0[4];
+  drop_keep4(g, key, thr, k0);
+  if constexpr (sizeof(T) == 4) {
+    return i32x4{(int)((uint32_t)v[0] & k0[0]), (int)((uint32_t)v[1] & k0[1]), (int)((uint32_t)v[2] & k0[2]), (int)((uint32_t)v[3] & k0[3])};
+  } else {
+    uint32_t k1[4];
+    drop_keep4(g + 1, key, thr, k1);
+    return i32x4{(int)((uint32_t)v[0] & ((k0[0] & 0xFFFFu) | (k0[1] & 0xFFFF0000u))),
+                 (int)((uint32_t)v[1] & ((k0[2] & 0xFFFFu) | (k0[3] & 0xFFFF0000u))),
+                 (int)((uint32_t)v[2] & ((k1[0] & 0xFFFFu) | (k1[1] & 0xFFFF0000u))),
+                 (int)((uint32_t)v[3] & ((k1[2] & 0xFFFFu) | (k1[3] & 0xFFFF0000u)))};
+  }
+}
+
 // ---- epilogue of one 32x32 accumulator block ------------------------------------------------------
 // With the MFMA operands swapped, lane l holds row m = l%32 and, for q = 0..3, the four consecutive
 // columns 8q + 4(l/32) + {0..3}.  For 16-bit outputs the two half-waves exchange their halves of
@@ -100,7 +136,19 @@ struct Epilogue {
   int M, N, split;
   float alpha;       // scales the accumulated products (not D, not bias); partials stay unscaled
   const void* bias;  // [N] in T, or nullptr
+  uint32_t drop_thr, drop_key, drop_cpr;  // see GemmArgs
 };
+// alpha * acc of four consecutive columns n .. n+3 (n a multiple of 4) of row m, dropout mask applied
+__device__ __forceinline__ f32x4 epilogue_scale(const Epilogue& ep, f32x4 v, int m, int n) {
+  if (ep.alpha != 1.f) v *= ep.alpha;
+  if (ep.drop_thr != 0u) {
+    uint32_t keep[4];
+    drop_keep4((uint32_t)m * ep.drop_cpr + (uint32_t)(n >> 2), ep.drop_key, ep.drop_thr, keep);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = keep[k] ? v[k] : 0.f;
+  }
+  return v;
+}
 
 template <typename T>
 __device__ __forceinline__ void store_block(const Epilogue& ep, const f32x16& acc, int m, int nbase, int lane) {
@@ -122,7 +170,7 @@ __device__ __forceinline__ void store_block(const Epilogue& ep, const f32x16& ac
       const int n = nbase + 8 * q + 4 * h;
       if (n >= ep.N) continue;
       f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-      if (ep.alpha != 1.f) v *= ep.alpha;
+      v = epilogue_scale(ep, v, m, n);
       if (ep.D) v += *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.D) + (int64_t)m * ep.ldd + n);
       if (ep.bias) v += *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.bias) + n);
       *reinterpret_cast<f32x4*>(static_cast<float*>(ep.C) + (int64_t)m * ep.ldc + n) = v;
@@ -135,7 +183,7 @@ __device__ __forceinline__ void store_block(const Epilogue& ep, const f32x16& ac
       for (int w = 0; w < 2; ++w) {
         const int q = 2 * qp + w;
         f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-        if (ep.alpha != 1.f) v *= ep.alpha;
+        v = epilogue_scale(ep, v, m, nbase + 8 * q + 4 * h);
         if (ep.D || ep.bias) {
           const int n = nbase + 8 * q + 4 * h;
           if (n < ep.N) {
@@ -393,7 +441,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
   }
 
   // ---- epilogue
-  Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, (int)blockIdx.y, g.alpha, g.bias};
+  Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, (int)blockIdx.y, g.alpha, g.bias, g.drop_thr, g.drop_key, g.drop_cpr};
 #pragma unroll
   for (int a = 0; a < G::TM; ++a)
 #pragma unroll
@@ -406,7 +454,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits,
                                                             int M, int N, T* __restrict__ C, int64_t ldc,
                                                             const T* __restrict__ D, int64_t ldd, float alpha,
-                                                            const T* __restrict__ bias) {
+                                                            const T* __restrict__ bias, uint32_t drop_thr,
+                                                            uint32_t drop_key, uint32_t drop_cpr) {
   const int64_t quads = (int64_t)M * N / 4;  // N is a multiple of 4
   for (int64_t qd = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; qd < quads;
        qd += (int64_t)gridDim.x * blockDim.x) {
@@ -418,6 +467,12 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
       s += p;
     }
     if (alpha != 1.f) s *= alpha;
+    if (drop_thr != 0u) {
+      uint32_t keep[4];
+      drop_keep4((uint32_t)m * drop_cpr + (uint32_t)(n >> 2), drop_key, drop_thr, keep);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) s[k] = keep[k] ? s[k] : 0.f;
+    }
     if (D) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) s[k] += (float)D[(int64_t)m * ldd + n + k];

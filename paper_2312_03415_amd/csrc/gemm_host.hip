@@ -106,6 +106,7 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   if (plan.tail_n0 > 0) {
     // columns [0, tail_n0) with this plan, columns [tail_n0, N) as their own problem
     if (plan.tail_n0 >= d.N) return hipErrorInvalidValue;
+    if (d.drop_thr != 0) return hipErrorInvalidValue;  // the mask is indexed by the full product's columns (K = r: never cut)
     const size_t esz = d.dtype == DT_F32 ? 4 : 2;
     GemmDesc dm = d, dt = d;
     GemmPlan pm = plan;
@@ -173,6 +174,9 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   a.ldbs = d.ldbs;
   a.alpha = d.alpha;
   a.bias = plan.splits > 1 ? nullptr : d.bias;
+  a.drop_thr = d.drop_thr;
+  a.drop_key = d.drop_key;
+  a.drop_cpr = d.drop_cpr;
   dim3 grid((unsigned)(plan.nbm * plan.nbn), (unsigned)plan.splits, 1);
   const int al = d.a_strided ? 1 : 0, bl = d.b_kcontig ? 1 : 0;
   hipError_t e;
@@ -185,13 +189,13 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   if (e != hipSuccess) return e;
   if (plan.splits > 1)
     e = splitk_reduce_launch(d.dtype, scratch, plan.splits, (int)d.M, (int)d.N, d.C, d.ldc, d.D, d.ldd, d.alpha,
-                             d.bias, stream);
+                             d.bias, DropMask{d.drop_thr, d.drop_key, d.drop_cpr}, stream);
   return e;
 }
 
 hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int M, int N, void* C,
                                 int64_t ldc, const void* D, int64_t ldd, float alpha, const void* bias,
-                                hipStream_t s) {
+                                DropMask drop, hipStream_t s) {
   const int64_t quads = (int64_t)M * N / 4;
   int blocks = (int)((quads + 255) / 256);
   if (blocks > 4096) blocks = 4096;
@@ -200,17 +204,17 @@ hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int
     case DT_BF16:
       hipLaunchKernelGGL(splitk_reduce_kernel<__bf16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
                          static_cast<__bf16*>(C), ldc, static_cast<const __bf16*>(D), ldd, alpha,
-                         static_cast<const __bf16*>(bias));
+                         static_cast<const __bf16*>(bias), drop.thr, drop.key, drop.cpr);
       break;
     case DT_F16:
       hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
                          static_cast<_Float16*>(C), ldc, static_cast<const _Float16*>(D), ldd, alpha,
-                         static_cast<const _Float16*>(bias));
+                         static_cast<const _Float16*>(bias), drop.thr, drop.key, drop.cpr);
       break;
     case DT_F32:
       hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
                          static_cast<float*>(C), ldc, static_cast<const float*>(D), ldd, alpha,
-                         static_cast<const float*>(bias));
+                         static_cast<const float*>(bias), drop.thr, drop.key, drop.cpr);
       break;
     default: return hipErrorInvalidValue;
   }
@@ -264,6 +268,7 @@ hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPla
     P.M = (int)d[w].M; P.N = (int)d[w].N; P.K = (int)d[w].K;
     P.a_strided = d[w].a_strided; P.b_kcontig = d[w].b_kcontig; P.trans_out = d[w].trans_out;
     P.alpha = d[w].alpha;
+    P.drop_thr = d[w].drop_thr; P.drop_key = d[w].drop_key; P.drop_cpr = d[w].drop_cpr;
     P.row_blocks = (int)((d[w].M + 31) / 32);
     {
       const int64_t esz = dtype == DT_F32 ? 4 : 2;

@@ -587,7 +587,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
     }
 
     // ---- epilogue (the next work item's first tiles keep arriving meanwhile)
-    Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split, g.alpha, g.bias};
+    Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split, g.alpha, g.bias, g.drop_thr, g.drop_key, g.drop_cpr};
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll

@@ -12,8 +12,13 @@ struct Builder {
   size_t used = 0;
   size_t max_partial = 0;
   Schedule* out;
+  bool failed = false;  // a step this build cannot run (masking X inside the tile GEMM)
 
   Builder(const LayerDims& l, void* ws, Schedule* o) : L(l), base(static_cast<char*>(ws)), out(o) {}
+
+  // the LoRA scale as the kernels apply it: under dropout the kept inputs are scaled by 1 / (1 - p)
+  float scale() const { return L.drop_thr ? L.scale * 256.f / (256.f - (float)L.drop_thr) : L.scale; }
+  uint32_t drop_cpr() const { return (uint32_t)(L.i / 4); }
 
   // dense [rows, cols] scratch matrix in the layer dtype
   Mat scratch(int64_t rows, int64_t cols) {
@@ -29,13 +34,14 @@ struct Builder {
   // b_is_w: B is the layer's frozen W (int4 when L.w_int4)
   void gemm(const char* what, int a_strided, int b_kcontig, int64_t M, int64_t N, int64_t K, Mat A, Mat B,
             Mat C, const Mat* D = nullptr, int64_t K2 = 0, const Mat* A2 = nullptr, const Mat* B2 = nullptr,
-            bool b_is_w = false, float alpha = 1.f, const void* bias = nullptr) {
+            bool b_is_w = false, float alpha = 1.f, const void* bias = nullptr, bool mask_out = false) {
     Step s;
     s.what = what;
     GemmDesc& d = s.d;
     d.dtype = L.dtype;
     d.alpha = alpha;
     d.bias = bias;
+    if (mask_out && L.drop_thr) { d.drop_thr = L.drop_thr; d.drop_key = L.drop_key; d.drop_cpr = drop_cpr(); }
     d.a_strided = a_strided;
     d.b_kcontig = b_kcontig;
     d.M = M;
@@ -62,7 +68,7 @@ struct Builder {
   // GEMM with W as the addend
   void merge(const char* what, Mat A, Mat B, Mat W, Mat M) {
     if (!merge_ok(L.dtype, L.r)) {
-      gemm(what, 0, 0, L.i, L.o, L.r, A, B, M, &W, 0, nullptr, nullptr, false, L.scale);
+      gemm(what, 0, 0, L.i, L.o, L.r, A, B, M, &W, 0, nullptr, nullptr, false, scale());
       return;
     }
     Step s;
@@ -72,7 +78,7 @@ struct Builder {
     s.mg.W = W.ptr; s.mg.A = A.ptr; s.mg.B = B.ptr; s.mg.M = const_cast<void*>(M.ptr);
     s.mg.ldw = W.ld; s.mg.lda = A.ld; s.mg.ldb = B.ld; s.mg.ldm = M.ld;
     s.mg.I = L.i; s.mg.O = L.o; s.mg.R = L.r;
-    s.mg.alpha = L.scale;
+    s.mg.alpha = scale();
     out->steps.push_back(s);
   }
 
@@ -83,10 +89,12 @@ struct Builder {
     int64_t M, N, K;
     Mat A, B, C;
     bool scaled = false;  // this product carries the layer's LoRA scale
+    bool mask_x = false;  // A is the layer input X: masked under LoRA dropout
   };
   SkinnyDesc to_skinny(const Sk& g) const {
     SkinnyDesc d;
-    d.alpha = g.scaled ? L.scale : 1.f;
+    d.alpha = g.scaled ? scale() : 1.f;
+    if (g.mask_x && L.drop_thr) { d.drop_thr = L.drop_thr; d.drop_key = L.drop_key; d.drop_cpr = drop_cpr(); }
     if (g.N <= g.M || g.a_strided == 0) {
       d.A = g.A.ptr; d.lda = g.A.ld; d.B = g.B.ptr; d.ldb = g.B.ld; d.C = const_cast<void*>(g.C.ptr); d.ldc = g.C.ld;
       d.M = g.M; d.N = g.N; d.K = g.K; d.a_strided = g.a_strided; d.b_kcontig = g.b_kcontig; d.trans_out = 0;
@@ -112,8 +120,9 @@ struct Builder {
   }
   void skinny(const char* what, const Sk& g) {
     if (!sk_ok(g)) {
+      if (g.mask_x && L.drop_thr) { failed = true; return; }  // only the streaming kernel masks its A operand
       gemm(what, g.a_strided, g.b_kcontig, g.M, g.N, g.K, g.A, g.B, g.C, nullptr, 0, nullptr, nullptr, false,
-           g.scaled ? L.scale : 1.f);
+           g.scaled ? scale() : 1.f);
       return;
     }
     Step s;
@@ -163,11 +172,11 @@ struct Builder {
 // (Algorithms 1 and 5 share these four statements).
 void rank_r_pass(Builder& b, const BwdOperands& op, int64_t n, int64_t i, int64_t o, int64_t r, Mat Z1, Mat Z2,
                  bool need_Z1, bool need_Z2, bool dA, bool dB) {
-  const Builder::Sk z1{0, 1, n, r, o, op.dY, op.B, Z1, true}, z2{0, 0, n, r, i, op.X, op.A, Z2, true};
+  const Builder::Sk z1{0, 1, n, r, o, op.dY, op.B, Z1, true}, z2{0, 0, n, r, i, op.X, op.A, Z2, true, true};
   if (need_Z1 && need_Z2) b.skinny2("Z1 = dY B^T ; Z2 = X A", "Z1 = dY B^T", z1, "Z2 = X A", z2);
   else if (need_Z1) b.skinny("Z1 = dY B^T", z1);
   else if (need_Z2) b.skinny("Z2 = X A", z2);
-  const Builder::Sk ga{1, 0, i, r, n, op.X, Z1, op.dA}, gb{1, 0, r, o, n, Z2, op.dY, op.dB};
+  const Builder::Sk ga{1, 0, i, r, n, op.X, Z1, op.dA, false, true}, gb{1, 0, r, o, n, Z2, op.dY, op.dB};
   if (dA && dB) b.skinny2("dA = X^T Z1 ; dB = Z2^T dY", "dA = X^T Z1", ga, "dB = Z2^T dY", gb);
   else if (dA) b.skinny("dA = X^T Z1", ga);
   else if (dB) b.skinny("dB = Z2^T dY", gb);
@@ -189,19 +198,19 @@ bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void*
   const int64_t n = L.n, i = L.i, o = L.o, r = L.r;
   switch (variant) {
     case 0: {  // default chain: T kept, one kernel per product
-      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, op.T, true});
+      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, op.T, true, true});
       b.gemm("Y = X W", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, 0, nullptr, nullptr, true, 1.f, op.bias);
       b.gemm("Y += T B", 0, 0, n, o, r, op.T, op.B, op.Y, &op.Y);
       break;
     }
     case 1: {  // forward1: (XW) + ((XA)B), the sum folded into one contraction over [X|T]
       Mat T = b.scratch(n, r);
-      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T, true});
+      b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T, true, true});
       b.gemm("Y = [X|T] [W;B]", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, r, &T, &op.B, true, 1.f, op.bias);
       break;
     }
     case 2: {  // forward2: X (W + AB)
-      if (L.w_int4) return false;  // no dense buffer to merge AB into
+      if (L.w_int4 || L.drop_thr) return false;  // no dense buffer to merge AB into / no merged weight under dropout
       Mat M = op.keep_M ? op.M : b.scratch(i, o);
       b.merge("M = W + A B", op.A, op.B, op.W, M);
       b.gemm("Y = X M", 0, 0, n, o, i, op.X, M, op.Y, nullptr, 0, nullptr, nullptr, false, 1.f, op.bias);
@@ -211,7 +220,7 @@ bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void*
       return false;
   }
   b.finish();
-  return true;
+  return !b.failed;
 }
 
 bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void* ws_base, Schedule* out) {
@@ -219,23 +228,29 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
   Builder b(L, ws_base, out);
   const int64_t n = L.n, i = L.i, o = L.o, r = L.r;
   const bool dX = op.want_dX, dA = op.want_dA, dB = op.want_dB;
+  if (L.drop_thr && variant > 1) return false;  // see LayerDims::drop_thr
   switch (variant) {
     case 0: {  // backward of the default chain (uses the kept T = XA)
       Mat Z1 = b.scratch(n, r);
       // one kernel per product, as autograd would run them
       if (dA || dX) b.skinny("Z1 = dY B^T", {0, 1, n, r, o, op.dY, op.B, Z1, true});
       if (dB) b.skinny("dB = T^T dY", {1, 0, r, o, n, op.T, op.dY, op.dB});
-      if (dA) b.skinny("dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA});
+      if (dA) b.skinny("dA = X^T Z1", {1, 0, i, r, n, op.X, Z1, op.dA, false, true});
       if (dX) {
         b.gemm("dX = dY W^T", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, 0, nullptr, nullptr, true);
-        b.gemm("dX += Z1 A^T", 0, 1, n, i, r, Z1, op.A, op.dX, &op.dX);
+        b.gemm("dX += Z1 A^T", 0, 1, n, i, r, Z1, op.A, op.dX, &op.dX, 0, nullptr, nullptr, false, 1.f, nullptr, true);
       }
       break;
     }
     case 1: {  // Algorithm 1
       Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r);
       rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA || dX, dB, dA, dB);
-      if (dX) b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A, true);
+      if (dX && L.drop_thr) {  // the mask sits between the two products: no concatenated contraction
+        b.gemm("dX = dY W^T", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, 0, nullptr, nullptr, true);
+        b.gemm("dX += Z1 A^T", 0, 1, n, i, r, Z1, op.A, op.dX, &op.dX, 0, nullptr, nullptr, false, 1.f, nullptr, true);
+      } else if (dX) {
+        b.gemm("dX = [dY|Z1] [W^T;A^T]", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, r, &Z1, &op.A, true);
+      }
       break;
     }
     case 2: {  // Algorithm 2
@@ -318,7 +333,7 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
       return false;
   }
   b.finish();
-  return true;
+  return !b.failed;
 }
 
 }  // namespace rl

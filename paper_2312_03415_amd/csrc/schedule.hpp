@@ -26,6 +26,11 @@ struct LayerDims {
   // formed (T = s XA, Z1 = s dY B^T, M = W + s AB, dA = s Z2 B^T, dB = s A^T Z2), so that every later
   // product of the graph is the paper's, unchanged.
   float scale = 1.f;
+  // LoRA dropout on the adapter's input (drop_thr = round(256 p), 0 = none): Y = XW + s' ((X o m) A) B with
+  // the keep-mask m of gemm_engine.hpp and s' = scale / (1 - drop_thr / 256) in place of scale.  Only the
+  // graphs that never merge AB into W and never form X^T dY exist with it: forward 0/1, backward 0/1, the
+  // latter with dX = dY W^T followed by dX += m o (Z1 A^T) instead of the concatenated contraction.
+  uint32_t drop_thr = 0, drop_key = 0;
 };
 
 struct Step {

@@ -34,6 +34,9 @@ struct SkinnyProblem {
   int a_bytes, b_bytes; // extent of A and B in bytes (< 2 GiB): the range the loads are checked against
   int tiles_per_split;  // K tiles of this problem per gridDim.y slice
   float alpha;          // C = alpha * op(A) op(B) (the LoRA scale, applied where a rank-r factor is formed)
+  // drop_thr != 0: A is the layer input X and its dropped elements (drop_chunk, gemm_engine.hpp) are
+  // zeroed on their way to LDS; drop_cpr = groups of four columns per row of X
+  uint32_t drop_thr, drop_key, drop_cpr;
 };
 
 struct SkinnyArgs {
@@ -60,7 +63,8 @@ struct SkinnyTile {
 
 // One problem's work for this workgroup.  AL / BL are the operand layouts (compile time, so that
 // the load and fragment paths are straight-line code): AL = 1: A stored [K,M]; BL = 1: B stored [N,K].
-template <typename T, int RT, int NWV, int AL, int BL>
+// DROP: the build of the kernel that can mask A (LoRA dropout); the plain build carries none of it.
+template <typename T, int RT, int NWV, int AL, int BL, bool DROP>
 __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsigned char* smem_raw) {
   using S = SkinnyTile<T, RT, NWV>;
   constexpr int VE = S::VE, BK = S::BK;
@@ -107,11 +111,13 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
   // spreads the requests over the memory channels instead of all hitting the same column offset.
   const int span = t_end - t_begin;
   const int rot = span > 0 ? (bx * 5) % span : 0;
+  int kst[DEPTH];  // k origin of the tile in each register stage (for the dropout mask)
   auto load_global = [&](int d, int q) {  // q = position in this workgroup's tile sequence
     const bool live = q < span;
     int tq = q + rot;
     if (tq >= span) tq -= span;
     const int k0 = (t_begin + tq) * BK;
+    if constexpr (DROP) kst[d] = k0;
 #pragma unroll
     for (int j = 0; j < A_PER; ++j) {
       const int c = lane + 64 * j;
@@ -149,6 +155,22 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
   };
 
   auto store_lds = [&](int d) {
+    if (DROP && P.drop_thr != 0u) {  // wave-uniform: A is X under LoRA dropout
+#pragma unroll
+      for (int j = 0; j < A_PER; ++j) {
+        const int c = lane + 64 * j;
+        uint32_t t, col;  // token (row of X) and first column of X of this chunk
+        if constexpr (!a_str) {
+          t = (uint32_t)(m0 + (c >> 3));
+          col = (uint32_t)(kst[d] + (c & 7) * VE);
+        } else {
+          constexpr int CPR = 32 / VE;
+          t = (uint32_t)(kst[d] + c / CPR);
+          col = (uint32_t)(m0 + (c % CPR) * VE);
+        }
+        ra[d][j] = drop_chunk<T>(ra[d][j], t * P.drop_cpr + (col >> 2), P.drop_key, P.drop_thr);
+      }
+    }
 #pragma unroll
     for (int j = 0; j < A_PER; ++j) {
       const int c = lane + 64 * j;
@@ -237,7 +259,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
 }
 
 // AL is common to both problems of a paired launch; BL0 / BL1 are their B layouts.
-template <typename T, int RT, int NWV, int AL, int BL0, int BL1>
+template <typename T, int RT, int NWV, int AL, int BL0, int BL1, bool DROP = false>
 __global__ __launch_bounds__(NWV * 64) void skinny_kernel(SkinnyArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   // Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2 and its own
@@ -252,11 +274,11 @@ __global__ __launch_bounds__(NWV * 64) void skinny_kernel(SkinnyArgs g) {
   const int R0 = g.p[0].row_blocks, R1 = g.nprob > 1 ? g.p[1].row_blocks : 0;
   const int n0 = R0 / 8 + (x < (R0 & 7) ? 1 : 0), s0 = x * (R0 / 8) + (x < (R0 & 7) ? x : (R0 & 7));
   if (slot < n0) {
-    skinny_body<T, RT, NWV, AL, BL0>(g.p[0], s0 + slot, smem_raw);
+    skinny_body<T, RT, NWV, AL, BL0, DROP>(g.p[0], s0 + slot, smem_raw);
     return;
   }
   const int n1 = R1 / 8 + (x < (R1 & 7) ? 1 : 0), s1 = x * (R1 / 8) + (x < (R1 & 7) ? x : (R1 & 7));
-  if (slot - n0 < n1) skinny_body<T, RT, NWV, AL, BL1>(g.p[1], s1 + (slot - n0), smem_raw);
+  if (slot - n0 < n1) skinny_body<T, RT, NWV, AL, BL1, DROP>(g.p[1], s1 + (slot - n0), smem_raw);
 }
 
 // Second stage for a K split over workgroups: C = sum over slices (in slice order) of the fp32

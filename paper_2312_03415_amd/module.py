@@ -34,11 +34,13 @@ class RunLoRAFunction(torch.autograd.Function):
     """y = x W + bias + scale (x A) B with W and bias frozen; gradients for x, A and B (Eq. 1, Eq. 3).
 
     pair = (forward variant, backward variant) as runlora_select returns them; keep_merged lets
-    forward2 hold W + scale AB for a merged backward (i*o elements kept until the backward ran).
+    forward2 hold W + scale AB for a merged backward (i*o elements kept until the backward ran);
+    dropout = (p, seed) or None: LoRA dropout on the adapter's input (mask defined in runlora.h; the
+    backward regenerates it from the seed the forward recorded).
     """
 
     @staticmethod
-    def forward(ctx, x, W, A, B, bias, scale, pair, keep_merged):
+    def forward(ctx, x, W, A, B, bias, scale, pair, keep_merged, dropout=None):
         fwd, bwd = pair
         i, o = W.shape
         r = A.shape[1]
@@ -54,7 +56,8 @@ class RunLoRAFunction(torch.autograd.Function):
             M = torch.empty((i, o), dtype=x.dtype, device=x.device)
         saved = rl.new_saved(T, M)
         ws = _workspace(x.device, rl.runlora_workspace_bytes(fwd, bwd, n, i, o, r, code))
-        rl.runlora_forward(fwd, x2, W, A, B, y, saved, workspace=ws, scale=scale, bias=bias)
+        p, seed = dropout if dropout else (None, 0)
+        rl.runlora_forward(fwd, x2, W, A, B, y, saved, workspace=ws, scale=scale, bias=bias, dropout_p=p, dropout_seed=seed)
         ctx.saved = saved
         ctx.bwd = bwd
         ctx.keep = (T, M)          # buffers *saved points into
@@ -80,7 +83,7 @@ class RunLoRAFunction(torch.autograd.Function):
         rl.runlora_backward(ctx.bwd, dy2, ctx.saved, W, A, B, dx, dA, dB, workspace=ws)
         if dx is not None:
             dx = dx.view(ctx.x_shape)
-        return dx, None, dA, dB, None, None, None, None
+        return dx, None, dA, dB, None, None, None, None, None
 
 
 class RunLoRALinear(nn.Module):
@@ -91,7 +94,7 @@ class RunLoRALinear(nn.Module):
     count is seen (criterion 2 when keep_merged), or fixed with pair=(f, b).
     """
 
-    def __init__(self, weight, r, alpha=None, bias=None, pair=None, keep_merged=False):
+    def __init__(self, weight, r, alpha=None, bias=None, pair=None, keep_merged=False, dropout=0.0):
         super().__init__()
         d_in, d_out = weight.shape
         self.d_in, self.d_out, self.r = d_in, d_out, r
@@ -103,14 +106,16 @@ class RunLoRALinear(nn.Module):
         self.lora_B = nn.Parameter(torch.zeros(r, d_out, dtype=weight.dtype, device=weight.device))
         self.pair = pair
         self.keep_merged = keep_merged
+        self.dropout = float(dropout)  # LoRA dropout probability, applied in training mode only
+        self.last_dropout_seed = None  # seed of the most recent training-mode forward (for reproducing its mask)
         self._pairs = {}
 
     @classmethod
-    def from_linear(cls, linear, r, alpha=None, pair=None, keep_merged=False):
+    def from_linear(cls, linear, r, alpha=None, pair=None, keep_merged=False, dropout=0.0):
         """nn.Linear keeps its weight as [d_out, d_in]; the layer holds the transposed copy."""
         w = linear.weight.detach().t().contiguous()
         b = linear.bias.detach() if linear.bias is not None else None
-        return cls(w, r, alpha, b, pair, keep_merged)
+        return cls(w, r, alpha, b, pair, keep_merged, dropout)
 
     def pair_for(self, n_tokens):
         if self.pair is not None:
@@ -124,6 +129,13 @@ class RunLoRALinear(nn.Module):
 
     def forward(self, x):
         n = x.numel() // self.d_in
+        if self.training and self.dropout > 0.0:
+            # with dropout only forward1 / backward1 (or the default chain) exist; a fresh seed per call
+            # from torch's CPU generator, so that torch.manual_seed makes runs repeatable
+            self.last_dropout_seed = int(torch.randint(0, 2 ** 31 - 1, (1,)).item())
+            pair = self.pair if self.pair in ((0, 0), (0, 1), (1, 1)) else (1, 1)
+            return RunLoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.bias, self.scale, pair, False,
+                                         (self.dropout, self.last_dropout_seed))
         return RunLoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.bias, self.scale,
                                      self.pair_for(n), self.keep_merged)
 
@@ -131,14 +143,14 @@ class RunLoRALinear(nn.Module):
         return f"d_in={self.d_in}, d_out={self.d_out}, r={self.r}, scale={self.scale:g}, bias={self.bias is not None}"
 
 
-def wrap_linears(model, r, alpha=None, targets=None, pair=None, keep_merged=False):
+def wrap_linears(model, r, alpha=None, targets=None, pair=None, keep_merged=False, dropout=0.0):
     """Replace nn.Linear submodules of `model` by RunLoRALinear (all of them, or those whose attribute
     name is in `targets`); every other parameter of the model is frozen.  Returns the replaced names."""
     replaced = []
     for name, module in list(model.named_modules()):
         for child_name, child in list(module.named_children()):
             if isinstance(child, nn.Linear) and (targets is None or child_name in targets):
-                setattr(module, child_name, RunLoRALinear.from_linear(child, r, alpha, pair, keep_merged))
+                setattr(module, child_name, RunLoRALinear.from_linear(child, r, alpha, pair, keep_merged, dropout))
                 replaced.append(f"{name}.{child_name}" if name else child_name)
     for pname, p in model.named_parameters():
         if not (pname.endswith("lora_A") or pname.endswith("lora_B")):

@@ -167,6 +167,9 @@ def test_forward_rejects_bad_arguments_before_touching_the_gpu():
     assert call_fwd(1, b) == rl.RL_ERR_ALIGN          # r must be a multiple of 8 for 16-bit types
     b = fwd_args(); b["Y"].data = b["X"].data
     assert call_fwd(1, b) == rl.RL_ERR_ALIAS
+    # LoRA dropout: probability in (0, 1); no merged forward, r <= 128
+    assert call_fwd(1, a, opts=rl.rl_opts_t(None, 0x70000000, 1 << 30, 0.0, None, 1.5, 1)) == rl.RL_ERR_SHAPE
+    assert call_fwd(2, a, opts=rl.rl_opts_t(None, 0x70000000, 1 << 30, 0.0, None, 0.1, 1)) == rl.RL_ERR_UNSUPPORTED
     # needs workspace, none given / too small / misaligned
     assert call_fwd(1, a) == rl.RL_ERR_WORKSPACE
     assert call_fwd(1, a, opts=rl.rl_opts_t(None, 0x70000000, 16)) == rl.RL_ERR_WORKSPACE

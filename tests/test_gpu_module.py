@@ -133,3 +133,39 @@ def test_wrap_linears_replaces_and_freezes():
     got.square().mean().backward()
     assert model.q_proj.lora_B.grad is not None and model.q_proj.lora_B.grad.abs().sum().item() > 0
     assert model.q_proj._pairs and list(model.q_proj._pairs) == [200]
+
+
+def test_layer_dropout_in_training_mode():
+    """Training mode with dropout: outputs and gradients match the oracle under the mask of the seed the
+    layer drew; eval mode runs without dropout."""
+    import torch
+    b, s, d_in, d_out, r, alpha, p = 2, 60, 264, 136, 8, 16.0, 0.25
+    layer, host = make_layer(d_in, d_out, r, "bf16", alpha, True)
+    layer.dropout = p
+    xs = synth.store(synth.normal(43, 1, (b * s, d_in)), "bf16")
+    gs = synth.store(synth.normal(43, 5, (b * s, d_out)), "bf16")
+    X, G = synth.widen(xs, "bf16"), synth.widen(gs, "bf16")
+    scale = alpha / r
+    layer.eval()
+    y_eval = layer(to_device(xs, "bf16").view(b, s, d_in))
+    assert relerr(to_f64(y_eval.reshape(-1, d_out)), oracle.scaled_forward(X, host["W"], host["A"], host["B"], scale, host["bias"])) < TOL["bf16"]
+    layer.train()
+    torch.manual_seed(5)
+    x = to_device(xs, "bf16").view(b, s, d_in).requires_grad_(True)
+    y = layer(x)
+    y.backward(to_device(gs, "bf16").view(b, s, d_out))
+    torch.cuda.synchronize()
+    mask, pq = oracle.dropout_mask(b * s, d_in, p, layer.last_dropout_seed)
+    Yw = oracle.dropout_forward(X, host["W"], host["A"], host["B"], mask, pq, scale, host["bias"])
+    dXw, dAw, dBw = oracle.dropout_backward(X, host["W"], host["A"], host["B"], G, mask, pq, scale)
+    assert relerr(to_f64(y.reshape(-1, d_out)), Yw) < TOL["bf16"]
+    assert relerr(to_f64(x.grad.reshape(-1, d_in)), dXw) < TOL["bf16"]
+    assert relerr(to_f64(layer.lora_A.grad), dAw) < TOL["bf16"] and relerr(to_f64(layer.lora_B.grad), dBw) < TOL["bf16"]
+    torch.manual_seed(5)
+    layer(x.detach())
+    first = layer.last_dropout_seed
+    layer(x.detach())
+    assert layer.last_dropout_seed != first            # a fresh mask per call
+    torch.manual_seed(5)
+    layer(x.detach())
+    assert layer.last_dropout_seed == first            # repeatable under torch.manual_seed

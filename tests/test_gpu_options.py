@@ -173,3 +173,85 @@ def test_layer_calls_can_be_captured_in_a_hip_graph():
             torch.cuda.synchronize()
             for k in out:
                 assert torch.equal(out[k], want[k]), (fwd, bwd, k)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_dropout_pairs_match_oracle(dtype):
+    """LoRA dropout on the adapter's input: the forward / backward graphs that exist with it, with a scale
+    and a bias, against the oracle under the same counter-based mask; and the mask really drops (the
+    result differs from the layer without dropout)."""
+    L = synth.Layer("drop", 333, 264, 392, 24, dtype, 37)
+    dev, host = layer_on_device(L)
+    bias_dev, bias64 = bias_for(L)
+    p, seed, scale = 0.3, 2024, 0.8
+    mask, pq = oracle.dropout_mask(L.n, L.i, p, seed)
+    Yw = oracle.dropout_forward(host["X"], host["W"], host["A"], host["B"], mask, pq, scale, bias64)
+    dXw, dAw, dBw = oracle.dropout_backward(host["X"], host["W"], host["A"], host["B"], host["dY"], mask, pq, scale)
+    want = {"Y": Yw, "dX": dXw, "dA": dAw, "dB": dBw}
+    plain = scaled_reference(host, scale, bias64)
+    assert relerr(plain["dA"], dAw) > 0.05
+    import torch
+    td = torch_dtype(dtype)
+    code = rl.dtype_from_name(dtype)
+    for fwd, bwd in [(0, 0), (1, 1), (0, 1)]:
+        print(f"case dropout dtype={dtype} fwd={fwd} bwd={bwd}", flush=True)
+        nan = float("nan")
+        Y = torch.full((L.n, L.o), nan, dtype=td, device="cuda")
+        T = torch.full((L.n, L.r), nan, dtype=td, device="cuda") if fwd == 0 else None
+        saved = rl.new_saved(T)
+        ws = rl.new_workspace(fwd, bwd, L.n, L.i, L.o, L.r, code)
+        rl.runlora_forward(fwd, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=ws, scale=scale,
+                           bias=bias_dev, dropout_p=p, dropout_seed=seed)
+        assert saved.dropout_thr == 77 and saved.dropout_seed == seed
+        ws.fill_(0xFF)
+        dX = torch.full((L.n, L.i), nan, dtype=td, device="cuda")
+        dA = torch.full((L.i, L.r), nan, dtype=td, device="cuda")
+        dB = torch.full((L.r, L.o), nan, dtype=td, device="cuda")
+        rl.runlora_backward(bwd, dev["dY"], saved, dev["W"], dev["A"], dev["B"], dX, dA, dB, workspace=ws)
+        torch.cuda.synchronize()
+        got = {"Y": to_f64(Y), "dX": to_f64(dX), "dA": to_f64(dA), "dB": to_f64(dB)}
+        for k in ("Y", "dX", "dA", "dB"):
+            err = relerr(got[k], want[k])
+            assert err < TOL[dtype], (fwd, bwd, k, err)
+    # graphs that merge AB into W or form X^T dY do not exist with dropout
+    Y = torch.empty((L.n, L.o), dtype=td, device="cuda")
+    ws = rl.new_workspace(2, 5, L.n, L.i, L.o, L.r, code)
+    with pytest.raises(rl.RunLoRAError) as e:
+        rl.runlora_forward(2, dev["X"], dev["W"], dev["A"], dev["B"], Y, rl.new_saved(), workspace=ws, dropout_p=p, dropout_seed=seed)
+    assert e.value.code == rl.RL_ERR_UNSUPPORTED
+    saved = rl.new_saved()
+    rl.runlora_forward(1, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=ws, dropout_p=p, dropout_seed=seed)
+    dX = torch.empty((L.n, L.i), dtype=td, device="cuda")
+    for bwd in (2, 3, 4, 5):
+        with pytest.raises(rl.RunLoRAError) as e:
+            rl.runlora_backward(bwd, dev["dY"], saved, dev["W"], dev["A"], dev["B"], dX, None, None, workspace=ws)
+        assert e.value.code == rl.RL_ERR_UNSUPPORTED
+
+
+def test_dropout_at_a_full_size_layer():
+    """OPT fc2 shape (n 4096, 8192 -> 2048, r 16): paired streaming launches with the mask on X in both
+    orientations, Y and dX on sampled rows, dA and dB in full."""
+    import torch
+    L = synth.config_opt13b_mlp("bf16")[1]
+    dev, host = layer_on_device(L)
+    p, seed = 0.1, 7
+    mask, pq = oracle.dropout_mask(L.n, L.i, p, seed)
+    rows = np.unique(np.concatenate([np.arange(0, L.n, 256), np.arange(255, L.n, 256), np.random.default_rng(3).integers(0, L.n, 16)]))
+    Yr = oracle.dropout_forward(host["X"][rows], host["W"], host["A"], host["B"], mask[rows], pq)
+    Xm = host["X"] * mask
+    s = 1.0 / (1.0 - pq)
+    Z1 = oracle.matmul(host["dY"], host["B"], tb=True)
+    dA = s * oracle.matmul(Xm, Z1, ta=True)
+    dB = s * oracle.matmul(oracle.matmul(Xm, host["A"]), host["dY"], ta=True)
+    dXr = oracle.matmul(host["dY"][rows], host["W"], tb=True) + s * mask[rows] * oracle.matmul(Z1[rows], host["A"], tb=True)
+    Y = torch.empty((L.n, L.o), dtype=torch.bfloat16, device="cuda")
+    gX = torch.empty((L.n, L.i), dtype=torch.bfloat16, device="cuda")
+    gA = torch.empty((L.i, L.r), dtype=torch.bfloat16, device="cuda")
+    gB = torch.empty((L.r, L.o), dtype=torch.bfloat16, device="cuda")
+    ws = rl.new_workspace(1, 1, L.n, L.i, L.o, L.r, rl.RL_BF16)
+    saved = rl.new_saved()
+    rl.runlora_forward(1, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=ws, dropout_p=p, dropout_seed=seed)
+    rl.runlora_backward(1, dev["dY"], saved, dev["W"], dev["A"], dev["B"], gX, gA, gB, workspace=ws)
+    torch.cuda.synchronize()
+    assert relerr(to_f64(Y)[rows], Yr) < TOL["bf16"] and relerr(to_f64(gX)[rows], dXr) < TOL["bf16"]
+    assert relerr(to_f64(gA), dA) < TOL["bf16"] and relerr(to_f64(gB), dB) < TOL["bf16"]

@@ -194,6 +194,59 @@ def test_scaled_layer_gradients_match_finite_differences():
     assert rel(Yr, oracle.scaled_forward(X, W, A, B, s, bias)[rows]) < 1e-14 and rel(dXr, dX[rows]) < 1e-14
 
 
+def test_dropout_mask_generator():
+    """The counter-based keep-mask: reproducible, keep rate 1 - p_q, the stated byte / group layout
+    (checked against a scalar re-implementation of the 32-bit hash on a few elements), different seeds
+    give different masks."""
+    n, i, p, seed = 64, 96, 0.3, 12345
+    m, pq = oracle.dropout_mask(n, i, p, seed)
+    assert pq == 77 / 256 and m.shape == (n, i) and set(np.unique(m)) <= {0.0, 1.0}
+    assert np.array_equal(m, oracle.dropout_mask(n, i, p, seed)[0])
+    assert abs(m.mean() - (1 - pq)) < 0.02
+    assert not np.array_equal(m, oracle.dropout_mask(n, i, p, seed + 1)[0])
+
+    def mix(x):
+        x &= 0xFFFFFFFF
+        x ^= x >> 16; x = (x * 0x7FEB352D) & 0xFFFFFFFF
+        x ^= x >> 15; x = (x * 0x846CA68B) & 0xFFFFFFFF
+        x ^= x >> 16
+        return x
+    key = mix(seed ^ 0x9E3779B9)
+    for t, c in [(0, 0), (0, 3), (1, 4), (17, 95), (63, 50)]:
+        h = mix((t * (i // 4) + c // 4) ^ key)
+        assert m[t, c] == float(((h >> (8 * (c % 4))) & 255) >= 77), (t, c)
+
+
+def test_dropout_layer_gradients_match_finite_differences():
+    X, W, A, B, G = draw(6, 8, 7, 3, seed=17)
+    m, pq = oracle.dropout_mask(6, 8, 0.4, 99)
+    assert 0 < m.sum() < m.size
+    s, bias, h = 1.7, synth.normal(17, 9, (7,)), 1e-6
+    sp = s / (1 - pq)
+
+    def loss(X, A, B):
+        return float(np.sum((X @ W + bias[None, :] + sp * (((X * m) @ A) @ B)) * G))
+
+    def fd(name):
+        base = {"X": X, "A": A, "B": B}
+        g = np.zeros_like(base[name])
+        for idx in np.ndindex(*g.shape):
+            pl = {k: v.copy() for k, v in base.items()}
+            mi = {k: v.copy() for k, v in base.items()}
+            pl[name][idx] += h
+            mi[name][idx] -= h
+            g[idx] = (loss(pl["X"], pl["A"], pl["B"]) - loss(mi["X"], mi["A"], mi["B"])) / (2 * h)
+        return g
+
+    assert rel(oracle.dropout_forward(X, W, A, B, m, pq, s, bias), X @ W + bias[None, :] + sp * (((X * m) @ A) @ B)) < 1e-14
+    dX, dA, dB = oracle.dropout_backward(X, W, A, B, G, m, pq, s)
+    assert rel(dX, fd("X")) < 1e-7 and rel(dA, fd("A")) < 1e-7 and rel(dB, fd("B")) < 1e-7
+    # an all-ones mask with p_q = 0 is the scaled layer without dropout
+    ones = np.ones_like(m)
+    for got, want in zip(oracle.dropout_backward(X, W, A, B, G, ones, 0.0, s), oracle.scaled_backward(X, W, A, B, G, s)):
+        assert rel(got, want) < 1e-13
+
+
 # ---- all computation graphs agree ---------------------------------------------------------------
 
 @pytest.mark.parametrize("shape", SHAPES)
