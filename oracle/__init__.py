@@ -233,3 +233,34 @@ def dropout_backward(X, W, A, B, dY, mask, p_q, scale=1.0):
     dX = matmul(dY, W, tb=True) + s * mask * matmul(Z1, A, tb=True)
     return dX, dA, dB
 
+
+
+# ---- VeRA: frozen A and B, trainable scaling vectors (named in the paper's conclusion as an adapter ----
+# the method carries over to; the paper gives no formulas, the definition below is the published one
+# written in this file's orientation, Y = XW):
+#     Y = XW + 1 bias^T + s (((X A) diag(d)) B) diag(b),      d in R^r, b in R^o trainable, A, B, W frozen
+# Gradients by the chain rule, step by step through T = XA, U = T diag(d), V = U B, Y = .. + s V diag(b):
+#     dV = s dY diag(b);  db[j] = s sum_t dY[t,j] V[t,j];  dU = dV B^T;  dd[k] = sum_t T[t,k] dU[t,k];
+#     dX = dY W^T + (dU diag(d)) A^T.
+
+def vera_forward(X, W, A, B, d, b, scale=1.0, bias=None):
+    X, W, A, B, d, b = map(_f64, (X, W, A, B, d, b))
+    T = matmul(X, A)
+    V = matmul(T * d.reshape(1, -1), B)
+    Y = matmul(X, W) + float(scale) * V * b.reshape(1, -1)
+    if bias is not None:
+        Y = Y + _f64(bias).reshape(1, -1)
+    return Y
+
+
+def vera_backward(X, W, A, B, d, b, dY, scale=1.0):
+    """(dX [n,i], dd [r], db [o])."""
+    X, W, A, B, d, b, dY = map(_f64, (X, W, A, B, d, b, dY))
+    s = float(scale)
+    T = matmul(X, A)
+    V = matmul(T * d.reshape(1, -1), B)
+    db = s * np.sum(dY * V, axis=0)
+    dU = matmul(s * dY * b.reshape(1, -1), B, tb=True)
+    dd = np.sum(T * dU, axis=0)
+    dX = matmul(dY, W, tb=True) + matmul(dU * d.reshape(1, -1), A, tb=True)
+    return dX, dd, db

@@ -247,6 +247,57 @@ def test_dropout_layer_gradients_match_finite_differences():
         assert rel(got, want) < 1e-13
 
 
+def test_vera_layer_against_loops_finite_differences_and_lora():
+    """VeRA, Y = XW + bias + s ((XA) diag(d)) B diag(b): the oracle against the definition written as scalar
+    loops, its gradients against central differences, and its reduction to the LoRA layer (d = 1, b = 1
+    is Eq. 1; in general it is Eq. 1 on B' = diag(d) B diag(b))."""
+    n, i, o, r = 5, 7, 6, 3
+    X, W, A, B, G = draw(n, i, o, r, seed=23)
+    d, b, bias = synth.normal(23, 8, (r,)), synth.normal(23, 9, (o,)), synth.normal(23, 10, (o,))
+    s, h = 0.6, 1e-6
+    Y = oracle.vera_forward(X, W, A, B, d, b, s, bias)
+    want = np.zeros((n, o))
+    for t in range(n):
+        for j in range(o):
+            acc = bias[j]
+            for c in range(i):
+                acc += X[t, c] * W[c, j]
+            for k in range(r):
+                xa = sum(X[t, c] * A[c, k] for c in range(i))
+                acc += s * xa * d[k] * B[k, j] * b[j]
+            want[t, j] = acc
+    assert rel(Y, want) < 1e-13
+
+    def loss(X, d, b):
+        return float(np.sum((X @ W + bias[None, :] + s * (((X @ A) * d[None, :]) @ B) * b[None, :]) * G))
+
+    def fd(name):
+        base = {"X": X, "d": d, "b": b}
+        g = np.zeros_like(base[name])
+        for idx in np.ndindex(*g.shape):
+            pl = {k: v.copy() for k, v in base.items()}
+            mi = {k: v.copy() for k, v in base.items()}
+            pl[name][idx] += h
+            mi[name][idx] -= h
+            g[idx] = (loss(pl["X"], pl["d"], pl["b"]) - loss(mi["X"], mi["d"], mi["b"])) / (2 * h)
+        return g
+
+    dX, dd, db = oracle.vera_backward(X, W, A, B, d, b, G, s)
+    assert dd.shape == (r,) and db.shape == (o,)
+    assert rel(dX, fd("X")) < 1e-7 and rel(dd, fd("d")) < 1e-7 and rel(db, fd("b")) < 1e-7
+    # reduction to the paper's layer
+    Bp = d[:, None] * B * b[None, :]
+    assert rel(Y, oracle.scaled_forward(X, W, A, Bp, s, bias)) < 1e-13
+    dXl, _, dBl = oracle.scaled_backward(X, W, A, Bp, G, s)
+    assert rel(dX, dXl) < 1e-13
+    assert rel(dd, np.sum(dBl * B * b[None, :], axis=1)) < 1e-12 and rel(db, np.sum(dBl * B * d[:, None], axis=0)) < 1e-12
+    one_r, one_o = np.ones(r), np.ones(o)
+    assert rel(oracle.vera_forward(X, W, A, B, one_r, one_o), oracle.reference_forward(X, W, A, B)) < 1e-14
+    # a zero d switches the adapter off but leaves a gradient for d; a zero b leaves one for b only
+    dX0, dd0, db0 = oracle.vera_backward(X, W, A, B, np.zeros(r), b, G, s)
+    assert rel(dX0, G @ W.T) < 1e-14 and np.any(dd0 != 0.0) and np.all(db0 == 0.0)
+
+
 # ---- all computation graphs agree ---------------------------------------------------------------
 
 @pytest.mark.parametrize("shape", SHAPES)
