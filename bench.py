@@ -49,6 +49,8 @@ def parse():
                     help="let forward2 keep W + AB for backward4/5 (i*o elements held per layer; pairs chosen for that)")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="LoRA dropout probability (0 = the paper's setting); pairs are then (1,1), the only RunLoRA graphs that exist with it")
+    ap.add_argument("--vera", action="store_true",
+                    help="run the layers as VeRA (frozen A, B, trainable vectors d and b; use with --rank 256 or so) through runlora_vera_*")
     ap.add_argument("--pair", default=None, help="force one 'fwd,bwd' pair on every layer instead of runlora_select")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a 1 GiB device copy five times (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -122,6 +124,11 @@ def main():
             t["dA"] = torch.empty((L.i, L.r), dtype=tdt, device=dev)
             t["dB"] = torch.empty((L.r, L.o), dtype=tdt, device=dev)
             t["M"] = torch.empty((L.i, L.o), dtype=tdt, device=dev) if args.keep_merged else None
+            if args.vera:
+                t["d"] = to_dev(synth.store(synth.normal(synth.BASE_SEED + L.index, 10, (L.r,)), dtype))
+                t["b"] = to_dev(synth.store(synth.normal(synth.BASE_SEED + L.index, 11, (L.o,)), dtype))
+                t["dd"] = torch.empty((L.r,), dtype=tdt, device=dev)
+                t["db"] = torch.empty((L.o,), dtype=tdt, device=dev)
             sets.append(t)
         if args.dropout > 0.0:
             fwd, bwd = 1, 1
@@ -133,6 +140,9 @@ def main():
         wd = rl.RL_INT4_G64 if int4 else None
         ws_bytes = max(rl.runlora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code, wd),
                        rl.runlora_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code, wd))
+        if args.vera:
+            ws_bytes = max(rl.runlora_vera_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code),
+                           rl.runlora_vera_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code))
         ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
         state.append(dict(L=L, sets=sets, pair=(fwd, bwd), ws=ws))
 
@@ -141,6 +151,11 @@ def main():
             t = st["sets"][k % args.sets]
             fwd, bwd = (0, 0) if default_chain else st["pair"]
             saved = rl.new_saved(t["T"] if fwd == 0 else None, t["M"] if fwd == 2 and bwd in rl.BWD_MERGED else None)
+            if args.vera:
+                rl.runlora_vera_forward(fwd, t["X"], t["W"], t["A"], t["B"], t["d"], t["b"], t["Y"], saved, st["ws"])
+                rl.runlora_vera_backward(bwd, t["dY"], saved, t["W"], t["A"], t["B"], t["d"], t["b"], t["dX"], t["dd"],
+                                         t["db"], st["ws"])
+                continue
             rl.runlora_forward(fwd, t["X"], t["W"], t["A"], t["B"], t["Y"], saved, workspace=st["ws"],
                                dropout_p=args.dropout or None, dropout_seed=k)
             rl.runlora_backward(bwd, t["dY"], saved, t["W"], t["A"], t["B"], t["dX"], t["dA"], t["dB"],
@@ -168,6 +183,8 @@ def main():
                     continue
                 fl = rl.runlora_flops(0, f, L.n, L.i, L.o, L.r) + rl.runlora_flops(1, b, L.n, L.i, L.o, L.r)
                 best = fl if best is None else min(best, fl)
+        if args.vera:  # no gradient for A: its product, X^T (dY B^T) or (X^T dY) B^T, is not part of the layer
+            best -= 2 * L.r * L.i * min(L.n, L.o)
         return best
 
     f_useful = sum(useful_flops(L) for L in layers)
@@ -262,7 +279,8 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": wl_name, "layers": [dict(name=L.name, n=L.n, d_in=L.i, d_out=L.o, r=L.r) for L in layers],
                    "pairs": {st["L"].name: list(st["pair"]) for st in state}, "input_sets": args.sets,
-                   "keep_merged": bool(args.keep_merged), "lora_dropout": args.dropout},
+                   "keep_merged": bool(args.keep_merged), "lora_dropout": args.dropout,
+                   "adapter": "vera" if args.vera else "lora"},
         "ms_per_step_default_chain": round(sec_def * 1e3, 4),
         "speedup_over_default_chain": round(sec_def / sec_sel, 4),
         "time_reduction_pct": round(100.0 * (sec_def - sec_sel) / sec_def, 2),

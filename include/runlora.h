@@ -201,6 +201,33 @@ int runlora_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved
                      rl_tensor_t* dX, rl_tensor_t* dA, rl_tensor_t* dB, const rl_opts_t* opts);
 
 /*
+ * VeRA on the same computation graphs.  The paper's conclusion names VeRA among the LoRA variants its
+ * method extends to and gives no formulas; the layer here is the published one in this header's
+ * orientation: A [i,r] and B [r,o] frozen (random, shared between layers), trainable vectors d [r], b [o],
+ *     Y  = X W + 1 bias^T + s ((X A) diag(d)) B diag(b)
+ *     dX = dY W^T + s ((dY diag(b) B^T) diag(d)) A^T
+ *     dd[k] = s sum_t (XA)[t,k] (dY diag(b) B^T)[t,k],      db[j] = s sum_t dY[t,j] ((XA) diag(d) B)[t,j].
+ * It runs as the LoRA layer on (A, B~), B~ = diag(d) B diag(b) (r*o elements formed in the workspace, rounded
+ * to the storage type like every rank-r factor): `variant` is any rl_fwd_variant_t / rl_bwd_variant_t, *saved
+ * is the same record (a forward of one family may not be followed by a backward of the other), rl_opts_t
+ * means the same (scale, bias, dropout, stream), and the vector gradients are reductions of the LoRA
+ * graph's dB~ = s (XA)^T dY:  dd[k] = sum_j dB~[k,j] B[k,j] b[j],  db[j] = sum_k dB~[k,j] d[k] B[k,j]
+ * (fp32 sums in a fixed order, rounded once).  No gradient is formed for A.
+ *   d, b     device pointers, r and o elements of the activation dtype, 16-byte aligned
+ *   dd, db   device pointers (same sizes, dtype, alignment), overwritten; either may be NULL (skipped),
+ *            as may dX
+ *   workspace  required: runlora_vera_workspace_bytes(fwd, bwd, ...) bytes (fwd or bwd < 0: that side only)
+ * A kept W + s A B~ (rl_saved_t.M) is valid only while d and b are what the forward saw.
+ */
+int runlora_vera_forward(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
+                         const rl_tensor_t* B, const void* d, const void* b, rl_tensor_t* Y, rl_saved_t* saved,
+                         const rl_opts_t* opts);
+int runlora_vera_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved, const rl_tensor_t* W,
+                          const rl_tensor_t* A, const rl_tensor_t* B, const void* d, const void* b,
+                          rl_tensor_t* dX, void* dd, void* db, const rl_opts_t* opts);
+size_t runlora_vera_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype);
+
+/*
  * Choose the (forward, backward) pair for one layer shape ("choosing best forward and backward
  * computation graph based on FLOPs and time estimations", abstract).  Pure host function,
  * thread-safe, no HIP call.  Uses the time model unless the environment variable

@@ -34,6 +34,7 @@ EXPORTS = (
     "runlora_strerror", "runlora_last_hip_error",
     "runlora_version", "runlora_gemm", "runlora_gemm_workspace_bytes",
     "runlora_profile_enable", "runlora_profile_collect", "runlora_profile_disable", "runlora_probe_mfma",
+    "runlora_vera_forward", "runlora_vera_backward", "runlora_vera_workspace_bytes",
 )
 
 
@@ -103,6 +104,13 @@ def lib():
     L.runlora_forward.restype = ci
     L.runlora_backward.argtypes = [ci, tp, sp, tp, tp, tp, tp, tp, tp, op]
     L.runlora_backward.restype = ci
+    vp = ctypes.c_void_p
+    L.runlora_vera_forward.argtypes = [ci, tp, tp, tp, tp, vp, vp, tp, sp, op]
+    L.runlora_vera_forward.restype = ci
+    L.runlora_vera_backward.argtypes = [ci, tp, sp, tp, tp, tp, vp, vp, tp, vp, vp, op]
+    L.runlora_vera_backward.restype = ci
+    L.runlora_vera_workspace_bytes.argtypes = [ci, ci, i64, i64, i64, i64, ci]
+    L.runlora_vera_workspace_bytes.restype = ctypes.c_size_t
     L.runlora_select.argtypes = [i64, i64, i64, i64, ci, ip, ip]
     L.runlora_select.restype = ci
     L.runlora_select_by.argtypes = [ci, i64, i64, i64, i64, ci, ip, ip]
@@ -233,6 +241,44 @@ def runlora_backward(variant, dY, saved, W, A, B, dX, dA, dB, workspace=None, st
     _check(lib().runlora_backward(variant, _ref(ddy), ctypes.byref(saved), _ref(dw), _ref(da), _ref(db), _ref(gx),
                                   _ref(ga), _ref(gb), ctypes.byref(o)))
     return dX, dA, dB
+
+
+def _vec(t, count, dtype, name):
+    """Device pointer of a 1-D vector argument (None -> NULL)."""
+    if t is None:
+        return None
+    if t.dim() != 1 or t.numel() != count or t.dtype != dtype or t.stride(0) != 1:
+        raise ValueError(f"{name} must be a dense vector of {count} elements of the activation dtype")
+    return t.data_ptr()
+
+
+def runlora_vera_forward(variant, X, W, A, B, d, b, Y, saved, workspace, stream=None, scale=None, bias=None,
+                         dropout_p=None, dropout_seed=0):
+    """VeRA forward, Y = XW (+ bias) + scale ((XA) diag(d)) B diag(b), in forward graph `variant`; the
+    workspace (runlora_vera_workspace_bytes) is required.  Other arguments as runlora_forward."""
+    if bias is not None and (bias.dtype != X.dtype or bias.numel() != Y.shape[1]):
+        raise ValueError("bias must have d_out elements of the activation dtype")
+    dx, dw, da, db, dy = (tensor_desc(t) for t in (X, W, A, B, Y))
+    o = _opts(workspace, stream, scale, bias, dropout_p, dropout_seed)
+    _check(lib().runlora_vera_forward(variant, _ref(dx), _ref(dw), _ref(da), _ref(db), _vec(d, B.shape[0], X.dtype, "d"),
+                                      _vec(b, B.shape[1], X.dtype, "b"), _ref(dy), ctypes.byref(saved), ctypes.byref(o)))
+    return Y
+
+
+def runlora_vera_backward(variant, dY, saved, W, A, B, d, b, dX, dd, db, workspace, stream=None):
+    """VeRA gradients for X, d and b in backward graph `variant`; any of dX / dd / db may be None."""
+    ddy, dw, da, dbm = (tensor_desc(t) for t in (dY, W, A, B))
+    gx = tensor_desc(dX)
+    o = _opts(workspace, stream)
+    r, oo = B.shape
+    _check(lib().runlora_vera_backward(variant, _ref(ddy), ctypes.byref(saved), _ref(dw), _ref(da), _ref(dbm),
+                                       _vec(d, r, dY.dtype, "d"), _vec(b, oo, dY.dtype, "b"), _ref(gx),
+                                       _vec(dd, r, dY.dtype, "dd"), _vec(db, oo, dY.dtype, "db"), ctypes.byref(o)))
+    return dX, dd, db
+
+
+def runlora_vera_workspace_bytes(fwd, bwd, n, i, o, r, dtype):
+    return int(lib().runlora_vera_workspace_bytes(fwd, bwd, n, i, o, r, dtype))
 
 
 def runlora_select(n_tokens, d_in, d_out, r, dtype, criterion=None):

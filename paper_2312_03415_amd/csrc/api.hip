@@ -5,6 +5,7 @@
 
 #include "../../include/runlora.h"
 #include "schedule.hpp"
+#include "vera.hpp"
 
 using namespace rl;
 
@@ -144,7 +145,16 @@ void describe_step(const Step& s, rl_step_time_t* r) {
   r->a_strided = d.a_strided; r->b_kcontig = d.b_kcontig;
 }
 
+// While set, the layer calls check their arguments and build their schedule but enqueue nothing: an
+// entry point built on top of them validates everything this way before its own first launch.
+thread_local bool g_dry_run = false;
+struct DryRun {
+  DryRun() { g_dry_run = true; }
+  ~DryRun() { g_dry_run = false; }
+};
+
 int run_schedule(const Schedule& sch, char* ws, hipStream_t stream) {
+  if (g_dry_run) return RL_OK;
   float* partial = ws ? reinterpret_cast<float*>(ws + sch.partial_offset) : nullptr;
   for (const Step& s : sch.steps) {
     const bool timed = g_prof.on && g_prof.used < g_prof.start.size();
@@ -347,6 +357,117 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   if ((rc = check_workspace(sch, opts)) != RL_OK) return rc;
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
   return run_schedule(sch, ws, stream);
+}
+
+// ---- VeRA: the LoRA graphs on (A, B~ = diag(d) B diag(b)), see vera.hpp ------------------------------------
+
+namespace {
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// workspace layout of the VeRA calls: [B~ r x o][dB~ r x o][the LoRA call's own workspace]
+struct VeraLayout {
+  size_t factor_bytes = 0;  // one r x o matrix in the layer dtype, rounded up to 256
+  rl_tensor_t Bt{}, dBt{};
+  rl_opts_t inner{};
+};
+
+int vera_layout(const rl_tensor_t* B, const void* d, const void* b, const rl_opts_t* opts, VeraLayout* v) {
+  if (!B || !d || !b) return RL_ERR_NULL;
+  const int dt = internal_dtype(B->dtype);
+  if (dt < 0) return RL_ERR_DTYPE;
+  if (B->rows < 1 || B->cols < 1 || B->rows > (1LL << 30) || B->cols > (1LL << 30)) return RL_ERR_SHAPE;
+  if (((reinterpret_cast<uintptr_t>(d) | reinterpret_cast<uintptr_t>(b)) & 15) != 0) return RL_ERR_ALIGN;
+  v->factor_bytes = align256((size_t)B->rows * (size_t)B->cols * dtype_size(dt));
+  if (!opts || !opts->workspace || opts->workspace_bytes < 2 * v->factor_bytes) return RL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(opts->workspace) & 255) != 0) return RL_ERR_ALIGN;
+  char* ws = static_cast<char*>(opts->workspace);
+  v->Bt = rl_tensor_t{ws, B->rows, B->cols, B->cols, B->dtype, nullptr, 0};
+  v->dBt = rl_tensor_t{ws + v->factor_bytes, B->rows, B->cols, B->cols, B->dtype, nullptr, 0};
+  v->inner = *opts;
+  v->inner.workspace = ws + 2 * v->factor_bytes;
+  v->inner.workspace_bytes = opts->workspace_bytes - 2 * v->factor_bytes;
+  return RL_OK;
+}
+
+}  // namespace
+
+extern "C" int runlora_vera_forward(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
+                                    const rl_tensor_t* B, const void* d, const void* b, rl_tensor_t* Y,
+                                    rl_saved_t* saved, const rl_opts_t* opts) {
+  if (!X || !W || !A || !B || !Y || !saved) return RL_ERR_NULL;
+  VeraLayout v;
+  int rc = vera_layout(B, d, b, opts, &v);
+  if (rc != RL_OK) return rc;
+  if (B->dtype != X->dtype) return RL_ERR_DTYPE;
+  if ((rc = check_tensor(B, A->cols, W->cols, X->dtype)) != RL_OK) return rc;
+  const size_t esz = dtype_size(internal_dtype(B->dtype));
+  if (Y->data && Y->rows >= 1 && Y->ld >= Y->cols && Y->cols == B->cols) {
+    Range ry = range_of(Y->data, Y->rows, Y->ld, Y->cols, esz);
+    if (overlap(ry, range_of(d, 1, B->rows, B->rows, esz)) || overlap(ry, range_of(b, 1, B->cols, B->cols, esz)) ||
+        overlap(ry, range_of(B->data, B->rows, B->ld, B->cols, esz)))
+      return RL_ERR_ALIAS;
+  }
+  {
+    DryRun dry;  // every check of the layer call, before the first launch
+    rl_saved_t probe = *saved;
+    if ((rc = runlora_forward(variant, X, W, A, &v.Bt, Y, &probe, &v.inner)) != RL_OK) return rc;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(opts->stream);
+  hipError_t e = vera_scale_run(internal_dtype(B->dtype), B->data, B->ld, d, b, v.Bt.data, v.Bt.ld, B->rows, B->cols, stream);
+  if (e != hipSuccess) return set_hip_error(e, "B~ = diag(d) B diag(b)");
+  return runlora_forward(variant, X, W, A, &v.Bt, Y, saved, &v.inner);
+}
+
+extern "C" int runlora_vera_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved, const rl_tensor_t* W,
+                                     const rl_tensor_t* A, const rl_tensor_t* B, const void* d, const void* b,
+                                     rl_tensor_t* dX, void* dd, void* db, const rl_opts_t* opts) {
+  if (!dY || !saved || !W || !A || !B) return RL_ERR_NULL;
+  VeraLayout v;
+  int rc = vera_layout(B, d, b, opts, &v);
+  if (rc != RL_OK) return rc;
+  if (B->dtype != dY->dtype) return RL_ERR_DTYPE;
+  if ((rc = check_tensor(B, A->cols, dY->cols, dY->dtype)) != RL_OK) return rc;
+  if (((reinterpret_cast<uintptr_t>(dd) | reinterpret_cast<uintptr_t>(db)) & 15) != 0) return RL_ERR_ALIGN;
+  const size_t esz = dtype_size(internal_dtype(B->dtype));
+  const int64_t r = B->rows, o = B->cols;
+  {  // the vector gradients must not overlap anything the call reads or its other outputs
+    Range outs[2] = {dd ? range_of(dd, 1, r, r, esz) : Range{nullptr, nullptr}, db ? range_of(db, 1, o, o, esz) : Range{nullptr, nullptr}};
+    std::vector<Range> others = {range_of(d, 1, r, r, esz), range_of(b, 1, o, o, esz), range_of(B->data, r, B->ld, o, esz)};
+    if (dY->data && dY->rows >= 1 && dY->ld >= dY->cols) others.push_back(range_of(dY->data, dY->rows, dY->ld, dY->cols, esz));
+    if (A->data && A->rows >= 1 && A->ld >= A->cols) others.push_back(range_of(A->data, A->rows, A->ld, A->cols, esz));
+    if (saved->X && saved->n >= 1 && saved->ldx >= saved->i && saved->i >= 1) others.push_back(range_of(saved->X, saved->n, saved->ldx, saved->i, esz));
+    if (dX && dX->data && dX->rows >= 1 && dX->ld >= dX->cols) others.push_back(range_of(dX->data, dX->rows, dX->ld, dX->cols, esz));
+    if (W->data && W->rows >= 1 && W->ld >= W->cols) others.push_back(range_of(W->data, W->rows, W->ld, W->cols, W->dtype == RL_INT4_G64 ? 1 : esz));
+    for (const Range& out : outs) {
+      if (!out.lo) continue;
+      for (const Range& in : others)
+        if (overlap(out, in)) return RL_ERR_ALIAS;
+    }
+    if (outs[0].lo && outs[1].lo && overlap(outs[0], outs[1])) return RL_ERR_ALIAS;
+  }
+  rl_tensor_t* dBt = (dd || db) ? &v.dBt : nullptr;
+  {
+    DryRun dry;
+    if ((rc = runlora_backward(variant, dY, saved, W, A, &v.Bt, dX, nullptr, dBt, &v.inner)) != RL_OK) return rc;
+  }
+  const int dt = internal_dtype(B->dtype);
+  hipStream_t stream = static_cast<hipStream_t>(opts->stream);
+  hipError_t e = vera_scale_run(dt, B->data, B->ld, d, b, v.Bt.data, v.Bt.ld, r, o, stream);
+  if (e != hipSuccess) return set_hip_error(e, "B~ = diag(d) B diag(b)");
+  if ((rc = runlora_backward(variant, dY, saved, W, A, &v.Bt, dX, nullptr, dBt, &v.inner)) != RL_OK) return rc;
+  if (dBt) {
+    e = vera_grad_run(dt, v.dBt.data, v.dBt.ld, B->data, B->ld, d, b, dd, db, r, o, stream);
+    if (e != hipSuccess) return set_hip_error(e, "dd, db from dB~");
+  }
+  return RL_OK;
+}
+
+extern "C" size_t runlora_vera_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype) {
+  const int dt = internal_dtype(dtype);
+  if (dt < 0 || n < 1 || i < 1 || o < 1 || r < 1) return 0;
+  if (fwd > RL_FWD2 || bwd > RL_BWD8 || (fwd < 0 && bwd < 0)) return 0;
+  return 2 * align256((size_t)r * (size_t)o * dtype_size(dt)) + runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype);
 }
 
 extern "C" size_t runlora_saved_bytes(int fwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype, int keep_merged) {

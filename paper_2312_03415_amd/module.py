@@ -9,6 +9,7 @@ and every product runs inside the HIP library through binding.runlora_forward / 
     layer = RunLoRALinear.from_linear(nn_linear, r=16, alpha=32)     # W frozen, A and B trainable
     y = layer(x)                                                     # x [..., d_in] -> [..., d_out]
     wrap_linears(model, r=16, alpha=32, targets=("q_proj", "v_proj"))
+    vera = RunVeRALinear(weight, A_shared, B_shared)                 # frozen A, B; trainable vectors d, b
 """
 import math
 
@@ -138,6 +139,90 @@ class RunLoRALinear(nn.Module):
                                          (self.dropout, self.last_dropout_seed))
         return RunLoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.bias, self.scale,
                                      self.pair_for(n), self.keep_merged)
+
+    def extra_repr(self):
+        return f"d_in={self.d_in}, d_out={self.d_out}, r={self.r}, scale={self.scale:g}, bias={self.bias is not None}"
+
+
+class RunVeRAFunction(torch.autograd.Function):
+    """y = x W + bias + scale ((x A) diag(d)) B diag(b) with W, bias, A and B frozen; gradients for x, d and b
+    (runlora_vera_forward / runlora_vera_backward: the LoRA graphs on B~ = diag(d) B diag(b))."""
+
+    @staticmethod
+    def forward(ctx, x, W, A, B, d, b, bias, scale, pair):
+        fwd, bwd = pair
+        i, o = W.shape
+        r = A.shape[1]
+        x2 = x.reshape(-1, i)
+        if x2.stride(-1) != 1 or x2.stride(0) % 8 != 0 or x2.data_ptr() % 16 != 0:
+            x2 = x2.contiguous()
+        n = x2.shape[0]
+        code = rl.dtype_code(x.dtype)
+        y = torch.empty((n, o), dtype=x.dtype, device=x.device)
+        T = torch.empty((n, r), dtype=x.dtype, device=x.device) if fwd == rl.FWD_DEFAULT else None
+        saved = rl.new_saved(T)
+        ws = _workspace(x.device, rl.runlora_vera_workspace_bytes(fwd, bwd, n, i, o, r, code))
+        rl.runlora_vera_forward(fwd, x2, W, A, B, d, b, y, saved, ws, scale=scale, bias=bias)
+        ctx.saved = saved
+        ctx.bwd = bwd
+        ctx.keep = T
+        ctx.x_shape = x.shape
+        ctx.save_for_backward(x2, W, A, B, d, b)
+        return y.view(*x.shape[:-1], o)
+
+    @staticmethod
+    def backward(ctx, dy):
+        x2, W, A, B, d, b = ctx.saved_tensors
+        i, o = W.shape
+        r = A.shape[1]
+        n = x2.shape[0]
+        dy2 = dy.reshape(n, o)
+        if dy2.stride(-1) != 1 or dy2.stride(0) % 8 != 0 or dy2.data_ptr() % 16 != 0:
+            dy2 = dy2.contiguous()
+        need = ctx.needs_input_grad
+        dx = torch.empty((n, i), dtype=x2.dtype, device=x2.device) if need[0] else None
+        dd = torch.empty_like(d) if need[4] else None
+        db = torch.empty_like(b) if need[5] else None
+        code = rl.dtype_code(dy.dtype)
+        ws = _workspace(dy.device, rl.runlora_vera_workspace_bytes(-1, ctx.bwd, n, i, o, r, code))
+        rl.runlora_vera_backward(ctx.bwd, dy2, ctx.saved, W, A, B, d, b, dx, dd, db, ws)
+        if dx is not None:
+            dx = dx.view(ctx.x_shape)
+        return dx, None, None, None, dd, db, None, None, None
+
+
+class RunVeRALinear(nn.Module):
+    """VeRA layer: frozen W [d_in, d_out] (+ bias) and frozen random A [d_in, r], B [r, d_out] (pass the
+    same tensors to every layer to share them, as VeRA does), trainable vectors d [r] (start 0.1) and
+    b [d_out] (start 0, so that the layer starts as the frozen one)."""
+
+    def __init__(self, weight, A, B, bias=None, scale=1.0, pair=None, d_init=0.1):
+        super().__init__()
+        d_in, d_out = weight.shape
+        r = A.shape[1]
+        if A.shape != (d_in, r) or B.shape != (r, d_out):
+            raise ValueError("A must be [d_in, r] and B [r, d_out]")
+        self.d_in, self.d_out, self.r, self.scale, self.pair = d_in, d_out, r, float(scale), pair
+        self.weight = nn.Parameter(weight.contiguous(), requires_grad=False)
+        self.bias = nn.Parameter(bias.contiguous(), requires_grad=False) if bias is not None else None
+        self.register_buffer("vera_A", A, persistent=False)
+        self.register_buffer("vera_B", B, persistent=False)
+        self.vera_d = nn.Parameter(torch.full((r,), d_init, dtype=weight.dtype, device=weight.device))
+        self.vera_b = nn.Parameter(torch.zeros(d_out, dtype=weight.dtype, device=weight.device))
+        self._pairs = {}
+
+    def pair_for(self, n_tokens):
+        if self.pair is not None:
+            return self.pair
+        p = self._pairs.get(n_tokens)
+        if p is None:
+            p = rl.runlora_select(n_tokens, self.d_in, self.d_out, self.r, rl.dtype_code(self.weight.dtype))
+            self._pairs[n_tokens] = p
+        return p
+
+    def forward(self, x):
+        return RunVeRAFunction.apply(x, self.weight, self.vera_A, self.vera_B, self.vera_d, self.vera_b, self.bias,
+                                     self.scale, self.pair_for(x.numel() // self.d_in))
 
     def extra_repr(self):
         return f"d_in={self.d_in}, d_out={self.d_out}, r={self.r}, scale={self.scale:g}, bias={self.bias is not None}"

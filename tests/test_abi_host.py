@@ -218,6 +218,56 @@ def test_backward_rejects_bad_arguments_before_touching_the_gpu():
     assert call(1, dX=None) == rl.RL_ERR_WORKSPACE          # skipping dX is legal; still needs scratch
 
 
+def test_vera_calls_reject_bad_arguments_before_touching_the_gpu():
+    """The VeRA entry points check their own arguments and, through a dry run of the layer call they are
+    built on, everything that call checks, before the first launch."""
+    n, i, o, r = 64, 32, 48, 8
+    dt = rl.RL_BF16
+    L = rl.lib()
+    br = ctypes.byref
+    a = fwd_args(n, i, o, r)
+    d, b = 0x20000000, 0x20001000
+    need = rl.runlora_vera_workspace_bytes(1, 1, n, i, o, r, dt)
+    assert need == 2 * ((r * o * 2 + 255) // 256 * 256) + rl.runlora_workspace_bytes(1, 1, n, i, o, r, dt)
+    assert rl.runlora_vera_workspace_bytes(3, 1, n, i, o, r, dt) == 0 and rl.runlora_vera_workspace_bytes(-1, -1, n, i, o, r, dt) == 0
+    ws = rl.rl_opts_t(None, 0x70000000, need)
+
+    def fwd(variant, a=a, d=d, b=b, opts=ws):
+        return L.runlora_vera_forward(variant, br(a["X"]), br(a["W"]), br(a["A"]), br(a["B"]), d, b, br(a["Y"]),
+                                      br(rl.rl_saved_t()), br(opts) if opts else None)
+
+    assert fwd(1, d=None) == rl.RL_ERR_NULL
+    assert fwd(1, b=b + 4) == rl.RL_ERR_ALIGN
+    assert fwd(1, opts=None) == rl.RL_ERR_WORKSPACE
+    assert fwd(1, opts=rl.rl_opts_t(None, 0x70000000, 2 * 768)) == rl.RL_ERR_WORKSPACE      # room for B~ and dB~ only
+    assert fwd(5) == rl.RL_ERR_VARIANT
+    assert fwd(1, d=a["Y"].data) == rl.RL_ERR_ALIAS
+    c = fwd_args(n, i, o, r); c["X"].ld = 36
+    assert fwd(1, a=c) == rl.RL_ERR_ALIGN                                                   # found by the dry run
+    c = fwd_args(n, i, o, r); c["B"].rows = 16
+    assert fwd(1, a=c) == rl.RL_ERR_SHAPE
+    assert fwd(0) == rl.RL_ERR_NULL                                                         # default chain: no T buffer given
+
+    base, step = 0x10000000, 0x1000000
+    dY, W, A, B, dX = T(base, n, o), T(base + step, i, o), T(base + 2 * step, i, r), T(base + 3 * step, r, o), T(base + 4 * step, n, i)
+    saved = rl.rl_saved_t(1, dt, n, i, o, r, base + 7 * step, i, None, 0)
+    dd, db = 0x20002000, 0x20003000
+
+    def bwd(variant, saved=saved, d=d, b=b, dd=dd, db=db, opts=ws):
+        return L.runlora_vera_backward(variant, br(dY), br(saved), br(W), br(A), br(B), d, b, br(dX), dd, db,
+                                       br(opts) if opts else None)
+
+    assert bwd(9) == rl.RL_ERR_VARIANT
+    assert bwd(1, b=None) == rl.RL_ERR_NULL
+    assert bwd(1, dd=dd + 8) == rl.RL_ERR_ALIGN
+    assert bwd(1, dd=d) == rl.RL_ERR_ALIAS
+    assert bwd(1, db=dY.data) == rl.RL_ERR_ALIAS
+    assert bwd(1, dd=db) == rl.RL_ERR_ALIAS
+    assert bwd(0) == rl.RL_ERR_SAVED_MISMATCH
+    assert bwd(1, opts=rl.rl_opts_t(None, 0x70000000, 2 * 768)) == rl.RL_ERR_WORKSPACE
+    assert bwd(1, saved=rl.rl_saved_t(1, dt, n + 1, i, o, r, base + 7 * step, i, None, 0)) == rl.RL_ERR_SAVED_MISMATCH
+
+
 def test_gemm_call_rejects_bad_arguments():
     g = rl.rl_gemm_t(rl.RL_BF16, 1, 1, -1, 0, 64, 64, 64, 0, 0x1000, 0x2000, None, None, None, 0x3000, 64, 64, 0, 0, 64, 0)
     L = rl.lib()

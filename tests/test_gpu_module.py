@@ -183,3 +183,37 @@ def test_block_timing_script_runs_the_same_block_three_ways(model, capsys):
     assert out["rel_diff_vs_default"] < 2e-2 and out["rel_diff_vs_torch"] < 2e-2
     assert len(out["pairs"]) == (7 if model == "llama7b" else 6)
     assert json.loads(capsys.readouterr().out.strip().splitlines()[-1])["model"] == model
+
+
+def test_vera_module_matches_oracle_and_shares_frozen_factors():
+    """RunVeRALinear through autograd: output and the gradients of x, d and b against the oracle's VeRA
+    layer; A and B are buffers, not parameters, and two layers may hold the same tensors."""
+    import torch
+    from paper_2312_03415_amd.module import RunVeRALinear
+    n, d_in, d_out, r = 150, 136, 264, 64
+    L = synth.Layer("veramod", n, d_in, d_out, r, "bf16", 51)
+    st = synth.layer_inputs(L)
+    host = {k: synth.widen(v, "bf16") for k, v in st.items()}
+    dvec = synth.store(synth.normal(51, 10, (r,)), "bf16")
+    bvec = synth.store(synth.normal(51, 11, (d_out,)), "bf16")
+    A, B = to_device(st["A"], "bf16"), to_device(st["B"], "bf16")
+    layer = RunVeRALinear(to_device(st["W"], "bf16"), A, B, scale=0.5)
+    other = RunVeRALinear(to_device(st["W"], "bf16"), A, B)
+    assert other.vera_A.data_ptr() == layer.vera_A.data_ptr()
+    assert sorted(k for k, p in layer.named_parameters() if p.requires_grad) == ["vera_b", "vera_d"]
+    with torch.no_grad():
+        layer.vera_d.copy_(to_device(dvec, "bf16"))
+        layer.vera_b.copy_(to_device(bvec, "bf16"))
+    x = to_device(st["X"], "bf16").view(3, 50, d_in).requires_grad_(True)
+    y = layer(x)
+    y.backward(to_device(st["dY"], "bf16").view(3, 50, d_out))
+    torch.cuda.synchronize()
+    d64, b64 = synth.widen(dvec, "bf16"), synth.widen(bvec, "bf16")
+    Yw = oracle.vera_forward(host["X"], host["W"], host["A"], host["B"], d64, b64, 0.5)
+    dXw, ddw, dbw = oracle.vera_backward(host["X"], host["W"], host["A"], host["B"], d64, b64, host["dY"], 0.5)
+    assert relerr(to_f64(y.reshape(-1, d_out)), Yw) < TOL["bf16"]
+    assert relerr(to_f64(x.grad.reshape(-1, d_in)), dXw) < TOL["bf16"]
+    assert relerr(to_f64(layer.vera_d.grad), ddw) < TOL["bf16"] and relerr(to_f64(layer.vera_b.grad), dbw) < TOL["bf16"]
+    # a fresh layer (b = 0) is the frozen linear layer
+    y0 = other(x.detach())
+    assert relerr(to_f64(y0.reshape(-1, d_out)), host["X"] @ host["W"]) < TOL["bf16"]
