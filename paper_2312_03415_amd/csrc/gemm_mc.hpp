@@ -324,19 +324,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   // Move the cursor on.  Past the last work item it stays on the last tile, which is then fetched
   // again (into a stage nobody reads), so that the number of loads in flight, which the waits below
   // count, never changes.
-  auto cursor_advance = [&]() {
-    if (!clive) return;
-    ++cu;
-    if (cu != cnext) {
-      kA += stepA;
-      kB += stepB;
-      if constexpr (BQ) {
-        ++cts;
-        kBq = __builtin_amdgcn_readfirstlane(kBq + stepBq);
-        kBs = __builtin_amdgcn_readfirstlane(cq ? (P::B_STR ? (uint32_t)(cts >> 1) * ldbs2 : (uint32_t)cts * (2u * BK)) : kBq);
-      }
-      return;
-    }
+  auto cursor_event = [&]() {  // cu has just reached cnext: next work item, the end of all work, or a rebuild
     if (cu == cu_end) {
       if (cw + (int)gridDim.x < nwork) {
         cw += gridDim.x;
@@ -344,10 +332,37 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
       } else {
         clive = false;
         --cu;
+        kA -= stepA;  // stay on the last tile
+        kB -= stepB;
       }
       return;
     }
     cursor_setup();
+  };
+  auto cursor_advance = [&]() {
+    if constexpr (!BQ) {
+      // straight-line in the common case (next tile of the same run, or nothing left to fetch): the
+      // pointers are bumped unconditionally, an event rebuilds them
+      const bool live = clive;
+      cu += live ? 1 : 0;
+      kA += live ? stepA : 0u;
+      kB += live ? stepB : 0u;
+      if (__builtin_expect(live && cu == cnext, 0)) cursor_event();
+    } else {
+      if (!clive) return;
+      ++cu;
+      if (cu != cnext) {
+        kA += stepA;
+        kB += stepB;
+        ++cts;
+        kBq = __builtin_amdgcn_readfirstlane(kBq + stepBq);
+        kBs = __builtin_amdgcn_readfirstlane(cq ? (P::B_STR ? (uint32_t)(cts >> 1) * ldbs2 : (uint32_t)cts * (2u * BK)) : kBq);
+        return;
+      }
+      kA += stepA;  // (cursor_event undoes this where it matters)
+      kB += stepB;
+      cursor_event();
+    }
   };
 
   // ---- fragment addresses (bytes inside a stage, stage 0) -------------------------------------------
@@ -431,6 +446,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   f32x16 acc[4][4];
 
 #define MC_VMEM_AT(q) (((q) & 3) == 3)
+#define MC_VMEM_EARLY(q) ((q) == 2 || (q) == 5 || (q) == 8 || (q) == 11)
 #define MC_FENCE() __builtin_amdgcn_sched_barrier(0)
   // One K step, in exactly this instruction order (a scheduling fence after every piece): 16 MFMAs out
   // of fragment buffer `bufc`; behind each of the first 8, one fragment of K step KSR of the stage at
@@ -438,7 +454,13 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   // A wave issues at most one instruction per 4 cycles and an MFMA occupies the matrix core for 32, so
   // up to ~7 other instructions fit behind each MFMA; spreading them keeps the matrix core fed, and
   // spreading the loads keeps the four waves from flooding the address unit at the same moment.
-  auto kstep = [&](auto ksr_c, int bufc, int bufr, uint32_t soff, auto issue_one, auto behind) {
+  // sync_c: -1 = none; otherwise MC_SYNC(sync_c) runs behind the first MFMA and the fragment reads follow
+  // from the second on (the stage they read, and the stage the loads refill, are safe only after it).
+  // early_c: loads behind MFMAs 2, 5, 8, 11 instead of 3, 7, 11, 15 (leaves the tail of the step free).
+  auto kstep = [&](auto ksr_c, auto sync_c, auto early_c, int bufc, int bufr, uint32_t soff, auto issue_one, auto behind) {
+    constexpr int SYNC = decltype(sync_c)::value;
+    constexpr bool EARLY = decltype(early_c)::value;
+    constexpr int R0 = SYNC >= 0 ? 1 : 0;
     wait_tr(bufc);
     MC_FENCE();
     int j = 0;
@@ -446,15 +468,24 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
     for (int q = 0; q < 16; ++q) {
       Elem<T>::mma(acc[q >> 2][q & 3], fb[bufc][q & 3], fa[bufc][q >> 2]);
       MC_FENCE();
-      if (q < 4) {
-        fa[bufr][q] = read_frag_op(P::A_STR, fragA, soff, q, ksr_c);
+      if constexpr (SYNC >= 0) {
+        if (q == 0) {
+          asm volatile("" ::: "memory");
+          __builtin_amdgcn_s_waitcnt(mc_wait_imm(SYNC, true));
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");
+          MC_FENCE();
+        }
+      }
+      if (q >= R0 && q < R0 + 4) {
+        fa[bufr][q - R0] = read_frag_op(P::A_STR, fragA, soff, q - R0, ksr_c);
         MC_FENCE();
-      } else if (q < 8) {
-        fb[bufr][q - 4] = read_frag_op(P::B_STR, fragB, soff, q - 4, ksr_c);
+      } else if (q >= R0 + 4 && q < R0 + 8) {
+        fb[bufr][q - R0 - 4] = read_frag_op(P::B_STR, fragB, soff, q - R0 - 4, ksr_c);
         MC_FENCE();
       }
-      behind(q);  // further work placed behind MFMA q (the int4 route's dequantisation)
-      if (MC_VMEM_AT(q)) {
+      behind(q);  // further work placed behind MFMA q (the int4 route's dequantisation, the cursor's step)
+      if (EARLY ? MC_VMEM_EARLY(q) : MC_VMEM_AT(q)) {
         issue_one(j++);
         MC_FENCE();
       }
@@ -520,6 +551,8 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) fb[0][b] = read_frag_op(P::B_STR, fragB, 0u, b, K0c{});
   }
+  // the only K tiles that can be partial: the last one of each segment
+  const int pu0 = (K0 % BK) != 0 ? nt0 - 1 : -1, pu1 = (K1 % BK) != 0 ? ntk - 1 : -1;
   int stp = NS - 1;  // stage of the previous tile = where the tile being fetched goes
   int st = 0;  // stage of the tile being multiplied; runs on across work items
 
@@ -535,37 +568,39 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
         for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
     for (int u = u0; u < u1; ++u) {
-      const int kvalid = u < nt0 ? K0 - u * BK : K1 - (u - nt0) * BK;  // >= 32 for a full tile
+      const bool partial = (u == pu0) | (u == pu1);  // wave-uniform, rare
       const int stn = (st + 1 == NS) ? 0 : st + 1;
-      if (kvalid < BK) {  // partial tile (wave-uniform): zero what lies beyond K
+      int kvalid = BK;
+      if (__builtin_expect(partial, 0)) {  // zero what lies beyond K
+        kvalid = u < nt0 ? K0 - u * BK : K1 - (u - nt0) * BK;
         MC_FENCE();
         wait_tr(0);
         mask_frags(0, 0, kvalid);
       }
       // K step 0 out of buffer 0; K step 1's fragments go to buffer 1; second half of the fetch
       // that the previous K step began
+      using NoSync = std::integral_constant<int, -1>;
       if constexpr (!BQ) {
-        kstep(std::integral_constant<int, 1>{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES), [&](int j) { issue_B1(stp, j); }, nothing);
+        // the cursor moves on behind MFMA 12, after the last of this step's loads (which belong to its tile)
+        kstep(std::integral_constant<int, 1>{}, NoSync{}, std::true_type{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES),
+              [&](int j) { issue_B1(stp, j); }, [&](int q) { if (q == 12) { cursor_advance(); MC_FENCE(); } });
       } else {
         // int4 route: behind MFMA q, value q % 8 of slot 2 + q / 8 of the next tile's B (fetched during
         // the previous tile) is dequantised; a completed slot goes to the next tile's stage and its
         // registers are refilled with the B half of the cursor's tile.
-        kstep(std::integral_constant<int, 1>{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES),
+        kstep(std::integral_constant<int, 1>{}, NoSync{}, std::false_type{}, 0, 1, (uint32_t)(st * P::STAGE_BYTES),
               [&](int j) { if (j & 1) load_B(2 + (j >> 1)); },
               [&](int q) { commit_B(stn, 2 + (q >> 3), q & 7, q23); MC_FENCE(); });
         q23 = cq;
+        cursor_advance();
       }
-      cursor_advance();
       // Tile u+1 must have landed (own loads, then everyone's: loads return in order, so "at most
       // (NS-2) tiles' worth outstanding" means tile u+1 is in), and everyone must be done reading
       // stage st before it is refilled.  (Int4 route: the loads issued after the last A load of tile
       // u+1 are 2 + 4 + 8 + 4: see K step 1 below.)
-      if constexpr (!BQ) {
-        MC_SYNC((NS - 2) * P::LPT);
-      } else {
-        MC_SYNC(18);
-      }
-      if (kvalid < BK) {
+      // The wait and the barrier run behind the first MFMA of K step 1 (which only needs registers).
+      if (__builtin_expect(partial, 0)) {
+        MC_FENCE();
         wait_tr(1);
         mask_frags(1, 1, kvalid);
         MC_FENCE();
@@ -573,12 +608,13 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
       // K step 1 out of buffer 1, with the next tile's first fragments and the first half of the
       // refill of stage st
       if constexpr (!BQ) {
-        kstep(std::integral_constant<int, 0>{}, 1, 0, (uint32_t)(stn * P::STAGE_BYTES), [&](int j) { issue_A1(st, j); }, nothing);
+        kstep(std::integral_constant<int, 0>{}, std::integral_constant<int, (NS - 2) * P::LPT>{}, std::false_type{}, 1, 0,
+              (uint32_t)(stn * P::STAGE_BYTES), [&](int j) { issue_A1(st, j); }, nothing);
       } else {
         // int4 route: slots 0,1 of the tile after the next one (the cursor has moved on) likewise; their
         // loads follow the A loads at MFMA 7 and 15
-        kstep(std::integral_constant<int, 0>{}, 1, 0, (uint32_t)(stn * P::STAGE_BYTES),
-              [&](int j) { issue_A1(st, j); if (j & 1) load_B(j >> 1); },
+        kstep(std::integral_constant<int, 0>{}, std::integral_constant<int, 18>{}, std::false_type{}, 1, 0,
+              (uint32_t)(stn * P::STAGE_BYTES), [&](int j) { issue_A1(st, j); if (j & 1) load_B(j >> 1); },
               [&](int q) { commit_B(stp, q >> 3, q & 7, q01); MC_FENCE(); });
         q01 = cq;
       }

@@ -51,8 +51,10 @@ def test_k_loop_of_the_matrix_core_kernel(asm, al, bl, ns, bq):
     meta = asm[asm.index(".name:           " + name):]
     meta = meta[:meta.index(".wavefront_size")]
     assert re.search(r"\.vgpr_spill_count:\s+0\b", meta), "the kernel spills vector registers"
-    ksteps = [b for b in blocks(text) if sum(i.startswith("v_mfma") for i in b) >= 16]
-    assert len(ksteps) >= 2, "expected both K steps of a tile as straight-line blocks of 16 MFMAs"
+    # the two K steps of a tile: straight-line runs of MFMAs (the cursor's rare-event branch may cut one in two)
+    ksteps = [b for b in blocks(text) if sum(i.startswith("v_mfma") for i in b) >= 3]
+    assert sum(sum(i.startswith("v_mfma") for i in b) for b in ksteps) >= 32, "expected the 32 MFMAs of a K tile in a few straight-line blocks"
+    assert len(ksteps) <= 4 * (2 if bq else 1), "the K steps are cut into many blocks: branches between the MFMAs"
     for b in ksteps:
         first = next(k for k, i in enumerate(b) if i.startswith("v_mfma"))
         last = max(k for k, i in enumerate(b) if i.startswith("v_mfma"))
