@@ -54,6 +54,38 @@ constexpr int mc_wait_imm(int vm, bool lgkm_zero) {
   return (vm & 15) | (7 << 4) | ((lgkm_zero ? 0 : 15) << 8) | ((vm >> 4) << 14);
 }
 
+// Epilogue of one 32x32 block for the common case: 16-bit output, no addend, no bias, alpha = 1, no mask, no
+// split, tile completely inside C.  `p` is this lane's address of (row l%32, column 8 (l/32)) of the block.
+// Rounding and lane exchange are those of store_block (same results); what is left out is the per-store
+// bounds and option logic, which costs several times the stores themselves.
+template <typename T>
+__device__ __forceinline__ void store_block_plain(T* p, const f32x16& c) {
+  static_assert(sizeof(T) == 2, "16-bit outputs");
+  // the accumulator registers are read here and not before (an explicit instruction: left to itself the
+  // compiler copies all 256 of them to vector registers ahead of the epilogue and runs out of registers)
+  auto rd = [&](int e) -> float {
+    float x;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(c[e]));
+    return x;
+  };
+#pragma unroll
+  for (int qp = 0; qp < 2; ++qp) {
+    // two values per conversion instruction (round to nearest even, as from_f32 does one at a time)
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef T tx2_t __attribute__((ext_vector_type(2)));
+    auto pack2 = [&](int e) -> unsigned {
+      const f32x2_t f2 = {rd(e), rd(e + 1)};
+      return __builtin_bit_cast(unsigned, __builtin_convertvector(f2, tx2_t));
+    };
+    const unsigned pa[2] = {pack2(8 * qp + 0), pack2(8 * qp + 2)};
+    const unsigned pb[2] = {pack2(8 * qp + 4), pack2(8 * qp + 6)};
+    auto s0 = __builtin_amdgcn_permlane32_swap(pa[0], pb[0], false, false);
+    auto s1 = __builtin_amdgcn_permlane32_swap(pa[1], pb[1], false, false);
+    i32x4 out = {(int)s0[0], (int)s1[0], (int)s0[1], (int)s1[1]};
+    *reinterpret_cast<i32x4*>(p + 16 * qp) = out;
+  }
+}
+
 // The kernel body is a device function (the buffer-descriptor builtins exist only in device code).
 // BQ: B of segment 0 is int4 with fp16 group scales (GemmArgs::Bscale).  The B half of a K tile then
 // does not go to LDS by LDS-DMA: every lane fetches, for each of its four 16-byte LDS slots, the eight
@@ -64,7 +96,9 @@ constexpr int mc_wait_imm(int vm, bool lgkm_zero) {
 // slots per K step.  Everything downstream (swizzle, fragment reads, MFMAs) is unchanged.  The dense
 // second segment of a K-concatenated product takes the same route with its 16 bytes passed through,
 // so that every K tile issues the same number of loads (the waits count them).
-template <typename T, int AL, int BL, int NS, bool BQ = false>
+// PLAIN: the launch has no addend, bias, scale, mask or split and M, N are multiples of the tile, so every
+// tile takes the short epilogue (decided on the host: two epilogues in one kernel cost registers).
+template <typename T, int AL, int BL, int NS, bool BQ = false, bool PLAIN = false>
 __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   using P = McTile<AL, BL, NS>;
   static_assert(!BQ || (NS == 3 && AL == 0), "int4 B: 3-stage ring, A stored [M,K]");
@@ -623,12 +657,24 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
     }
 
     // ---- epilogue (the next work item's first tiles keep arriving meanwhile)
-    Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split, g.alpha, g.bias, g.drop_thr, g.drop_key, g.drop_cpr};
+    if constexpr (PLAIN) {
+      T* const cbase = static_cast<T*>(g.C) + (int64_t)(m0 + wm * 128 + l31) * g.ldc + (n0 + wn * 128 + 8 * hi);
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+      for (int a = 0; a < 4; ++a) {
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
-        store_block<T>(ep, acc[a][b], m0 + wm * 128 + a * 32 + l31, n0 + wn * 128 + b * 32, lane);
+        for (int b = 0; b < 4; ++b) {
+          store_block_plain<T>(cbase + (int64_t)(a * 32) * g.ldc + b * 32, acc[a][b]);
+          __builtin_amdgcn_sched_barrier(0);  // block by block: the accumulators stay where they are until used
+        }
+      }
+    } else {
+      Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split, g.alpha, g.bias, g.drop_thr, g.drop_key, g.drop_cpr};
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          store_block<T>(ep, acc[a][b], m0 + wm * 128 + a * 32 + l31, n0 + wn * 128 + b * 32, lane);
+    }
   }
   // the LDS-DMA writes still in flight target this workgroup's LDS: let them land before it is released
   __builtin_amdgcn_s_waitcnt(mc_wait_imm(0, true));
@@ -637,9 +683,9 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 #undef MC_FENCE
 }
 
-template <typename T, int AL, int BL, int NS, bool BQ = false>
+template <typename T, int AL, int BL, int NS, bool BQ = false, bool PLAIN = false>
 __global__ __launch_bounds__(256, 1) void gemm_mc_kernel(GemmArgs g) {
-  gemm_mc_body<T, AL, BL, NS, BQ>(g);
+  gemm_mc_body<T, AL, BL, NS, BQ, PLAIN>(g);
 }
 
 }  // namespace rl

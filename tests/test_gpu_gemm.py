@@ -140,3 +140,29 @@ def test_streaming_kernel(N, layout, dtype):
     rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, tile_cfg=8)
     torch.cuda.synchronize()
     assert relerr(to_f64(C), want) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("layout", list(LAYOUTS))
+def test_short_epilogue_build_equals_the_general_one(layout, dtype):
+    """When a launch of the matrix-core kernel (tile_cfg 7) has only whole 256x256 tiles and nothing but rounding
+    in its epilogue, a build with a short epilogue runs.  Its output must be bit for bit that of the general
+    build, which an all-zero bias selects (adding +0 changes no value that is not -0), and match the oracle;
+    two tiles per workgroup row and column, several K tiles, ragged last K tile, second segment."""
+    import torch
+    a_str, b_kc = LAYOUTS[layout]
+    M, N, K, K2 = 512, 768, 1048, 24
+    A, Ah = make(5, 1, (K, M) if a_str else (M, K), dtype)
+    B, Bh = make(5, 2, (N, K) if b_kc else (K, N), dtype, 1.0 / K)
+    A2, A2h = make(5, 3, (K2, M) if a_str else (M, K2), dtype)
+    B2, B2h = make(5, 4, (N, K2) if b_kc else (K2, N), dtype, 1.0 / K2)
+    want = oracle.matmul(Ah, Bh, ta=a_str, tb=b_kc) + oracle.matmul(A2h, B2h, ta=a_str, tb=b_kc)
+    td = torch_dtype(dtype)
+    C = torch.full((M, N), float("nan"), dtype=td, device="cuda")
+    Cg = torch.full((M, N), float("nan"), dtype=td, device="cuda")
+    zero_bias = torch.zeros(N, dtype=td, device="cuda")
+    rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, A2=A2, B2=B2, tile_cfg=7, splits=1)
+    rl.runlora_gemm(A, B, Cg, a_strided=a_str, b_kcontig=b_kc, A2=A2, B2=B2, tile_cfg=7, splits=1, bias=zero_bias)
+    torch.cuda.synchronize()
+    assert relerr(to_f64(C), want) < TOL[dtype]
+    assert torch.equal(C.view(torch.int16), Cg.view(torch.int16))

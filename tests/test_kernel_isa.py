@@ -27,8 +27,8 @@ def asm(tmp_path_factory):
     return out.read_text()
 
 
-def kernel_text(asm, al, bl, ns, bq):
-    name = f"_ZN2rl14gemm_mc_kernelIDF16bLi{al}ELi{bl}ELi{ns}ELb{bq}EEEvNS_8GemmArgsE"
+def kernel_text(asm, al, bl, ns, bq, plain=0):
+    name = f"_ZN2rl14gemm_mc_kernelIDF16bLi{al}ELi{bl}ELi{ns}ELb{bq}ELb{plain}EEEvNS_8GemmArgsE"
     start = asm.index("\n" + name + ":")
     return name, asm[start:asm.index("s_endpgm", start)]
 
@@ -45,9 +45,10 @@ def blocks(text):
     return out
 
 
-@pytest.mark.parametrize("al,bl,ns,bq", [(0, 0, 4, 0), (0, 1, 4, 0), (1, 0, 4, 0), (0, 0, 3, 1), (0, 1, 3, 1)])
-def test_k_loop_of_the_matrix_core_kernel(asm, al, bl, ns, bq):
-    name, text = kernel_text(asm, al, bl, ns, bq)
+@pytest.mark.parametrize("al,bl,ns,bq,plain", [(0, 0, 4, 0, 0), (0, 1, 4, 0, 0), (1, 0, 4, 0, 0), (0, 0, 3, 1, 0), (0, 1, 3, 1, 0),
+                                                (0, 0, 4, 0, 1), (0, 1, 4, 0, 1), (1, 0, 4, 0, 1)])
+def test_k_loop_of_the_matrix_core_kernel(asm, al, bl, ns, bq, plain):
+    name, text = kernel_text(asm, al, bl, ns, bq, plain)
     meta = asm[asm.index(".name:           " + name):]
     meta = meta[:meta.index(".wavefront_size")]
     assert re.search(r"\.vgpr_spill_count:\s+0\b", meta), "the kernel spills vector registers"
