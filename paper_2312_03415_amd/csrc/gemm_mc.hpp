@@ -54,38 +54,6 @@ constexpr int mc_wait_imm(int vm, bool lgkm_zero) {
   return (vm & 15) | (7 << 4) | ((lgkm_zero ? 0 : 15) << 8) | ((vm >> 4) << 14);
 }
 
-// Epilogue of one 32x32 block for the common case: 16-bit output, no addend, no bias, alpha = 1, no mask, no
-// split, tile completely inside C.  `p` is this lane's address of (row l%32, column 8 (l/32)) of the block.
-// Rounding and lane exchange are those of store_block (same results); what is left out is the per-store
-// bounds and option logic, which costs several times the stores themselves.
-template <typename T>
-__device__ __forceinline__ void store_block_plain(T* p, const f32x16& c) {
-  static_assert(sizeof(T) == 2, "16-bit outputs");
-  // the accumulator registers are read here and not before (an explicit instruction: left to itself the
-  // compiler copies all 256 of them to vector registers ahead of the epilogue and runs out of registers)
-  auto rd = [&](int e) -> float {
-    float x;
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(c[e]));
-    return x;
-  };
-#pragma unroll
-  for (int qp = 0; qp < 2; ++qp) {
-    // two values per conversion instruction (round to nearest even, as from_f32 does one at a time)
-    typedef float f32x2_t __attribute__((ext_vector_type(2)));
-    typedef T tx2_t __attribute__((ext_vector_type(2)));
-    auto pack2 = [&](int e) -> unsigned {
-      const f32x2_t f2 = {rd(e), rd(e + 1)};
-      return __builtin_bit_cast(unsigned, __builtin_convertvector(f2, tx2_t));
-    };
-    const unsigned pa[2] = {pack2(8 * qp + 0), pack2(8 * qp + 2)};
-    const unsigned pb[2] = {pack2(8 * qp + 4), pack2(8 * qp + 6)};
-    auto s0 = __builtin_amdgcn_permlane32_swap(pa[0], pb[0], false, false);
-    auto s1 = __builtin_amdgcn_permlane32_swap(pa[1], pb[1], false, false);
-    i32x4 out = {(int)s0[0], (int)s1[0], (int)s0[1], (int)s1[1]};
-    *reinterpret_cast<i32x4*>(p + 16 * qp) = out;
-  }
-}
-
 // The kernel body is a device function (the buffer-descriptor builtins exist only in device code).
 // BQ: B of segment 0 is int4 with fp16 group scales (GemmArgs::Bscale).  The B half of a K tile then
 // does not go to LDS by LDS-DMA: every lane fetches, for each of its four 16-byte LDS slots, the eight
@@ -97,7 +65,8 @@ __device__ __forceinline__ void store_block_plain(T* p, const f32x16& c) {
 // second segment of a K-concatenated product takes the same route with its 16 bytes passed through,
 // so that every K tile issues the same number of loads (the waits count them).
 // PLAIN: the launch has no addend, bias, scale, mask or split and M, N are multiples of the tile, so every
-// tile takes the short epilogue (decided on the host: two epilogues in one kernel cost registers).
+// tile takes the short epilogue (decided on the host: two epilogues in one kernel cost registers).  That
+// epilogue needs 32 KB of LDS behind the ring (8 KB per wave).
 template <typename T, int AL, int BL, int NS, bool BQ = false, bool PLAIN = false>
 __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   using P = McTile<AL, BL, NS>;
@@ -658,13 +627,48 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 
     // ---- epilogue (the next work item's first tiles keep arriving meanwhile)
     if constexpr (PLAIN) {
-      T* const cbase = static_cast<T*>(g.C) + (int64_t)(m0 + wm * 128 + l31) * g.ldc + (n0 + wn * 128 + 8 * hi);
+      // Row-contiguous stores: a wave store instruction that covers whole 128-byte lines costs a quarter of one
+      // that writes 32 bytes to each of 32 rows.  Each block row (32 rows x 128 columns of this wave) goes through
+      // a private 8 KB LDS area: 8-byte pieces in the accumulator layout in, 16-byte pieces of 4 rows x 256 bytes out.
+      unsigned char* const stg = smem + P::LDS_BYTES + wave * 8192;
+      const uint32_t stg_base = (uint32_t)(uintptr_t)((mc_lds_void_t*)stg);
+      const uint32_t wr = stg_base + (uint32_t)l31 * 256u;   // this lane's row in the area
+      const uint32_t wsw = 2u * (uint32_t)(l31 & 15);        // its rotation of the 8-byte slots (even: pairs stay together)
+      const int rr = lane >> 4, rc = lane & 15;              // read side: row within a group of 4, 16-byte chunk
+      T* gp = static_cast<T*>(g.C) + (int64_t)(m0 + wm * 128 + rr) * g.ldc + (n0 + wn * 128 + rc * 8);
+      typedef float f32x2_t __attribute__((ext_vector_type(2)));
+      typedef T tx2_t __attribute__((ext_vector_type(2)));
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-          store_block_plain<T>(cbase + (int64_t)(a * 32) * g.ldc + b * 32, acc[a][b]);
-          __builtin_amdgcn_sched_barrier(0);  // block by block: the accumulators stay where they are until used
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            // explicit reads at the point of use: left to itself the compiler copies all 256 accumulator
+            // registers to vector registers ahead of the epilogue and runs out of registers
+            float x0, x1, x2, x3;
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x0) : "a"(acc[a][b][4 * q + 0]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x1) : "a"(acc[a][b][4 * q + 1]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x2) : "a"(acc[a][b][4 * q + 2]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x3) : "a"(acc[a][b][4 * q + 3]));
+            const f32x2_t lo = {x0, x1}, hi2 = {x2, x3};
+            i32x2 v = {(int)__builtin_bit_cast(unsigned, __builtin_convertvector(lo, tx2_t)),
+                       (int)__builtin_bit_cast(unsigned, __builtin_convertvector(hi2, tx2_t))};
+            const uint32_t slot = ((uint32_t)(8 * b + 2 * q) ^ wsw) + (uint32_t)hi;  // columns 32 b + 8 q + 4 hi .. + 3
+            asm volatile("ds_write_b64 %0, %1" : : "v"(wr + slot * 8u), "v"(v) : "memory");
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int row = 4 * k + rr;
+          const uint32_t addr = stg_base + (uint32_t)row * 256u + (((uint32_t)(2 * rc) ^ (2u * (uint32_t)(row & 15))) * 8u);
+          i32x4 o;
+          asm volatile("ds_read_b128 %0, %1" : "=v"(o) : "v"(addr) : "memory");
+          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o));
+          *reinterpret_cast<i32x4*>(gp + (int64_t)(a * 32 + 4 * k) * g.ldc) = o;
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     } else {

@@ -46,7 +46,7 @@ def blocks(text):
 
 
 @pytest.mark.parametrize("al,bl,ns,bq,plain", [(0, 0, 4, 0, 0), (0, 1, 4, 0, 0), (1, 0, 4, 0, 0), (0, 0, 3, 1, 0), (0, 1, 3, 1, 0),
-                                                (0, 0, 4, 0, 1), (0, 1, 4, 0, 1), (1, 0, 4, 0, 1)])
+                                                (0, 0, 3, 0, 1), (0, 1, 3, 0, 1), (1, 0, 3, 0, 1)])
 def test_k_loop_of_the_matrix_core_kernel(asm, al, bl, ns, bq, plain):
     name, text = kernel_text(asm, al, bl, ns, bq, plain)
     meta = asm[asm.index(".name:           " + name):]
