@@ -660,14 +660,28 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
           }
         }
         __builtin_amdgcn_sched_barrier(0);
+        // all eight reads first, then each store as soon as its piece has arrived (LDS operations return in order)
+        i32x4 o[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const int row = 4 * k + rr;
           const uint32_t addr = stg_base + (uint32_t)row * 256u + (((uint32_t)(2 * rc) ^ (2u * (uint32_t)(row & 15))) * 8u);
-          i32x4 o;
-          asm volatile("ds_read_b128 %0, %1" : "=v"(o) : "v"(addr) : "memory");
-          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o));
-          *reinterpret_cast<i32x4*>(gp + (int64_t)(a * 32 + 4 * k) * g.ldc) = o;
+          asm volatile("ds_read_b128 %0, %1" : "=v"(o[k]) : "v"(addr) : "memory");
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          switch (k) {  // the count is an immediate
+            case 0: asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(o[0])); break;
+            case 1: asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(o[1])); break;
+            case 2: asm volatile("s_waitcnt lgkmcnt(5)" : "+v"(o[2])); break;
+            case 3: asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(o[3])); break;
+            case 4: asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(o[4])); break;
+            case 5: asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(o[5])); break;
+            case 6: asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(o[6])); break;
+            default: asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o[7])); break;
+          }
+          *reinterpret_cast<i32x4*>(gp + (int64_t)(a * 32 + 4 * k) * g.ldc) = o[k];
           __builtin_amdgcn_sched_barrier(0);
         }
       }
