@@ -64,10 +64,12 @@ constexpr int mc_wait_imm(int vm, bool lgkm_zero) {
 // slots per K step.  Everything downstream (swizzle, fragment reads, MFMAs) is unchanged.  The dense
 // second segment of a K-concatenated product takes the same route with its 16 bytes passed through,
 // so that every K tile issues the same number of loads (the waits count them).
-// PLAIN: the launch has no addend, bias, scale, mask or split and M, N are multiples of the tile, so every
-// tile takes the short epilogue (decided on the host: two epilogues in one kernel cost registers).  That
-// epilogue needs 32 KB of LDS behind the ring (8 KB per wave).
-template <typename T, int AL, int BL, int NS, bool BQ = false, bool PLAIN = false>
+// PLAIN (decided on the host: two epilogues in one kernel cost registers): M and N are multiples of the tile and
+//   1: the launch has no addend, bias, scale, mask or split: every tile takes the short 16-bit epilogue, which
+//      needs 32 KB of LDS behind the ring (8 KB per wave);
+//   2: the launch is a split contraction: every tile writes fp32 partials, 64 KB of LDS behind the ring.
+// Both store whole row segments (see the epilogue).
+template <typename T, int AL, int BL, int NS, bool BQ = false, int PLAIN = 0>
 __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   using P = McTile<AL, BL, NS>;
   static_assert(!BQ || (NS == 3 && AL == 0), "int4 B: 3-stage ring, A stored [M,K]");
@@ -626,7 +628,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
     }
 
     // ---- epilogue (the next work item's first tiles keep arriving meanwhile)
-    if constexpr (PLAIN) {
+    if constexpr (PLAIN == 1) {
       // Row-contiguous stores: a wave store instruction that covers whole 128-byte lines costs a quarter of one
       // that writes 32 bytes to each of 32 rows.  Each block row (32 rows x 128 columns of this wave) goes through
       // a private 8 KB LDS area: 8-byte pieces in the accumulator layout in, 16-byte pieces of 4 rows x 256 bytes out.
@@ -685,6 +687,60 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
+    } else if constexpr (PLAIN == 2) {
+      // fp32 partials of a split contraction, row-contiguous like the 16-bit case: each block row (32 rows x 128
+      // fp32 columns of this wave = 16 KB) passes through LDS; 16-byte pieces in the accumulator layout in, two
+      // rows x 512 bytes per store instruction out.
+      unsigned char* const stg = smem + P::LDS_BYTES + wave * 16384;
+      const uint32_t stg_base = (uint32_t)(uintptr_t)((mc_lds_void_t*)stg);
+      const uint32_t wr = stg_base + (uint32_t)l31 * 512u;
+      const uint32_t wsw = (uint32_t)l31;                   // rotation of the 16-byte slots of this lane's row
+      const int rr = lane >> 5, rc = lane & 31;              // read side: row within a pair, 16-byte chunk
+      float* gp = g.partial + ((int64_t)split * g.M + (m0 + wm * 128 + rr)) * g.N + (n0 + wn * 128 + rc * 4);
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float x0, x1, x2, x3;  // explicit reads at the point of use, as above
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x0) : "a"(acc[a][b][4 * q + 0]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x1) : "a"(acc[a][b][4 * q + 1]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x2) : "a"(acc[a][b][4 * q + 2]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x3) : "a"(acc[a][b][4 * q + 3]));
+            const f32x4 v = {x0, x1, x2, x3};
+            const uint32_t slot = (uint32_t)(8 * b + 2 * q + hi) ^ wsw;  // columns 32 b + 8 q + 4 hi .. + 3
+            asm volatile("ds_write_b128 %0, %1" : : "v"(wr + slot * 16u), "v"(v) : "memory");
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          f32x4 o[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const int row = 2 * (8 * half + k) + rr;
+            const uint32_t addr = stg_base + (uint32_t)row * 512u + (((uint32_t)rc ^ (uint32_t)(row & 31)) * 16u);
+            asm volatile("ds_read_b128 %0, %1" : "=v"(o[k]) : "v"(addr) : "memory");
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            switch (k) {
+              case 0: asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(o[0])); break;
+              case 1: asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(o[1])); break;
+              case 2: asm volatile("s_waitcnt lgkmcnt(5)" : "+v"(o[2])); break;
+              case 3: asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(o[3])); break;
+              case 4: asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(o[4])); break;
+              case 5: asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(o[5])); break;
+              case 6: asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(o[6])); break;
+              default: asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o[7])); break;
+            }
+            *reinterpret_cast<f32x4*>(gp + (int64_t)(a * 32 + 2 * (8 * half + k)) * g.N) = o[k];
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      }
     } else {
       Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split, g.alpha, g.bias, g.drop_thr, g.drop_key, g.drop_cpr};
 #pragma unroll
@@ -701,7 +757,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
 #undef MC_FENCE
 }
 
-template <typename T, int AL, int BL, int NS, bool BQ = false, bool PLAIN = false>
+template <typename T, int AL, int BL, int NS, bool BQ = false, int PLAIN = 0>
 __global__ __launch_bounds__(256, 1) void gemm_mc_kernel(GemmArgs g) {
   gemm_mc_body<T, AL, BL, NS, BQ, PLAIN>(g);
 }

@@ -166,3 +166,29 @@ def test_short_epilogue_build_equals_the_general_one(layout, dtype):
     torch.cuda.synchronize()
     assert relerr(to_f64(C), want) < TOL[dtype]
     assert torch.equal(C.view(torch.int16), Cg.view(torch.int16))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("layout", list(LAYOUTS))
+def test_split_contraction_over_whole_tiles(layout, dtype):
+    """A split contraction whose M and N are multiples of 256 runs the build of the matrix-core kernel that
+    stores its fp32 partials row by row; 2 and 3 slices (the last one shorter and ending in a partial K tile),
+    with and without an addend, scale and bias in the reduce."""
+    import torch
+    a_str, b_kc = LAYOUTS[layout]
+    M, N, K = 512, 768, 2096
+    A, Ah = make(7, 1, (K, M) if a_str else (M, K), dtype)
+    B, Bh = make(7, 2, (N, K) if b_kc else (K, N), dtype, 1.0 / K)
+    D, Dh = make(7, 3, (M, N), dtype)
+    bias, biash = make(7, 4, (N,), dtype)
+    want = oracle.matmul(Ah, Bh, ta=a_str, tb=b_kc)
+    td = torch_dtype(dtype)
+    for splits in (2, 3):
+        C = torch.full((M, N), float("nan"), dtype=td, device="cuda")
+        rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, tile_cfg=7, splits=splits)
+        torch.cuda.synchronize()
+        assert relerr(to_f64(C), want) < TOL[dtype], splits
+        C2 = torch.full((M, N), float("nan"), dtype=td, device="cuda")
+        rl.runlora_gemm(A, B, C2, a_strided=a_str, b_kcontig=b_kc, D=D, tile_cfg=7, splits=splits, alpha=0.5, bias=bias)
+        torch.cuda.synchronize()
+        assert relerr(to_f64(C2), 0.5 * want + Dh + biash[None, :]) < TOL[dtype], splits

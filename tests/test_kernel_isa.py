@@ -28,7 +28,7 @@ def asm(tmp_path_factory):
 
 
 def kernel_text(asm, al, bl, ns, bq, plain=0):
-    name = f"_ZN2rl14gemm_mc_kernelIDF16bLi{al}ELi{bl}ELi{ns}ELb{bq}ELb{plain}EEEvNS_8GemmArgsE"
+    name = f"_ZN2rl14gemm_mc_kernelIDF16bLi{al}ELi{bl}ELi{ns}ELb{bq}ELi{plain}EEEvNS_8GemmArgsE"
     start = asm.index("\n" + name + ":")
     return name, asm[start:asm.index("s_endpgm", start)]
 
@@ -46,7 +46,7 @@ def blocks(text):
 
 
 @pytest.mark.parametrize("al,bl,ns,bq,plain", [(0, 0, 4, 0, 0), (0, 1, 4, 0, 0), (1, 0, 4, 0, 0), (0, 0, 3, 1, 0), (0, 1, 3, 1, 0),
-                                                (0, 0, 3, 0, 1), (0, 1, 3, 0, 1), (1, 0, 3, 0, 1)])
+                                                (0, 0, 3, 0, 1), (0, 1, 3, 0, 1), (1, 0, 3, 0, 1), (0, 1, 3, 0, 2), (0, 0, 3, 1, 1)])
 def test_k_loop_of_the_matrix_core_kernel(asm, al, bl, ns, bq, plain):
     name, text = kernel_text(asm, al, bl, ns, bq, plain)
     meta = asm[asm.index(".name:           " + name):]
