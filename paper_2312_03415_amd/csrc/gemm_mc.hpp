@@ -67,8 +67,9 @@ constexpr int mc_wait_imm(int vm, bool lgkm_zero) {
 // PLAIN (decided on the host: two epilogues in one kernel cost registers): M and N are multiples of the tile and
 //   1: the launch has no addend, bias, scale, mask or split: every tile takes the short 16-bit epilogue, which
 //      needs 32 KB of LDS behind the ring (8 KB per wave);
-//   2: the launch is a split contraction: every tile writes fp32 partials, 64 KB of LDS behind the ring.
-// Both store whole row segments (see the epilogue).
+//   2: the launch is a split contraction: every tile writes fp32 partials, 64 KB of LDS behind the ring;
+//   0: everything else (general epilogue), 64 KB behind the ring as well.
+// All three store whole row segments (see the epilogue).
 template <typename T, int AL, int BL, int NS, bool BQ = false, int PLAIN = 0>
 __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
   using P = McTile<AL, BL, NS>;
@@ -742,12 +743,86 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
         }
       }
     } else {
-      Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split, g.alpha, g.bias, g.drop_thr, g.drop_key, g.drop_cpr};
+      // General epilogue (ragged tiles, addend, bias, scale, mask, or partials of a ragged split): the fp32 block row
+      // passes through the same 16 KB LDS area as above and comes back as rows; a lane then owns four consecutive
+      // columns of one row, which is the unit of every option (one mask group, 8 bytes of addend / bias / output),
+      // and a store instruction covers 2 rows x 256 bytes (512 of partials).  Arithmetic and its order are
+      // store_block's: alpha, mask, + addend, + bias, one rounding.
+      const Epilogue ep{g.C, g.ldc, g.D, g.ldd, g.partial, g.M, g.N, split, g.alpha, g.bias, g.drop_thr, g.drop_key, g.drop_cpr};
+      unsigned char* const stg = smem + P::LDS_BYTES + wave * 16384;
+      const uint32_t stg_base = (uint32_t)(uintptr_t)((mc_lds_void_t*)stg);
+      const uint32_t wr = stg_base + (uint32_t)l31 * 512u;
+      const uint32_t wsw = (uint32_t)l31;
+      const int rr = lane >> 5, rc = lane & 31;
+      const int n = n0 + wn * 128 + rc * 4;   // this lane's four columns (N is a multiple of 8: valid together)
+      const bool n_ok = n < g.N;
+      f32x4 bias4 = {0.f, 0.f, 0.f, 0.f};
+      if (g.bias != nullptr && g.partial == nullptr && n_ok) {
+        T b4[4];
+        *reinterpret_cast<i32x2*>(b4) = *reinterpret_cast<const i32x2*>(static_cast<const T*>(g.bias) + n);
 #pragma unroll
-      for (int a = 0; a < 4; ++a)
+        for (int e = 0; e < 4; ++e) bias4[e] = (float)b4[e];
+      }
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-          store_block<T>(ep, acc[a][b], m0 + wm * 128 + a * 32 + l31, n0 + wn * 128 + b * 32, lane);
+      for (int a = 0; a < 4; ++a) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float x0, x1, x2, x3;
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x0) : "a"(acc[a][b][4 * q + 0]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x1) : "a"(acc[a][b][4 * q + 1]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x2) : "a"(acc[a][b][4 * q + 2]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x3) : "a"(acc[a][b][4 * q + 3]));
+            const f32x4 v = {x0, x1, x2, x3};
+            const uint32_t slot = (uint32_t)(8 * b + 2 * q + hi) ^ wsw;
+            asm volatile("ds_write_b128 %0, %1" : : "v"(wr + slot * 16u), "v"(v) : "memory");
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          f32x4 o[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const int row = 2 * (8 * half + k) + rr;
+            const uint32_t addr = stg_base + (uint32_t)row * 512u + (((uint32_t)rc ^ (uint32_t)(row & 31)) * 16u);
+            asm volatile("ds_read_b128 %0, %1" : "=v"(o[k]) : "v"(addr) : "memory");
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            switch (k) {
+              case 0: asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(o[0])); break;
+              case 1: asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(o[1])); break;
+              case 2: asm volatile("s_waitcnt lgkmcnt(5)" : "+v"(o[2])); break;
+              case 3: asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(o[3])); break;
+              case 4: asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(o[4])); break;
+              case 5: asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(o[5])); break;
+              case 6: asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(o[6])); break;
+              default: asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o[7])); break;
+            }
+            const int m = m0 + wm * 128 + a * 32 + 2 * (8 * half + k) + rr;
+            if (m < g.M && n_ok) {
+              if (g.partial != nullptr) {
+                *reinterpret_cast<f32x4*>(g.partial + ((int64_t)split * g.M + m) * g.N + n) = o[k];
+              } else {
+                f32x4 v = epilogue_scale(ep, o[k], m, n);
+                if (g.D != nullptr) {
+                  T d4[4];
+                  *reinterpret_cast<i32x2*>(d4) = *reinterpret_cast<const i32x2*>(static_cast<const T*>(g.D) + (int64_t)m * g.ldd + n);
+#pragma unroll
+                  for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
+                }
+                if (g.bias != nullptr) v += bias4;
+                T o4[4] = {from_f32<T>(v[0]), from_f32<T>(v[1]), from_f32<T>(v[2]), from_f32<T>(v[3])};
+                *reinterpret_cast<i32x2*>(static_cast<T*>(g.C) + (int64_t)m * g.ldc + n) = *reinterpret_cast<const i32x2*>(o4);
+              }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      }
     }
   }
   // the LDS-DMA writes still in flight target this workgroup's LDS: let them land before it is released

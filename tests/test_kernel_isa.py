@@ -45,7 +45,7 @@ def blocks(text):
     return out
 
 
-@pytest.mark.parametrize("al,bl,ns,bq,plain", [(0, 0, 4, 0, 0), (0, 1, 4, 0, 0), (1, 0, 4, 0, 0), (0, 0, 3, 1, 0), (0, 1, 3, 1, 0),
+@pytest.mark.parametrize("al,bl,ns,bq,plain", [(0, 0, 3, 0, 0), (0, 1, 3, 0, 0), (1, 0, 3, 0, 0), (0, 0, 3, 1, 0), (0, 1, 3, 1, 0),
                                                 (0, 0, 3, 0, 1), (0, 1, 3, 0, 1), (1, 0, 3, 0, 1), (0, 1, 3, 0, 2), (0, 0, 3, 1, 1)])
 def test_k_loop_of_the_matrix_core_kernel(asm, al, bl, ns, bq, plain):
     name, text = kernel_text(asm, al, bl, ns, bq, plain)
