@@ -280,11 +280,11 @@ size_t runlora_workspace_bytes_w(int fwd, int bwd, int64_t n, int64_t i, int64_t
  *   K2 = 0     no second segment.   D = NULL: no addend (D may alias C).
  *   tile_cfg   -1 = library heuristic; 0..5 = 256x256, 128x128, 128x32, 128x64, 32x128, 64x128
  *              output tile per workgroup in the generic engine; 6 / 7 = the matrix-core kernel for
- *              the large contractions (256x256 tile, K tile 32, 4 wavefronts, LDS ring of 3 / 4
- *              stages filled by LDS-DMA loads; 16-bit types, fp32 falls back to 0; with 7, a call
- *              whose M and N are multiples of 256 and that has no addend, bias, alpha or -- apart
- *              from a split contraction -- anything else in its epilogue runs a build with a short,
- *              row-contiguous epilogue on a 3-stage ring: same results); 8 = the
+ *              the large contractions (256x256 tile, K tile 32, 4 wavefronts, LDS ring of 3
+ *              stages filled by LDS-DMA loads, epilogue staged through LDS so that whole row
+ *              segments are stored; 16-bit types, fp32 falls back to 0; 6 and 7 differ only in
+ *              that 7 picks a build with a shorter epilogue for a call whose M and N are multiples
+ *              of 256 and that has no addend, bias or alpha: same results); 8 = the
  *              streaming kernel for rank-r products (N <= 128, no second segment, no addend:
  *              4 wavefronts per 32 output rows split the contraction)
  *   trans_out  1 = store C transposed, as [N,M] with ldc >= M (streaming kernel only); else 0
