@@ -54,6 +54,22 @@ constexpr int mc_wait_imm(int vm, bool lgkm_zero) {
   return (vm & 15) | (7 << 4) | ((lgkm_zero ? 0 : 15) << 8) | ((vm >> 4) << 14);
 }
 
+// Piece k of eight LDS reads issued back to back has arrived (LDS operations return in order; the count of
+// s_waitcnt is an immediate, hence the switch, which unrolling resolves).
+template <typename V>
+__device__ __forceinline__ void mc_wait_piece(int k, V (&o)[8]) {
+  switch (k) {
+    case 0: asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(o[0])); break;
+    case 1: asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(o[1])); break;
+    case 2: asm volatile("s_waitcnt lgkmcnt(5)" : "+v"(o[2])); break;
+    case 3: asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(o[3])); break;
+    case 4: asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(o[4])); break;
+    case 5: asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(o[5])); break;
+    case 6: asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(o[6])); break;
+    default: asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o[7])); break;
+  }
+}
+
 // The kernel body is a device function (the buffer-descriptor builtins exist only in device code).
 // BQ: B of segment 0 is int4 with fp16 group scales (GemmArgs::Bscale).  The B half of a K tile then
 // does not go to LDS by LDS-DMA: every lane fetches, for each of its four 16-byte LDS slots, the eight
@@ -674,16 +690,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          switch (k) {  // the count is an immediate
-            case 0: asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(o[0])); break;
-            case 1: asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(o[1])); break;
-            case 2: asm volatile("s_waitcnt lgkmcnt(5)" : "+v"(o[2])); break;
-            case 3: asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(o[3])); break;
-            case 4: asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(o[4])); break;
-            case 5: asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(o[5])); break;
-            case 6: asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(o[6])); break;
-            default: asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o[7])); break;
-          }
+          mc_wait_piece(k, o);
           *reinterpret_cast<i32x4*>(gp + (int64_t)(a * 32 + 4 * k) * g.ldc) = o[k];
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -727,16 +734,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int k = 0; k < 8; ++k) {
-            switch (k) {
-              case 0: asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(o[0])); break;
-              case 1: asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(o[1])); break;
-              case 2: asm volatile("s_waitcnt lgkmcnt(5)" : "+v"(o[2])); break;
-              case 3: asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(o[3])); break;
-              case 4: asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(o[4])); break;
-              case 5: asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(o[5])); break;
-              case 6: asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(o[6])); break;
-              default: asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o[7])); break;
-            }
+            mc_wait_piece(k, o);
             *reinterpret_cast<f32x4*>(gp + (int64_t)(a * 32 + 2 * (8 * half + k)) * g.N) = o[k];
             __builtin_amdgcn_sched_barrier(0);
           }
@@ -792,16 +790,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int k = 0; k < 8; ++k) {
-            switch (k) {
-              case 0: asm volatile("s_waitcnt lgkmcnt(7)" : "+v"(o[0])); break;
-              case 1: asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(o[1])); break;
-              case 2: asm volatile("s_waitcnt lgkmcnt(5)" : "+v"(o[2])); break;
-              case 3: asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(o[3])); break;
-              case 4: asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(o[4])); break;
-              case 5: asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(o[5])); break;
-              case 6: asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(o[6])); break;
-              default: asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o[7])); break;
-            }
+            mc_wait_piece(k, o);
             const int m = m0 + wm * 128 + a * 32 + 2 * (8 * half + k) + rr;
             if (m < g.M && n_ok) {
               if (g.partial != nullptr) {

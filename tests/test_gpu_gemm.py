@@ -19,8 +19,8 @@ SHAPES = {
     3: (300, 56, 200),    # 128x64
     4: (24, 264, 456),    # 32x128
     5: (56, 264, 456),    # 64x128
-    6: (600, 520, 328),   # 256x256, pipelined kernel, 4 wavefronts (fp32 falls back to config 0)
-    7: (600, 520, 328),   # 256x256, pipelined kernel, 8 wavefronts
+    6: (600, 520, 328),   # 256x256, matrix-core kernel (fp32 falls back to config 0)
+    7: (600, 520, 328),   # 256x256, matrix-core kernel, shorter epilogue where the call allows it
 }
 
 
