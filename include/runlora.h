@@ -282,9 +282,10 @@ size_t runlora_workspace_bytes_w(int fwd, int bwd, int64_t n, int64_t i, int64_t
  *              output tile per workgroup in the generic engine; 6 / 7 = the matrix-core kernel for
  *              the large contractions (256x256 tile, K tile 32, 4 wavefronts, LDS ring of 3
  *              stages filled by LDS-DMA loads, epilogue staged through LDS so that whole row
- *              segments are stored; 16-bit types, fp32 falls back to 0; 6 and 7 differ only in
- *              that 7 picks a build with a shorter epilogue for a call whose M and N are multiples
- *              of 256 and that has no addend, bias or alpha: same results); 8 = the
+ *              segments are stored; 16-bit types, fp32 falls back to 0; a call whose M and N are
+ *              multiples of 256 and that has no addend, bias or alpha runs a build with a shorter
+ *              epilogue, same results; 7 once meant a ring of 4 stages, which measured the same,
+ *              and is kept as a second name of 6); 8 = the
  *              streaming kernel for rank-r products (N <= 128, no second segment, no addend:
  *              4 wavefronts per 32 output rows split the contraction)
  *   trans_out  1 = store C transposed, as [N,M] with ldc >= M (streaming kernel only); else 0
