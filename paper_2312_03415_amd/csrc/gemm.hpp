@@ -39,7 +39,7 @@ struct GemmDesc {
 enum TileCfg {
   CFG_BIG = 0, CFG_MID, CFG_TALL32, CFG_TALL64, CFG_WIDE32, CFG_WIDE64,
   CFG_MC3,  // matrix-core kernel (gemm_mc.hpp, 16-bit types): 256x256x32, 4 waves, 3-stage LDS ring
-  CFG_MC4,  // same kernel, 4-stage ring (the one the heuristics pick)
+  CFG_MC4,  // the same kernel (once its 4-stage ring, which measured the same; the id the heuristics pick for dense B)
   CFG_COUNT
 };
 
