@@ -24,7 +24,7 @@ TILE_BM = [256, 128, 128, 128, 32, 64, 256, 256]
 TILE_BN = [256, 128, 32, 64, 128, 128, 256, 256]
 TILE_BK16 = [64, 64, 64, 64, 64, 64, 32, 32]
 WG_PER_CU = [1, 2, 3, 2, 3, 3, 1, 1]
-NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x256x32 matrix-core, 3 stages", "256x256x32 matrix-core, 4 stages"]
+NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x256x32 matrix-core (id 6)", "256x256x32 matrix-core (id 7)"]
 LAYOUTS = {"NN": (0, 0), "NT": (0, 1), "TN": (1, 0)}
 
 
