@@ -105,6 +105,7 @@ struct MergeDesc {
   int64_t ldw = 0, lda = 0, ldb = 0, ldm = 0;
   int64_t I = 0, O = 0, R = 0;
   float alpha = 1.f;  // M = W + alpha A B
+  int b_trans = 0;    // B stored [O, R]
 };
 inline bool merge_ok(int dtype, int64_t r) { return dtype != DT_F32 && r <= 128; }
 hipError_t merge_run(int dtype, const MergeDesc& d, hipStream_t stream);

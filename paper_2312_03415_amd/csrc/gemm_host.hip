@@ -311,6 +311,7 @@ hipError_t merge_run(int dtype, const MergeDesc& d, hipStream_t stream) {
   a.I = (int)d.I; a.O = (int)d.O; a.R = (int)d.R;
   a.blocks_per_wg = 1;
   a.alpha = d.alpha;
+  a.b_trans = d.b_trans;
   return dtype == DT_BF16 ? merge_launch_bf16(a, stream) : merge_launch_f16(a, stream);
 }
 

@@ -787,6 +787,16 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
             const uint32_t addr = stg_base + (uint32_t)row * 512u + (((uint32_t)rc ^ (uint32_t)(row & 31)) * 16u);
             asm volatile("ds_read_b128 %0, %1" : "=v"(o[k]) : "v"(addr) : "memory");
           }
+          // the addend's eight pieces of this half are requested together, ahead of their use (one at a time, every
+          // piece would wait out a trip to memory)
+          i32x2 dq[8];
+          if (g.D != nullptr && g.partial == nullptr) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              const int m = m0 + wm * 128 + a * 32 + 2 * (8 * half + k) + rr;
+              dq[k] = (m < g.M && n_ok) ? *reinterpret_cast<const i32x2*>(static_cast<const T*>(g.D) + (int64_t)m * g.ldd + n) : i32x2{0, 0};
+            }
+          }
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int k = 0; k < 8; ++k) {
@@ -799,7 +809,7 @@ __device__ __forceinline__ void gemm_mc_body(const GemmArgs& g) {
                 f32x4 v = epilogue_scale(ep, o[k], m, n);
                 if (g.D != nullptr) {
                   T d4[4];
-                  *reinterpret_cast<i32x2*>(d4) = *reinterpret_cast<const i32x2*>(static_cast<const T*>(g.D) + (int64_t)m * g.ldd + n);
+                  *reinterpret_cast<i32x2*>(d4) = dq[k];
 #pragma unroll
                   for (int e = 0; e < 4; ++e) v[e] += (float)d4[e];
                 }

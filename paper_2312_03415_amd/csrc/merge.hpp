@@ -1,5 +1,6 @@
 // M = W + alpha A B for the merged-weight graphs (forward2, Eq. 2; Z1 / Z3 of Algorithms 4 and 5 of arxiv
-// 2312.03415): [i,o] = [i,o] + [i,r][r,o] with r <= 128, bf16 / fp16.
+// 2312.03415): [i,o] = [i,o] + [i,r][r,o] with r <= 128, bf16 / fp16.  The default chain's rank-r updates
+// (Y += T B, dX += Z1 A^T: the same operation on [n,o] / [n,i], in place) run here as well.
 //
 // The product is tiny (2 i o r FLOPs); the kernel reads W once and writes M once, so it is bound by
 // HBM bandwidth (2 i o e bytes) and is organised around coalesced 16-byte accesses with many of
@@ -23,6 +24,7 @@ struct MergeArgs {
   int I, O, R;
   int blocks_per_wg;  // 32-row blocks each workgroup walks (gridDim.y covers ceil(I/32) of them)
   float alpha;        // the layer's LoRA scale (1 for the paper's layer)
+  int b_trans;        // 1: B is stored [O, R] (the r values of a column contiguous), as A^T of dX += Z1 A^T is
 };
 
 template <int KSTEPS, int CB>
@@ -58,8 +60,20 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs g) {
   for (int c = lane; c < 16 * KSTEPS * (MT::COLS / 8); c += 64) {
     const int k = c / (MT::COLS / 8), col = (c % (MT::COLS / 8)) * 8;
     i32x4 v = {0, 0, 0, 0};
-    if (k < g.R && n0 + col < g.O) v = *reinterpret_cast<const i32x4*>(Bp + (int64_t)k * g.ldb + n0 + col);
+    if (!g.b_trans && k < g.R && n0 + col < g.O) v = *reinterpret_cast<const i32x4*>(Bp + (int64_t)k * g.ldb + n0 + col);
     *reinterpret_cast<i32x4*>(sB + k * BLD + col) = v;
+  }
+  if (g.b_trans) {  // B stored [O, R]: 16 bytes = eight k of one column, scattered into the [k][COLS] tile (once per workgroup)
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    for (int c = lane; c < MT::COLS * (2 * KSTEPS); c += 64) {
+      const int col = c / (2 * KSTEPS), k8 = (c % (2 * KSTEPS)) * 8;
+      if (n0 + col < g.O && k8 < g.R) {
+        const i32x4 v = *reinterpret_cast<const i32x4*>(Bp + (int64_t)(n0 + col) * g.ldb + k8);
+        const T* e8 = reinterpret_cast<const T*>(&v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sB[(k8 + e) * BLD + col] = e8[e];
+      }
+    }
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's own LDS writes are done (same wave reads them)
   i32x4 fb[CB][KSTEPS];

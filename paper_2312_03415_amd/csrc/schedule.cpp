@@ -35,6 +35,22 @@ struct Builder {
   void gemm(const char* what, int a_strided, int b_kcontig, int64_t M, int64_t N, int64_t K, Mat A, Mat B,
             Mat C, const Mat* D = nullptr, int64_t K2 = 0, const Mat* A2 = nullptr, const Mat* B2 = nullptr,
             bool b_is_w = false, float alpha = 1.f, const void* bias = nullptr, bool mask_out = false) {
+    // A rank-r update of a large matrix (Y += T B, dX += Z1 A^T of the default chain) is the merge kernel's
+    // operation, M = W + alpha A B, on other operands: one pass over the matrix at streaming speed instead of
+    // a tile GEMM whose contraction is a fraction of a K tile.
+    if (D && K2 == 0 && !a_strided && !bias && !(mask_out && L.drop_thr) && !(b_is_w && L.w_int4) && merge_ok(L.dtype, K)) {
+      Step m;
+      m.what = what;
+      m.is_merge = true;
+      m.d.dtype = L.dtype;
+      m.mg.W = D->ptr; m.mg.A = A.ptr; m.mg.B = B.ptr; m.mg.M = const_cast<void*>(C.ptr);
+      m.mg.ldw = D->ld; m.mg.lda = A.ld; m.mg.ldb = B.ld; m.mg.ldm = C.ld;
+      m.mg.I = M; m.mg.O = N; m.mg.R = K;
+      m.mg.alpha = alpha;
+      m.mg.b_trans = b_kcontig;
+      out->steps.push_back(m);
+      return;
+    }
     Step s;
     s.what = what;
     GemmDesc& d = s.d;
