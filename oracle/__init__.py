@@ -264,3 +264,44 @@ def vera_backward(X, W, A, B, d, b, dY, scale=1.0):
     dd = np.sum(T * dU, axis=0)
     dX = matmul(dY, W, tb=True) + matmul(dU * d.reshape(1, -1), A, tb=True)
     return dX, dd, db
+
+
+# ---- DoRA: magnitude / direction decomposition of the adapted weight (named in the paper's conclusion ----
+# as an adapter the method carries over to; the paper gives no formulas, the definition below is the
+# published one written in this file's orientation, Y = XW, output feature j = column j):
+#     V = W + s A B,   c[j] = || V[:, j] ||_2,   Y = X (V diag(m / c)) + 1 bias^T,     m in R^o trainable
+# The published method back-propagates with c held constant (it is detached from the graph), and so do
+# the gradients here.  Step by step through U = X V, Y = U diag(g) + bias, g = m / c:
+#     dm[j] = sum_t dY[t,j] U[t,j] / c[j];   dU = dY diag(g);   dX = dU V^T;
+#     dA = s X^T (dU B^T);   dB = s (X A)^T dU.
+
+def dora_norm(W, A, B, scale=1.0):
+    """c [o]: the column norms of W + s A B."""
+    W, A, B = map(_f64, (W, A, B))
+    V = W + float(scale) * matmul(A, B)
+    return np.sqrt(np.sum(V * V, axis=0))
+
+
+def dora_forward(X, W, A, B, m, scale=1.0, bias=None):
+    X, W, A, B, m = map(_f64, (X, W, A, B, m))
+    V = W + float(scale) * matmul(A, B)
+    c = np.sqrt(np.sum(V * V, axis=0))
+    Y = matmul(X, V) * (m / c).reshape(1, -1)
+    if bias is not None:
+        Y = Y + _f64(bias).reshape(1, -1)
+    return Y
+
+
+def dora_backward(X, W, A, B, m, dY, scale=1.0):
+    """(dX [n,i], dA [i,r], dB [r,o], dm [o]) with the column norm treated as a constant."""
+    X, W, A, B, m, dY = map(_f64, (X, W, A, B, m, dY))
+    s = float(scale)
+    V = W + s * matmul(A, B)
+    c = np.sqrt(np.sum(V * V, axis=0))
+    U = matmul(X, V)
+    dm = np.sum(dY * U, axis=0) / c
+    dU = dY * (m / c).reshape(1, -1)
+    dX = matmul(dU, V, tb=True)
+    dA = s * matmul(X, matmul(dU, B, tb=True), ta=True)
+    dB = s * matmul(matmul(X, A), dU, ta=True)
+    return dX, dA, dB, dm

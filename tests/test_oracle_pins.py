@@ -298,6 +298,74 @@ def test_vera_layer_against_loops_finite_differences_and_lora():
     assert rel(dX0, G @ W.T) < 1e-14 and np.any(dd0 != 0.0) and np.all(db0 == 0.0)
 
 
+def test_dora_layer_against_loops_finite_differences_and_lora():
+    """DoRA, Y = X (V diag(m / c)) + bias with V = W + s A B and c the column norms of V, gradients with c
+    held constant (the published method detaches it): the oracle against the definition written as scalar
+    loops; its gradients against central differences of the layer with c frozen at its value; m = c gives
+    back the LoRA layer; and the layer is Eq. 1 on (W diag(g), A, B diag(g)), g = m / c."""
+    n, i, o, r = 5, 7, 6, 3
+    X, W, A, B, G = draw(n, i, o, r, seed=29)
+    m, bias = 0.5 + np.abs(synth.normal(29, 8, (o,))), synth.normal(29, 9, (o,))
+    s, h = 0.7, 1e-6
+    c = np.zeros(o)
+    for j in range(o):
+        acc = 0.0
+        for q in range(i):
+            v = W[q, j] + s * sum(A[q, k] * B[k, j] for k in range(r))
+            acc += v * v
+        c[j] = acc ** 0.5
+    assert rel(oracle.dora_norm(W, A, B, s), c) < 1e-14
+    Y = oracle.dora_forward(X, W, A, B, m, s, bias)
+    want = np.zeros((n, o))
+    for t in range(n):
+        for j in range(o):
+            u = 0.0
+            for q in range(i):
+                u += X[t, q] * (W[q, j] + s * sum(A[q, k] * B[k, j] for k in range(r)))
+            want[t, j] = u * m[j] / c[j] + bias[j]
+    assert rel(Y, want) < 1e-13
+
+    def loss(X, A, B, m):  # c is a constant of the backward pass
+        return float(np.sum(((X @ (W + s * A @ B)) * (m / c)[None, :] + bias[None, :]) * G))
+
+    def fd(name):
+        base = {"X": X, "A": A, "B": B, "m": m}
+        g = np.zeros_like(base[name])
+        for idx in np.ndindex(*g.shape):
+            pl = {k: v.copy() for k, v in base.items()}
+            mi = {k: v.copy() for k, v in base.items()}
+            pl[name][idx] += h
+            mi[name][idx] -= h
+            g[idx] = (loss(**pl) - loss(**mi)) / (2 * h)
+        return g
+
+    dX, dA, dB, dm = oracle.dora_backward(X, W, A, B, m, G, s)
+    assert dm.shape == (o,)
+    for got, name in ((dX, "X"), (dA, "A"), (dB, "B"), (dm, "m")):
+        assert rel(got, fd(name)) < 1e-7, name
+    # the norm does move with A and B: the full derivative differs from the detached one (a check that the
+    # test above would notice a backward that differentiates through c)
+    def loss_full(A):
+        return float(np.sum(oracle.dora_forward(X, W, A, B, m, s, bias) * G))
+    Ap, Am = A.copy(), A.copy()
+    Ap[0, 0] += h
+    Am[0, 0] -= h
+    assert abs((loss_full(Ap) - loss_full(Am)) / (2 * h) - dA[0, 0]) > 1e-4 * abs(dA[0, 0])
+    # m = c: the plain LoRA layer and its gradients
+    assert rel(oracle.dora_forward(X, W, A, B, c, s, bias), oracle.scaled_forward(X, W, A, B, s, bias)) < 1e-13
+    dXl, dAl, dBl = oracle.scaled_backward(X, W, A, B, G, s)
+    dX1, dA1, dB1, _ = oracle.dora_backward(X, W, A, B, c, G, s)
+    assert rel(dX1, dXl) < 1e-13 and rel(dA1, dAl) < 1e-13 and rel(dB1, dBl) < 1e-13
+    # Eq. 1 on column-scaled operands
+    g = m / c
+    assert rel(Y, oracle.scaled_forward(X, W * g[None, :], A, B * g[None, :], s, bias)) < 1e-13
+    dXs, dAs, dBs = oracle.scaled_backward(X, W * g[None, :], A, B * g[None, :], G, s)
+    assert rel(dX, dXs) < 1e-13 and rel(dA, dAs) < 1e-13 and rel(dB, dBs * g[None, :]) < 1e-13
+    # every output column of the adapted weight has length m[j]
+    Wp = (W + s * A @ B) * g[None, :]
+    assert rel(np.sqrt(np.sum(Wp * Wp, axis=0)), m) < 1e-14
+
+
 # ---- all computation graphs agree ---------------------------------------------------------------
 
 @pytest.mark.parametrize("shape", SHAPES)
