@@ -228,6 +228,38 @@ int runlora_vera_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* 
 size_t runlora_vera_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype);
 
 /*
+ * DoRA on the merged-weight computation graphs.  The paper's conclusion names DoRA among the LoRA variants its
+ * method extends to and gives no formulas; the layer here is the published one in this header's orientation
+ * (output feature j = column j), with the column norm a constant of the backward pass as published:
+ *     V = W + s A B,   c[j] = ||V[:, j]||_2,   g = m / c,   Y = X (V diag(g)) + 1 bias^T,    m [o] trainable
+ *     dX = (dY diag(g)) V^T,   dA = s X^T ((dY diag(g)) B^T),   dB = s (X A)^T (dY diag(g)),
+ *     dm[j] = sum_t dY[t,j] (X V)[t,j] / c[j]  =  sum_t dY[t,j] (Y[t,j] - bias[j]) / m[j].
+ * With c fixed this is the LoRA layer on (W diag(g), A, B diag(g)).  W diag(g) is never formed: only the graphs
+ * in which W enters through W + s A B alone exist (variant = RL_FWD2; RL_BWD4 / 5 / 7 / 8; anything else returns
+ * RL_ERR_UNSUPPORTED), and there the kernel that forms W + s A B scales W's columns on the way.  16-bit dtypes,
+ * r <= 128, no LoRA dropout (otherwise RL_ERR_UNSUPPORTED).  *saved and rl_opts_t mean what they mean for
+ * runlora_forward / runlora_backward (scale, bias, stream; rl_saved_t.M keeps (W + s A B) diag(g), valid while
+ * W, A, B and m are what the forward saw); a forward of one family may not be followed by a backward of another.
+ *   m        device pointer, o elements of the activation dtype, 16-byte aligned; no element may be 0 if dm
+ *            is asked for (dm divides by it; DoRA initialises m to the column norms of W)
+ *   c        device pointer, o floats (fp32 whatever the dtype), 16-byte aligned: written by the forward (the
+ *            column norms, fp32 sums of the unrounded W + s A B in a fixed order), read by the backward.  A
+ *            zero column of W + s A B gives c = 0 and a non-finite g, as the definition does.
+ *   Y        runlora_dora_backward: the forward's output [n,o], unchanged, required only for dm; the bias the
+ *            forward added is taken from opts->bias of the backward call (NULL = none)
+ *   dX, dA, dB, dm   overwritten; any may be NULL (skipped); dm has o elements of the activation dtype
+ *   workspace  required: runlora_dora_workspace_bytes(fwd, bwd, ...) bytes (fwd or bwd < 0: that side only)
+ */
+int runlora_dora_forward(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
+                         const rl_tensor_t* B, const void* m, rl_tensor_t* Y, rl_saved_t* saved, float* c,
+                         const rl_opts_t* opts);
+int runlora_dora_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved, const rl_tensor_t* W,
+                          const rl_tensor_t* A, const rl_tensor_t* B, const void* m, const float* c,
+                          const rl_tensor_t* Y, rl_tensor_t* dX, rl_tensor_t* dA, rl_tensor_t* dB, void* dm,
+                          const rl_opts_t* opts);
+size_t runlora_dora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype);
+
+/*
  * Choose the (forward, backward) pair for one layer shape ("choosing best forward and backward
  * computation graph based on FLOPs and time estimations", abstract).  Pure host function,
  * thread-safe, no HIP call.  Uses the time model unless the environment variable

@@ -35,6 +35,7 @@ EXPORTS = (
     "runlora_version", "runlora_gemm", "runlora_gemm_workspace_bytes",
     "runlora_profile_enable", "runlora_profile_collect", "runlora_profile_disable", "runlora_probe_mfma",
     "runlora_vera_forward", "runlora_vera_backward", "runlora_vera_workspace_bytes",
+    "runlora_dora_forward", "runlora_dora_backward", "runlora_dora_workspace_bytes",
 )
 
 
@@ -111,6 +112,12 @@ def lib():
     L.runlora_vera_backward.restype = ci
     L.runlora_vera_workspace_bytes.argtypes = [ci, ci, i64, i64, i64, i64, ci]
     L.runlora_vera_workspace_bytes.restype = ctypes.c_size_t
+    L.runlora_dora_forward.argtypes = [ci, tp, tp, tp, tp, vp, tp, sp, vp, op]
+    L.runlora_dora_forward.restype = ci
+    L.runlora_dora_backward.argtypes = [ci, tp, sp, tp, tp, tp, vp, vp, tp, tp, tp, tp, vp, op]
+    L.runlora_dora_backward.restype = ci
+    L.runlora_dora_workspace_bytes.argtypes = [ci, ci, i64, i64, i64, i64, ci]
+    L.runlora_dora_workspace_bytes.restype = ctypes.c_size_t
     L.runlora_select.argtypes = [i64, i64, i64, i64, ci, ip, ip]
     L.runlora_select.restype = ci
     L.runlora_select_by.argtypes = [ci, i64, i64, i64, i64, ci, ip, ip]
@@ -279,6 +286,38 @@ def runlora_vera_backward(variant, dY, saved, W, A, B, d, b, dX, dd, db, workspa
 
 def runlora_vera_workspace_bytes(fwd, bwd, n, i, o, r, dtype):
     return int(lib().runlora_vera_workspace_bytes(fwd, bwd, n, i, o, r, dtype))
+
+
+def runlora_dora_forward(variant, X, W, A, B, m, Y, saved, c, workspace, stream=None, scale=None, bias=None):
+    """DoRA forward, Y = X ((W + scale A B) diag(m / c)) (+ bias), c = column norms of W + scale A B (written to
+    the fp32 vector c); variant must be RL_FWD2; the workspace (runlora_dora_workspace_bytes) is required."""
+    import torch
+    if bias is not None and (bias.dtype != X.dtype or bias.numel() != Y.shape[1]):
+        raise ValueError("bias must have d_out elements of the activation dtype")
+    dx, dw, da, db, dy = (tensor_desc(t) for t in (X, W, A, B, Y))
+    o = _opts(workspace, stream, scale, bias)
+    _check(lib().runlora_dora_forward(variant, _ref(dx), _ref(dw), _ref(da), _ref(db), _vec(m, B.shape[1], X.dtype, "m"),
+                                      _ref(dy), ctypes.byref(saved), _vec(c, B.shape[1], torch.float32, "c"), ctypes.byref(o)))
+    return Y
+
+
+def runlora_dora_backward(variant, dY, saved, W, A, B, m, c, Y, dX, dA, dB, dm, workspace, stream=None, bias=None):
+    """DoRA gradients for X, A, B and m (column norm held constant) in backward graph `variant` (RL_BWD4 / 5 / 7 /
+    8); any of dX / dA / dB / dm may be None; Y (the forward's output) and the forward's bias are needed for dm."""
+    import torch
+    ddy, dw, da, dbm = (tensor_desc(t) for t in (dY, W, A, B))
+    gy = tensor_desc(Y)
+    gx, ga, gb = (tensor_desc(t) for t in (dX, dA, dB))
+    o = _opts(workspace, stream, None, bias)
+    oo = B.shape[1]
+    _check(lib().runlora_dora_backward(variant, _ref(ddy), ctypes.byref(saved), _ref(dw), _ref(da), _ref(dbm),
+                                       _vec(m, oo, dY.dtype, "m"), _vec(c, oo, torch.float32, "c"), _ref(gy), _ref(gx),
+                                       _ref(ga), _ref(gb), _vec(dm, oo, dY.dtype, "dm"), ctypes.byref(o)))
+    return dX, dA, dB, dm
+
+
+def runlora_dora_workspace_bytes(fwd, bwd, n, i, o, r, dtype):
+    return int(lib().runlora_dora_workspace_bytes(fwd, bwd, n, i, o, r, dtype))
 
 
 def runlora_select(n_tokens, d_in, d_out, r, dtype, criterion=None):

@@ -14,7 +14,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librunlora.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-SOURCES = ["gemm_bf16.hip", "gemm_f16.hip", "gemm_f32.hip", "gemm_host.hip", "schedule.cpp", "select.cpp", "api.hip", "probe.hip", "vera.hip"]
+SOURCES = ["gemm_bf16.hip", "gemm_f16.hip", "gemm_f32.hip", "gemm_host.hip", "schedule.cpp", "select.cpp", "api.hip", "probe.hip", "vera.hip", "dora.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

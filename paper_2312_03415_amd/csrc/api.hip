@@ -5,6 +5,7 @@
 
 #include "../../include/runlora.h"
 #include "schedule.hpp"
+#include "dora.hpp"
 #include "vera.hpp"
 
 using namespace rl;
@@ -147,6 +148,12 @@ void describe_step(const Step& s, rl_step_time_t* r) {
 
 // While set, the layer calls check their arguments and build their schedule but enqueue nothing: an
 // entry point built on top of them validates everything this way before its own first launch.
+// set by the DoRA entry points around their inner layer call: the frozen weight is W diag(g_wcol)
+thread_local const float* g_wcol = nullptr;
+struct WCol {
+  explicit WCol(const float* g) { g_wcol = g; }
+  ~WCol() { g_wcol = nullptr; }
+};
 thread_local bool g_dry_run = false;
 struct DryRun {
   DryRun() { g_dry_run = true; }
@@ -217,6 +224,7 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
 
   const float scale = (opts && opts->scale != 0.f) ? opts->scale : 1.f;
   LayerDims L{n, i, o, r, dt, w_int4, scale};
+  L.wcol = g_wcol;
   if (opts && opts->dropout_p != 0.f) {
     if (!(opts->dropout_p > 0.f && opts->dropout_p < 1.f)) return RL_ERR_SHAPE;
     if (variant == RL_FWD2 || r > 128 || n * i >= (1LL << 34)) return RL_ERR_UNSUPPORTED;
@@ -336,6 +344,7 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   }
 
   LayerDims L{n, i, o, r, dt, w_int4, saved->scale != 0.f ? saved->scale : 1.f};
+  L.wcol = g_wcol;
   if (saved->dropout_thr != 0u) {
     if (saved->dropout_thr > 255u) return RL_ERR_SAVED_MISMATCH;
     if (variant > RL_BWD1 || r > 128 || n * i >= (1LL << 34)) return RL_ERR_UNSUPPORTED;
@@ -468,6 +477,182 @@ extern "C" size_t runlora_vera_workspace_bytes(int fwd, int bwd, int64_t n, int6
   if (dt < 0 || n < 1 || i < 1 || o < 1 || r < 1) return 0;
   if (fwd > RL_FWD2 || bwd > RL_BWD8 || (fwd < 0 && bwd < 0)) return 0;
   return 2 * align256((size_t)r * (size_t)o * dtype_size(dt)) + runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype);
+}
+
+// ---- DoRA: the merged-weight graphs on (W diag(g), A, B diag(g)), g = m / c, see dora.hpp ----------------
+
+namespace {
+
+// workspace layout of the DoRA calls: [g: o floats][B~ r x o][dB~ r x o][partial sums: rows x o floats][the layer call's own]
+struct DoraLayout {
+  float* g = nullptr;
+  rl_tensor_t Bt{}, dBt{};
+  float* partial = nullptr;
+  int norm_rows = 0, dm_rows = 0;
+  size_t head_bytes = 0;
+  rl_opts_t inner{};
+};
+
+size_t dora_head_bytes(int64_t n, int64_t i, int64_t o, int64_t r, int dt, int* norm_rows, int* dm_rows) {
+  int gx = 0, gy = 0, bpw = 0;
+  merge_grid(i, o, r, &gx, &gy, &bpw);
+  const int dmr = dora_dm_slices(n, o);
+  if (norm_rows) *norm_rows = gy;
+  if (dm_rows) *dm_rows = dmr;
+  const size_t rows = (size_t)(gy > dmr ? gy : dmr);
+  return align256((size_t)o * 4) + 2 * align256((size_t)r * (size_t)o * dtype_size(dt)) + align256(rows * (size_t)o * 4);
+}
+
+int dora_layout(const rl_tensor_t* W, const rl_tensor_t* A, const rl_tensor_t* B, const void* m, int64_t n,
+                const rl_opts_t* opts, DoraLayout* v) {
+  if (!m) return RL_ERR_NULL;
+  const int dt = internal_dtype(B->dtype);
+  if (dt < 0) return RL_ERR_DTYPE;
+  if (W->dtype != B->dtype || A->dtype != B->dtype) return RL_ERR_DTYPE;
+  const int64_t i = W->rows, o = W->cols, r = A->cols;
+  if (n < 1 || i < 1 || o < 1 || r < 1 || i > (1LL << 30) || o > (1LL << 30) || B->rows != r || B->cols != o || A->rows != i)
+    return RL_ERR_SHAPE;
+  if (dt == DT_F32 || r > 128) return RL_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(m) & 15) != 0) return RL_ERR_ALIGN;
+  v->head_bytes = dora_head_bytes(n, i, o, r, dt, &v->norm_rows, &v->dm_rows);
+  if (!opts || !opts->workspace || opts->workspace_bytes < v->head_bytes) return RL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(opts->workspace) & 255) != 0) return RL_ERR_ALIGN;
+  char* ws = static_cast<char*>(opts->workspace);
+  const size_t fb = align256((size_t)r * (size_t)o * dtype_size(dt));
+  v->g = reinterpret_cast<float*>(ws);
+  ws += align256((size_t)o * 4);
+  v->Bt = rl_tensor_t{ws, r, o, o, B->dtype, nullptr, 0};
+  v->dBt = rl_tensor_t{ws + fb, r, o, o, B->dtype, nullptr, 0};
+  v->partial = reinterpret_cast<float*>(ws + 2 * fb);
+  v->inner = *opts;
+  v->inner.workspace = static_cast<char*>(opts->workspace) + v->head_bytes;
+  v->inner.workspace_bytes = opts->workspace_bytes - v->head_bytes;
+  return RL_OK;
+}
+
+}  // namespace
+
+extern "C" int runlora_dora_forward(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
+                                    const rl_tensor_t* B, const void* m, rl_tensor_t* Y, rl_saved_t* saved, float* c,
+                                    const rl_opts_t* opts) {
+  if (!X || !W || !A || !B || !Y || !saved || !c) return RL_ERR_NULL;
+  if (variant != RL_FWD2) return variant < RL_FWD_DEFAULT || variant > RL_FWD2 ? RL_ERR_VARIANT : RL_ERR_UNSUPPORTED;
+  DoraLayout v;
+  int rc = dora_layout(W, A, B, m, X->rows, opts, &v);
+  if (rc != RL_OK) return rc;
+  if (opts->dropout_p != 0.f) return RL_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(c) & 15) != 0) return RL_ERR_ALIGN;
+  const int dt = internal_dtype(B->dtype);
+  const size_t esz = dtype_size(dt);
+  const int64_t i = W->rows, o = W->cols, r = A->cols;
+  if ((rc = check_tensor(B, r, o, X->dtype)) != RL_OK) return rc;
+  {  // c is written before Y is: it may overlap no operand and not Y; Y may not overlap m
+    Range rc_ = range_of(c, 1, o, o, 4), rm = range_of(m, 1, o, o, esz);
+    std::vector<Range> others = {rm, range_of(B->data, r, B->ld, o, esz)};
+    if (W->data && W->ld >= o) others.push_back(range_of(W->data, i, W->ld, o, esz));
+    if (A->data && A->ld >= r) others.push_back(range_of(A->data, i, A->ld, r, esz));
+    if (X->data && X->rows >= 1 && X->ld >= X->cols) others.push_back(range_of(X->data, X->rows, X->ld, X->cols, esz));
+    if (opts->bias) others.push_back(range_of(opts->bias, 1, o, o, esz));
+    if (saved->M && saved->ldm >= o) others.push_back(range_of(saved->M, i, saved->ldm, o, esz));
+    if (Y->data && Y->rows >= 1 && Y->ld >= Y->cols && Y->cols == o) {
+      Range ry = range_of(Y->data, Y->rows, Y->ld, o, esz);
+      if (overlap(ry, rm)) return RL_ERR_ALIAS;
+      others.push_back(ry);
+    }
+    for (const Range& in : others)
+      if (overlap(rc_, in)) return RL_ERR_ALIAS;
+  }
+  WCol hook(v.g);
+  {
+    DryRun dry;  // every check of the layer call, before the first launch
+    rl_saved_t probe = *saved;
+    if ((rc = runlora_forward(variant, X, W, A, &v.Bt, Y, &probe, &v.inner)) != RL_OK) return rc;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(opts->stream);
+  MergeDesc nd;
+  nd.W = W->data; nd.A = A->data; nd.B = B->data; nd.M = nullptr;
+  nd.ldw = W->ld; nd.lda = A->ld; nd.ldb = B->ld; nd.ldm = 0;
+  nd.I = i; nd.O = o; nd.R = r;
+  nd.alpha = opts->scale != 0.f ? opts->scale : 1.f;
+  nd.sq_partial = v.partial;
+  hipError_t e = merge_run(dt, nd, stream);
+  if (e != hipSuccess) return set_hip_error(e, "column sums of (W + s A B)^2");
+  if ((e = dora_norm_finish_run(dt, v.partial, v.norm_rows, m, c, v.g, o, stream)) != hipSuccess)
+    return set_hip_error(e, "c, g = m / c");
+  if ((e = dora_colscale_run(dt, B->data, B->ld, v.g, v.Bt.data, v.Bt.ld, r, o, stream)) != hipSuccess)
+    return set_hip_error(e, "B~ = B diag(g)");
+  return runlora_forward(variant, X, W, A, &v.Bt, Y, saved, &v.inner);
+}
+
+extern "C" int runlora_dora_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved, const rl_tensor_t* W,
+                                     const rl_tensor_t* A, const rl_tensor_t* B, const void* m, const float* c,
+                                     const rl_tensor_t* Y, rl_tensor_t* dX, rl_tensor_t* dA, rl_tensor_t* dB, void* dm,
+                                     const rl_opts_t* opts) {
+  if (!dY || !saved || !W || !A || !B || !c) return RL_ERR_NULL;
+  if (variant < RL_BWD_DEFAULT || variant > RL_BWD8) return RL_ERR_VARIANT;
+  if (variant != RL_BWD4 && variant != RL_BWD5 && variant != RL_BWD7 && variant != RL_BWD8) return RL_ERR_UNSUPPORTED;
+  DoraLayout v;
+  int rc = dora_layout(W, A, B, m, dY->rows, opts, &v);
+  if (rc != RL_OK) return rc;
+  if (saved->dropout_thr != 0u) return RL_ERR_UNSUPPORTED;
+  if (dm && !Y) return RL_ERR_NULL;
+  if (((reinterpret_cast<uintptr_t>(c) | reinterpret_cast<uintptr_t>(dm)) & 15) != 0) return RL_ERR_ALIGN;
+  const int dt = internal_dtype(B->dtype);
+  const size_t esz = dtype_size(dt);
+  const int64_t n = dY->rows, i = W->rows, o = W->cols, r = A->cols;
+  if ((rc = check_tensor(B, r, o, dY->dtype)) != RL_OK) return rc;
+  if (dB && (rc = check_tensor(dB, r, o, dY->dtype)) != RL_OK) return rc;
+  if (dm) {
+    if ((rc = check_tensor(Y, n, o, dY->dtype)) != RL_OK) return rc;
+    if (opts->bias && (reinterpret_cast<uintptr_t>(opts->bias) & 15) != 0) return RL_ERR_ALIGN;
+  }
+  {  // dm and dB are written here: they may overlap nothing the call reads and none of its other outputs
+    std::vector<Range> outs, others = {range_of(m, 1, o, o, esz), range_of(c, 1, o, o, 4), range_of(B->data, r, B->ld, o, esz)};
+    if (dm) outs.push_back(range_of(dm, 1, o, o, esz));
+    if (dB) outs.push_back(range_of(dB->data, r, dB->ld, o, esz));
+    if (dY->data && dY->rows >= 1 && dY->ld >= dY->cols) others.push_back(range_of(dY->data, n, dY->ld, dY->cols, esz));
+    if (Y && Y->data && Y->ld >= o) others.push_back(range_of(Y->data, n, Y->ld, o, esz));
+    if (opts->bias) others.push_back(range_of(opts->bias, 1, o, o, esz));
+    if (W->data && W->ld >= o) others.push_back(range_of(W->data, i, W->ld, o, esz));
+    if (A->data && A->ld >= r) others.push_back(range_of(A->data, i, A->ld, r, esz));
+    if (saved->X && saved->n >= 1 && saved->ldx >= saved->i && saved->i >= 1) others.push_back(range_of(saved->X, saved->n, saved->ldx, saved->i, esz));
+    if (saved->M && saved->ldm >= o) others.push_back(range_of(saved->M, i, saved->ldm, o, esz));
+    if (dX && dX->data && dX->rows >= 1 && dX->ld >= dX->cols) others.push_back(range_of(dX->data, dX->rows, dX->ld, dX->cols, esz));
+    if (dA && dA->data && dA->rows >= 1 && dA->ld >= dA->cols) others.push_back(range_of(dA->data, dA->rows, dA->ld, dA->cols, esz));
+    for (const Range& out : outs)
+      for (const Range& in : others)
+        if (overlap(out, in)) return RL_ERR_ALIAS;
+    if (outs.size() == 2 && overlap(outs[0], outs[1])) return RL_ERR_ALIAS;
+    if (Y && Y->data && Y->ld >= o) {  // the forward's output is read after dX and dA are written
+      Range ry = range_of(Y->data, n, Y->ld, o, esz);
+      if (dX && dX->data && dX->rows >= 1 && dX->ld >= dX->cols && overlap(ry, range_of(dX->data, dX->rows, dX->ld, dX->cols, esz))) return RL_ERR_ALIAS;
+      if (dA && dA->data && dA->rows >= 1 && dA->ld >= dA->cols && overlap(ry, range_of(dA->data, dA->rows, dA->ld, dA->cols, esz))) return RL_ERR_ALIAS;
+    }
+  }
+  rl_tensor_t* dBt = dB ? &v.dBt : nullptr;
+  WCol hook(v.g);
+  {
+    DryRun dry;
+    if ((rc = runlora_backward(variant, dY, saved, W, A, &v.Bt, dX, dA, dBt, &v.inner)) != RL_OK) return rc;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(opts->stream);
+  hipError_t e = dora_g_run(dt, m, c, v.g, o, stream);
+  if (e != hipSuccess) return set_hip_error(e, "g = m / c");
+  if ((e = dora_colscale_run(dt, B->data, B->ld, v.g, v.Bt.data, v.Bt.ld, r, o, stream)) != hipSuccess)
+    return set_hip_error(e, "B~ = B diag(g)");
+  if ((rc = runlora_backward(variant, dY, saved, W, A, &v.Bt, dX, dA, dBt, &v.inner)) != RL_OK) return rc;
+  if (dB && (e = dora_colscale_run(dt, v.dBt.data, v.dBt.ld, v.g, dB->data, dB->ld, r, o, stream)) != hipSuccess)
+    return set_hip_error(e, "dB = dB~ diag(g)");
+  if (dm && (e = dora_dm_run(dt, dY->data, dY->ld, Y->data, Y->ld, opts->bias, m, v.partial, dm, n, o, stream)) != hipSuccess)
+    return set_hip_error(e, "dm");
+  return RL_OK;
+}
+
+extern "C" size_t runlora_dora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype) {
+  const int dt = internal_dtype(dtype);
+  if (dt < 0 || dt == DT_F32 || n < 1 || i < 1 || o < 1 || r < 1 || r > 128) return 0;
+  if (fwd > RL_FWD2 || bwd > RL_BWD8 || (fwd < 0 && bwd < 0)) return 0;
+  return dora_head_bytes(n, i, o, r, dt, nullptr, nullptr) + runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype);
 }
 
 extern "C" size_t runlora_saved_bytes(int fwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype, int keep_merged) {

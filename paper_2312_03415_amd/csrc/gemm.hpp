@@ -106,8 +106,24 @@ struct MergeDesc {
   int64_t I = 0, O = 0, R = 0;
   float alpha = 1.f;  // M = W + alpha A B
   int b_trans = 0;    // B stored [O, R]
+  const float* wcol = nullptr;  // optional [O]: M = W diag(wcol) + alpha A B
+  // optional: store nothing to M; write the squared column sums of W + alpha A B, one row of O floats per
+  // row slice of the launch (merge_grid's gy rows; the caller adds them up)
+  float* sq_partial = nullptr;
 };
 inline bool merge_ok(int dtype, int64_t r) { return dtype != DT_F32 && r <= 128; }
+// the merge kernel's launch shape: gx workgroups of `cols` columns, gy row slices of bpw 32-row blocks each
+// (about two workgroups per compute unit, each walking several row blocks)
+inline void merge_grid(int64_t I, int64_t O, int64_t R, int* gx, int* gy, int* bpw) {
+  const int cols = R <= 64 ? 512 : 256;
+  *gx = (int)((O + cols - 1) / cols);
+  const int nb = (int)((I + 31) / 32);
+  int y = 512 / *gx;
+  if (y < 1) y = 1;
+  if (y > nb) y = nb;
+  *bpw = (nb + y - 1) / y;
+  *gy = (nb + *bpw - 1) / *bpw;
+}
 hipError_t merge_run(int dtype, const MergeDesc& d, hipStream_t stream);
 struct MergeArgs;
 hipError_t merge_launch_bf16(const MergeArgs& a, hipStream_t s);

@@ -312,6 +312,8 @@ hipError_t merge_run(int dtype, const MergeDesc& d, hipStream_t stream) {
   a.blocks_per_wg = 1;
   a.alpha = d.alpha;
   a.b_trans = d.b_trans;
+  a.wcol = d.wcol;
+  a.sq_partial = d.sq_partial;
   return dtype == DT_BF16 ? merge_launch_bf16(a, stream) : merge_launch_f16(a, stream);
 }
 

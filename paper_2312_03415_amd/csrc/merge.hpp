@@ -1,6 +1,7 @@
 // M = W + alpha A B for the merged-weight graphs (forward2, Eq. 2; Z1 / Z3 of Algorithms 4 and 5 of arxiv
 // 2312.03415): [i,o] = [i,o] + [i,r][r,o] with r <= 128, bf16 / fp16.  The default chain's rank-r updates
-// (Y += T B, dX += Z1 A^T: the same operation on [n,o] / [n,i], in place) run here as well.
+// (Y += T B, dX += Z1 A^T: the same operation on [n,o] / [n,i], in place) run here as well, and so do the two
+// passes DoRA adds: the squared column norms of W + alpha A B (nothing stored) and W diag(g) + alpha A B.
 //
 // The product is tiny (2 i o r FLOPs); the kernel reads W once and writes M once, so it is bound by
 // HBM bandwidth (2 i o e bytes) and is organised around coalesced 16-byte accesses with many of
@@ -25,6 +26,10 @@ struct MergeArgs {
   int blocks_per_wg;  // 32-row blocks each workgroup walks (gridDim.y covers ceil(I/32) of them)
   float alpha;        // the layer's LoRA scale (1 for the paper's layer)
   int b_trans;        // 1: B is stored [O, R] (the r values of a column contiguous), as A^T of dX += Z1 A^T is
+  const float* wcol;  // optional [O]: M = W diag(wcol) + alpha A B (the column-scaled frozen weight of DoRA)
+  // optional [gridDim.y][O]: nothing is stored to M; each workgroup writes, per column, the sum over its
+  // rows of (W + alpha A B)^2 in fp32 (the squared column norms, summed over gridDim.y by the caller)
+  float* sq_partial;
 };
 
 template <int KSTEPS, int CB>
@@ -89,6 +94,12 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs g) {
   if (rb1 > nblocks) rb1 = nblocks;
   const int prow = lane / MT::LPR, pcol = (lane % MT::LPR) * 8;  // this lane's (row in pass, column) for W / M
   const bool col_ok = n0 + pcol < g.O;
+  float gs[8], sq[8];  // W's column scale (1 without one) and the running squared column sums of this lane's 8 columns
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    gs[e] = (g.wcol != nullptr && col_ok) ? g.wcol[n0 + pcol + e] : 1.f;
+    sq[e] = 0.f;
+  }
   // W rows and the A fragment of a row block are fetched one block ahead, so that no global-memory
   // latency sits between two blocks
   i32x4 wreg[MT::PASSES], fnext[KSTEPS];
@@ -139,13 +150,32 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs g) {
       const f32x4 s0 = *reinterpret_cast<const f32x4*>(red + rloc * MT::LD + pcol);
       const f32x4 s1 = *reinterpret_cast<const f32x4*>(red + rloc * MT::LD + pcol + 4);
       const T* w8 = reinterpret_cast<const T*>(&wcur[p]);
+      if (g.sq_partial != nullptr) {  // uniform: rows and columns outside the matrix contribute zeros
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float v0 = (float)w8[e] + g.alpha * s0[e], v1 = (float)w8[4 + e] + g.alpha * s1[e];
+          sq[e] += v0 * v0;
+          sq[4 + e] += v1 * v1;
+        }
+        continue;
+      }
       T o8[8];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        o8[e] = from_f32<T>((float)w8[e] + g.alpha * s0[e]);
-        o8[4 + e] = from_f32<T>((float)w8[4 + e] + g.alpha * s1[e]);
+      for (int e = 0; e < 4; ++e) {  // the scaled W is rounded on its own (times 1 is exact), then the sum as before
+        o8[e] = from_f32<T>(__fmul_rn((float)w8[e], gs[e]) + g.alpha * s0[e]);
+        o8[4 + e] = from_f32<T>(__fmul_rn((float)w8[4 + e], gs[4 + e]) + g.alpha * s1[e]);
       }
       if (col_ok && row < g.I) *reinterpret_cast<i32x4*>(Mp + (int64_t)row * g.ldm + n0 + pcol) = *reinterpret_cast<i32x4*>(o8);
+    }
+  }
+  if (g.sq_partial != nullptr) {
+    // the RPP lanes that share a column group add up in a fixed order through the wave's LDS region
+    *reinterpret_cast<f32x4*>(red + prow * MT::COLS + pcol) = f32x4{sq[0], sq[1], sq[2], sq[3]};
+    *reinterpret_cast<f32x4*>(red + prow * MT::COLS + pcol + 4) = f32x4{sq[4], sq[5], sq[6], sq[7]};
+    for (int c = lane; c < MT::COLS; c += 64) {
+      float t = 0.f;
+      for (int p = 0; p < MT::RPP; ++p) t += red[p * MT::COLS + c];
+      if (n0 + c < g.O) g.sq_partial[(int64_t)blockIdx.y * g.O + n0 + c] = t;
     }
   }
 }

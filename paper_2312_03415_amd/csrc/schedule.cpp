@@ -95,6 +95,7 @@ struct Builder {
     s.mg.ldw = W.ld; s.mg.lda = A.ld; s.mg.ldb = B.ld; s.mg.ldm = M.ld;
     s.mg.I = L.i; s.mg.O = L.o; s.mg.R = L.r;
     s.mg.alpha = scale();
+    s.mg.wcol = L.wcol;
     out->steps.push_back(s);
   }
 
@@ -212,6 +213,7 @@ bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void*
   out->steps.clear();
   Builder b(L, ws_base, out);
   const int64_t n = L.n, i = L.i, o = L.o, r = L.r;
+  if (L.wcol && (variant != 2 || !merge_ok(L.dtype, r) || L.w_int4 || L.drop_thr)) return false;  // see LayerDims::wcol
   switch (variant) {
     case 0: {  // default chain: T kept, one kernel per product
       b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, op.T, true, true});
@@ -245,6 +247,8 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
   const int64_t n = L.n, i = L.i, o = L.o, r = L.r;
   const bool dX = op.want_dX, dA = op.want_dA, dB = op.want_dB;
   if (L.drop_thr && variant > 1) return false;  // see LayerDims::drop_thr
+  if (L.wcol && ((variant != 4 && variant != 5 && variant != 7 && variant != 8) || !merge_ok(L.dtype, r) || L.drop_thr))
+    return false;  // see LayerDims::wcol
   switch (variant) {
     case 0: {  // backward of the default chain (uses the kept T = XA)
       Mat Z1 = b.scratch(n, r);

@@ -31,6 +31,10 @@ struct LayerDims {
   // graphs that never merge AB into W and never form X^T dY exist with it: forward 0/1, backward 0/1, the
   // latter with dX = dY W^T followed by dX += m o (Z1 A^T) instead of the concatenated contraction.
   uint32_t drop_thr = 0, drop_key = 0;
+  // DoRA: the frozen weight is W diag(wcol) (device, o floats).  It is never formed: only the graphs in which
+  // W enters through M = W + s AB alone exist with it (forward2, backward 4 / 5 / 7 / 8), where the merge kernel
+  // scales W's columns on the way; 16-bit types, r <= 128.
+  const float* wcol = nullptr;
 };
 
 struct Step {

@@ -268,6 +268,65 @@ def test_vera_calls_reject_bad_arguments_before_touching_the_gpu():
     assert bwd(1, saved=rl.rl_saved_t(1, dt, n + 1, i, o, r, base + 7 * step, i, None, 0)) == rl.RL_ERR_SAVED_MISMATCH
 
 
+def test_dora_calls_reject_bad_arguments_before_touching_the_gpu():
+    """The DoRA entry points refuse the graphs that read W outside W + sAB, fp32, r > 128 and dropout, check their own
+    vectors, and run every check of the layer call they are built on before the first launch."""
+    n, i, o, r = 64, 32, 48, 8
+    dt = rl.RL_BF16
+    L = rl.lib()
+    br = ctypes.byref
+    a = fwd_args(n, i, o, r)
+    m, c = 0x20000000, 0x20001000
+    need = rl.runlora_dora_workspace_bytes(2, 5, n, i, o, r, dt)
+    assert need > rl.runlora_workspace_bytes(2, 5, n, i, o, r, dt) + 2 * r * o * 2 + o * 4
+    assert rl.runlora_dora_workspace_bytes(2, 5, n, i, o, r, rl.RL_F32) == 0
+    assert rl.runlora_dora_workspace_bytes(2, 5, n, i, o, 136, dt) == 0
+    assert rl.runlora_dora_workspace_bytes(-1, -1, n, i, o, r, dt) == 0
+    ws = rl.rl_opts_t(None, 0x70000000, need)
+
+    def fwd(variant, a=a, m=m, c=c, opts=ws):
+        return L.runlora_dora_forward(variant, br(a["X"]), br(a["W"]), br(a["A"]), br(a["B"]), m, br(a["Y"]),
+                                      br(rl.rl_saved_t()), c, br(opts) if opts else None)
+
+    assert fwd(0) == rl.RL_ERR_UNSUPPORTED and fwd(1) == rl.RL_ERR_UNSUPPORTED
+    assert fwd(3) == rl.RL_ERR_VARIANT
+    assert fwd(2, m=None) == rl.RL_ERR_NULL and fwd(2, c=None) == rl.RL_ERR_NULL
+    assert fwd(2, m=m + 4) == rl.RL_ERR_ALIGN and fwd(2, c=c + 4) == rl.RL_ERR_ALIGN
+    assert fwd(2, opts=None) == rl.RL_ERR_WORKSPACE
+    assert fwd(2, opts=rl.rl_opts_t(None, 0x70000000, 4096)) == rl.RL_ERR_WORKSPACE
+    assert fwd(2, c=a["Y"].data) == rl.RL_ERR_ALIAS and fwd(2, c=m) == rl.RL_ERR_ALIAS and fwd(2, m=a["Y"].data) == rl.RL_ERR_ALIAS
+    drop = rl.rl_opts_t(None, 0x70000000, need, 0.0, None, 0.1, 3)
+    assert fwd(2, opts=drop) == rl.RL_ERR_UNSUPPORTED
+    f32 = fwd_args(n, i, o, r, rl.RL_F32)
+    assert fwd(2, a=f32) == rl.RL_ERR_UNSUPPORTED
+    big = fwd_args(n, 256, o, 136)
+    assert fwd(2, a=big) == rl.RL_ERR_UNSUPPORTED
+    e = fwd_args(n, i, o, r); e["X"].ld = 36
+    assert fwd(2, a=e) == rl.RL_ERR_ALIGN                                                   # found by the dry run
+
+    base, step = 0x10000000, 0x1000000
+    dY, W, A, B, dX = T(base, n, o), T(base + step, i, o), T(base + 2 * step, i, r), T(base + 3 * step, r, o), T(base + 4 * step, n, i)
+    dA, dB, Y = T(base + 5 * step, i, r), T(base + 6 * step, r, o), T(base + 8 * step, n, o)
+    saved = rl.rl_saved_t(2, dt, n, i, o, r, base + 7 * step, i, None, 0)
+    dm = 0x20002000
+
+    def bwd(variant, saved=saved, m=m, c=c, Y=Y, dm=dm, dB=dB, opts=ws):
+        return L.runlora_dora_backward(variant, br(dY), br(saved), br(W), br(A), br(B), m, c, br(Y) if Y else None, br(dX),
+                                       br(dA), br(dB) if dB else None, dm, br(opts) if opts else None)
+
+    assert bwd(9) == rl.RL_ERR_VARIANT
+    for v in (0, 1, 2, 3, 6):
+        assert bwd(v) == rl.RL_ERR_UNSUPPORTED
+    assert bwd(5, c=None) == rl.RL_ERR_NULL and bwd(5, m=None) == rl.RL_ERR_NULL
+    assert bwd(5, Y=None) == rl.RL_ERR_NULL              # dm needs the forward's output
+    assert bwd(5, dm=dm + 8) == rl.RL_ERR_ALIGN
+    assert bwd(5, dm=m) == rl.RL_ERR_ALIAS and bwd(5, dm=dY.data) == rl.RL_ERR_ALIAS and bwd(5, dm=Y.data) == rl.RL_ERR_ALIAS
+    assert bwd(5, dB=T(base + 3 * step, r, o)) == rl.RL_ERR_ALIAS                           # dB on top of B
+    assert bwd(5, Y=T(base + 4 * step, n, o)) == rl.RL_ERR_ALIAS                            # Y is read after dX is written
+    assert bwd(5, opts=rl.rl_opts_t(None, 0x70000000, 4096)) == rl.RL_ERR_WORKSPACE
+    assert bwd(5, saved=rl.rl_saved_t(2, dt, n + 1, i, o, r, base + 7 * step, i, None, 0)) == rl.RL_ERR_SAVED_MISMATCH
+
+
 def test_gemm_call_rejects_bad_arguments():
     g = rl.rl_gemm_t(rl.RL_BF16, 1, 1, -1, 0, 64, 64, 64, 0, 0x1000, 0x2000, None, None, None, 0x3000, 64, 64, 0, 0, 64, 0)
     L = rl.lib()

@@ -1,0 +1,190 @@
+"""GPU parity of the DoRA entry points (magnitudes m, direction (W + sAB) / column norm; the paper's conclusion
+names DoRA among the adapters its method carries over to): c, Y, dX, dA, dB, dm of every merged-weight graph
+against the fp64 oracle of the layer's definition (oracle.dora_norm / dora_forward / dora_backward), the
+reduction to the LoRA calls, the kept merged weight, skipped outputs, refusals, and one full-size layer."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL, layer_on_device, relerr, to_device, to_f64, torch_dtype
+from paper_2312_03415_amd import binding as rl
+from paper_2312_03415_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+BWDS = (4, 5, 7, 8)
+
+
+def vectors(L):
+    """m: positive magnitudes around the column norms' size (DoRA starts from m = ||W||); bias."""
+    out = {}
+    m = 0.5 + np.abs(synth.normal(synth.BASE_SEED + L.index, 10, (L.o,)))
+    for name, v in (("m", m), ("bias", synth.normal(synth.BASE_SEED + L.index, 9, (L.o,)))):
+        st = synth.store(v, L.dtype)
+        out[name] = (to_device(st, L.dtype), synth.widen(st, L.dtype))
+    return out
+
+
+def run_dora(L, dev, vec, bwd, scale, bias, want=("dX", "dA", "dB", "dm"), keep=False, m=None):
+    import torch
+    td = torch_dtype(L.dtype)
+    code = rl.dtype_from_name(L.dtype)
+    nan = float("nan")
+    Y = torch.full((L.n, L.o), nan, dtype=td, device="cuda")
+    c = torch.full((L.o,), nan, dtype=torch.float32, device="cuda")
+    M = torch.full((L.i, L.o), nan, dtype=td, device="cuda") if keep else None
+    saved = rl.new_saved(None, M)
+    ws = torch.empty(rl.runlora_dora_workspace_bytes(2, bwd, L.n, L.i, L.o, L.r, code), dtype=torch.uint8, device="cuda")
+    m = vec["m"][0] if m is None else m
+    rl.runlora_dora_forward(2, dev["X"], dev["W"], dev["A"], dev["B"], m, Y, saved, c, ws, scale=scale, bias=bias)
+    ws.fill_(0xFF)  # nothing the forward left in the workspace may matter to the backward
+    dX = torch.full((L.n, L.i), nan, dtype=td, device="cuda") if "dX" in want else None
+    dA = torch.full((L.i, L.r), nan, dtype=td, device="cuda") if "dA" in want else None
+    dB = torch.full((L.r, L.o), nan, dtype=td, device="cuda") if "dB" in want else None
+    dm = torch.full((L.o,), nan, dtype=td, device="cuda") if "dm" in want else None
+    rl.runlora_dora_backward(bwd, dev["dY"], saved, dev["W"], dev["A"], dev["B"], m, c, Y, dX, dA, dB, dm, ws, bias=bias)
+    torch.cuda.synchronize()
+    out = {"Y": to_f64(Y), "c": c.double().cpu().numpy()}
+    for k, t in (("dX", dX), ("dA", dA), ("dB", dB), ("dm", dm)):
+        if t is not None:
+            out[k] = to_f64(t)
+    if keep:
+        out["M"] = to_f64(M)
+    return out
+
+
+def dora_reference(host, vec, scale, with_bias=True):
+    m, bias = vec["m"][1], vec["bias"][1]
+    args = (host["X"], host["W"], host["A"], host["B"], m)
+    Y = oracle.dora_forward(*args, scale, bias if with_bias else None)
+    dX, dA, dB, dm = oracle.dora_backward(*args, host["dY"], scale)
+    return {"c": oracle.dora_norm(host["W"], host["A"], host["B"], scale), "Y": Y, "dX": dX, "dA": dA, "dB": dB, "dm": dm}
+
+
+@pytest.mark.parametrize("dtype,r", [("bf16", 24), ("f16", 64), ("bf16", 128), ("f16", 8)])
+def test_dora_all_graphs(dtype, r):
+    """Ragged shape (several column strips and row slices of the norm pass, partial tiles everywhere), forward2
+    with each of backward 4 / 5 / 7 / 8, s = 0.5, a bias.  c is an fp32 sum of unrounded terms: 1e-5."""
+    L = synth.Layer("dora", 301, 264, 1096, r, dtype, 51)
+    dev, host = layer_on_device(L)
+    vec = vectors(L)
+    want = dora_reference(host, vec, 0.5)
+    for b in BWDS:
+        print(f"case dora layer={L} bwd={b}", flush=True)
+        got = run_dora(L, dev, vec, b, 0.5, vec["bias"][0])
+        assert relerr(got["c"], want["c"]) < 1e-5, (b, relerr(got["c"], want["c"]))
+        for k in ("Y", "dX", "dA", "dB", "dm"):
+            err = relerr(got[k], want[k])
+            assert err < TOL[dtype], (b, k, err)
+
+
+def test_dora_kept_merged_weight_and_skipped_outputs():
+    """Keeping (W + sAB) diag(g) between forward and backward changes no bit of any output; it is the oracle's
+    adapted weight, whose columns have length m; skipped outputs leave the others unchanged."""
+    L = synth.Layer("dora2", 200, 136, 264, 16, "bf16", 52)
+    dev, host = layer_on_device(L)
+    vec = vectors(L)
+    full = run_dora(L, dev, vec, 5, 0.7, vec["bias"][0])
+    kept = run_dora(L, dev, vec, 5, 0.7, vec["bias"][0], keep=True)
+    for k in full:
+        assert np.array_equal(full[k], kept[k]), k
+    V = host["W"] + 0.7 * host["A"] @ host["B"]
+    cn = np.sqrt((V * V).sum(axis=0))
+    assert relerr(kept["M"], V * (vec["m"][1] / cn)[None, :]) < TOL["bf16"]
+    assert relerr(np.sqrt((kept["M"] ** 2).sum(axis=0)), vec["m"][1]) < TOL["bf16"]
+    for want in (("dm",), ("dB",), ("dX",), ("dA", "dm"), ()):
+        part = run_dora(L, dev, vec, 5, 0.7, vec["bias"][0], want=want)
+        assert set(part) == {"Y", "c", *want}
+        for k in part:
+            assert np.array_equal(part[k], full[k]), (want, k)
+
+
+def test_dora_with_unit_gain_is_the_lora_layer():
+    """m = c rounded to the storage type makes g = 1 up to that rounding (5e-4 in f16): Y, dX, dA and dB are
+    then what the LoRA calls of the same graphs give, to tolerance."""
+    import torch
+    L = synth.Layer("dora3", 160, 136, 264, 16, "f16", 53)
+    dev, host = layer_on_device(L)
+    vec = vectors(L)
+    c = oracle.dora_norm(host["W"], host["A"], host["B"], 1.0)
+    st = synth.store(c, L.dtype)
+    m_dev, m_host = to_device(st, L.dtype), synth.widen(st, L.dtype)
+    got = run_dora(L, dev, vec, 4, None, None, m=m_dev)
+    code = rl.dtype_from_name(L.dtype)
+    Y = torch.empty((L.n, L.o), dtype=torch.float16, device="cuda")
+    saved = rl.new_saved(None)
+    ws = rl.new_workspace(2, 4, L.n, L.i, L.o, L.r, code)
+    rl.runlora_forward(2, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=ws)
+    dX = torch.empty((L.n, L.i), dtype=torch.float16, device="cuda")
+    dA = torch.empty((L.i, L.r), dtype=torch.float16, device="cuda")
+    dB = torch.empty((L.r, L.o), dtype=torch.float16, device="cuda")
+    rl.runlora_backward(4, dev["dY"], saved, dev["W"], dev["A"], dev["B"], dX, dA, dB, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(m_host / c - 1.0)) < 1e-3
+    for k, t in (("Y", Y), ("dX", dX), ("dA", dA), ("dB", dB)):
+        assert relerr(got[k], to_f64(t)) < TOL["f16"], k
+
+
+def test_dora_refusals():
+    """Graphs that read W outside W + sAB, fp32, r > 128 and dropout are refused with the documented codes before
+    anything is launched (outputs keep their fill)."""
+    import torch
+    L = synth.Layer("dora4", 64, 64, 128, 8, "bf16", 54)
+    dev, host = layer_on_device(L)
+    vec = vectors(L)
+    code = rl.dtype_from_name(L.dtype)
+    Y = torch.full((L.n, L.o), 7.0, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros((L.o,), dtype=torch.float32, device="cuda")
+    ws = torch.empty(rl.runlora_dora_workspace_bytes(2, 5, L.n, L.i, L.o, L.r, code) + 4096, dtype=torch.uint8, device="cuda")
+    saved = rl.new_saved(torch.empty((L.n, L.r), dtype=torch.bfloat16, device="cuda"))
+    for fwd in (0, 1):
+        with pytest.raises(rl.RunLoRAError) as e:
+            rl.runlora_dora_forward(fwd, dev["X"], dev["W"], dev["A"], dev["B"], vec["m"][0], Y, saved, c, ws)
+        assert e.value.code == rl.RL_ERR_UNSUPPORTED
+    with pytest.raises(rl.RunLoRAError) as e:
+        rl.runlora_dora_forward(3, dev["X"], dev["W"], dev["A"], dev["B"], vec["m"][0], Y, saved, c, ws)
+    assert e.value.code == rl.RL_ERR_VARIANT
+    saved = rl.new_saved(None)
+    rl.runlora_dora_forward(2, dev["X"], dev["W"], dev["A"], dev["B"], vec["m"][0], Y, saved, c, ws)
+    dX = torch.full((L.n, L.i), 7.0, dtype=torch.bfloat16, device="cuda")
+    for bwd in (0, 1, 2, 3, 6):
+        with pytest.raises(rl.RunLoRAError) as e:
+            rl.runlora_dora_backward(bwd, dev["dY"], saved, dev["W"], dev["A"], dev["B"], vec["m"][0], c, Y, dX, None, None, None, ws)
+        assert e.value.code == rl.RL_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((dX == 7.0).all())
+    # dm without the forward's output
+    dm = torch.zeros((L.o,), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(rl.RunLoRAError) as e:
+        rl.runlora_dora_backward(5, dev["dY"], saved, dev["W"], dev["A"], dev["B"], vec["m"][0], c, None, dX, None, None, dm, ws)
+    assert e.value.code == rl.RL_ERR_NULL
+    assert rl.runlora_dora_workspace_bytes(2, 5, 64, 64, 128, 8, rl.dtype_from_name("f32")) == 0
+    assert rl.runlora_dora_workspace_bytes(2, 5, 64, 64, 128, 136, code) == 0
+
+
+def test_dora_full_size_opt_fc1():
+    """OPT-1.3B fc1 shape (n 4096, 2048 -> 8192, bf16, r 16), forward2 + backward5: c, dm, dA, dB in full (they need
+    every token), Y and dX on sampled token rows."""
+    L = synth.Layer("dora_fc1", 4096, 2048, 8192, 16, "bf16", 55)
+    dev, host = layer_on_device(L)
+    vec = vectors(L)
+    m, bias = vec["m"][1], vec["bias"][1]
+    s = 2.0
+    got = run_dora(L, dev, vec, 5, s, vec["bias"][0])
+    V = host["W"] + s * oracle.matmul(host["A"], host["B"])
+    c = np.sqrt((V * V).sum(axis=0))
+    assert relerr(got["c"], c) < 1e-5
+    g = m / c
+    dU = host["dY"] * g[None, :]
+    T = oracle.matmul(host["X"], host["A"])
+    dB = s * oracle.matmul(T, dU, ta=True)
+    dA = s * oracle.matmul(host["X"], oracle.matmul(dU, host["B"], tb=True), ta=True)
+    # dm[j] = sum_t dY[t,j] (XV)[t,j] / c[j] = sum_i (X^T dY)[i,j] V[i,j] / c[j]
+    dm = (oracle.matmul(host["X"], host["dY"], ta=True) * V).sum(axis=0) / c
+    assert relerr(got["dB"], dB) < TOL["bf16"] and relerr(got["dA"], dA) < TOL["bf16"]
+    assert relerr(got["dm"], dm) < TOL["bf16"], relerr(got["dm"], dm)
+    rng = np.random.default_rng(6)
+    rows = np.unique(np.concatenate([np.arange(0, L.n, 512), np.arange(255, L.n, 512), rng.integers(0, L.n, 24)]))
+    Yr = oracle.dora_forward(host["X"][rows], host["W"], host["A"], host["B"], m, s, bias)
+    dXr = oracle.matmul(dU[rows], V, tb=True)
+    assert relerr(got["Y"][rows], Yr) < TOL["bf16"] and relerr(got["dX"][rows], dXr) < TOL["bf16"]
