@@ -50,6 +50,9 @@ def parse():
                     help="let forward2 keep W + AB for backward4/5 (i*o elements held per layer; pairs chosen for that)")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="LoRA dropout probability (0 = the paper's setting); pairs are then (1,1), the only RunLoRA graphs that exist with it")
+    ap.add_argument("--dora", action="store_true",
+                    help="run the layers as DoRA (trainable magnitudes m on top of A, B) through runlora_dora_*: forward2 + a merged "
+                         "backward (5, or the second number of --pair); the default-chain leg is then the LoRA layer's")
     ap.add_argument("--vera", action="store_true",
                     help="run the layers as VeRA (frozen A, B, trainable vectors d and b; use with --rank 256 or so) through runlora_vera_*")
     ap.add_argument("--pair", default=None, help="force one 'fwd,bwd' pair on every layer instead of runlora_select")
@@ -125,13 +128,19 @@ def main():
             t["dA"] = torch.empty((L.i, L.r), dtype=tdt, device=dev)
             t["dB"] = torch.empty((L.r, L.o), dtype=tdt, device=dev)
             t["M"] = torch.empty((L.i, L.o), dtype=tdt, device=dev) if args.keep_merged else None
+            if args.dora:
+                t["m"] = to_dev(synth.store(0.5 + np.abs(synth.normal(synth.BASE_SEED + L.index, 10, (L.o,))), dtype))
+                t["c"] = torch.empty((L.o,), dtype=torch.float32, device=dev)
+                t["dm"] = torch.empty((L.o,), dtype=tdt, device=dev)
             if args.vera:
                 t["d"] = to_dev(synth.store(synth.normal(synth.BASE_SEED + L.index, 10, (L.r,)), dtype))
                 t["b"] = to_dev(synth.store(synth.normal(synth.BASE_SEED + L.index, 11, (L.o,)), dtype))
                 t["dd"] = torch.empty((L.r,), dtype=tdt, device=dev)
                 t["db"] = torch.empty((L.o,), dtype=tdt, device=dev)
             sets.append(t)
-        if args.dropout > 0.0:
+        if args.dora:
+            fwd, bwd = 2, (int(args.pair.split(",")[1]) if args.pair else 5)
+        elif args.dropout > 0.0:
             fwd, bwd = 1, 1
         elif args.pair:
             fwd, bwd = (int(v) for v in args.pair.split(","))
@@ -144,6 +153,8 @@ def main():
         if args.vera:
             ws_bytes = max(rl.runlora_vera_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code),
                            rl.runlora_vera_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code))
+        if args.dora:
+            ws_bytes = max(ws_bytes, rl.runlora_dora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code))
         ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
         state.append(dict(L=L, sets=sets, pair=(fwd, bwd), ws=ws))
 
@@ -152,6 +163,11 @@ def main():
             t = st["sets"][k % args.sets]
             fwd, bwd = (0, 0) if default_chain else st["pair"]
             saved = rl.new_saved(t["T"] if fwd == 0 else None, t["M"] if fwd == 2 and bwd in rl.BWD_MERGED else None)
+            if args.dora and not default_chain:
+                rl.runlora_dora_forward(fwd, t["X"], t["W"], t["A"], t["B"], t["m"], t["Y"], saved, t["c"], st["ws"])
+                rl.runlora_dora_backward(bwd, t["dY"], saved, t["W"], t["A"], t["B"], t["m"], t["c"], t["Y"], t["dX"], t["dA"],
+                                         t["dB"], t["dm"], st["ws"])
+                continue
             if args.vera:
                 rl.runlora_vera_forward(fwd, t["X"], t["W"], t["A"], t["B"], t["d"], t["b"], t["Y"], saved, st["ws"])
                 rl.runlora_vera_backward(bwd, t["dY"], saved, t["W"], t["A"], t["B"], t["d"], t["b"], t["dX"], t["dd"],
@@ -281,7 +297,7 @@ def main():
         "config": {"workload": wl_name, "layers": [dict(name=L.name, n=L.n, d_in=L.i, d_out=L.o, r=L.r) for L in layers],
                    "pairs": {st["L"].name: list(st["pair"]) for st in state}, "input_sets": args.sets,
                    "keep_merged": bool(args.keep_merged), "lora_dropout": args.dropout,
-                   "adapter": "vera" if args.vera else "lora"},
+                   "adapter": "vera" if args.vera else ("dora" if args.dora else "lora")},
         "ms_per_step_default_chain": round(sec_def * 1e3, 4),
         "speedup_over_default_chain": round(sec_def / sec_sel, 4),
         "time_reduction_pct": round(100.0 * (sec_def - sec_sel) / sec_def, 2),

@@ -228,6 +228,77 @@ class RunVeRALinear(nn.Module):
         return f"d_in={self.d_in}, d_out={self.d_out}, r={self.r}, scale={self.scale:g}, bias={self.bias is not None}"
 
 
+class RunDoRAFunction(torch.autograd.Function):
+    """y = x ((W + scale A B) diag(m / c)) + bias, c the column norms of W + scale A B held constant in the backward
+    pass; gradients for x, A, B and m (runlora_dora_forward / runlora_dora_backward: forward2 and one of the merged
+    backward graphs, the merge kernel scaling W's columns on the way)."""
+
+    @staticmethod
+    def forward(ctx, x, W, A, B, m, bias, scale, bwd):
+        i, o = W.shape
+        r = A.shape[1]
+        x2 = x.reshape(-1, i)
+        if x2.stride(-1) != 1 or x2.stride(0) % 8 != 0 or x2.data_ptr() % 16 != 0:
+            x2 = x2.contiguous()
+        n = x2.shape[0]
+        code = rl.dtype_code(x.dtype)
+        y = torch.empty((n, o), dtype=x.dtype, device=x.device)
+        c = torch.empty((o,), dtype=torch.float32, device=x.device)
+        saved = rl.new_saved(None)
+        ws = _workspace(x.device, rl.runlora_dora_workspace_bytes(rl.FWD2, bwd, n, i, o, r, code))
+        rl.runlora_dora_forward(rl.FWD2, x2, W, A, B, m, y, saved, c, ws, scale=scale, bias=bias)
+        ctx.saved = saved
+        ctx.bwd = bwd
+        ctx.bias = bias
+        ctx.x_shape = x.shape
+        ctx.save_for_backward(x2, W, A, B, m, c, y)  # y is the tensor handed to the caller: no copy is kept
+        return y.view(*x.shape[:-1], o)
+
+    @staticmethod
+    def backward(ctx, dy):
+        x2, W, A, B, m, c, y = ctx.saved_tensors
+        i, o = W.shape
+        r = A.shape[1]
+        n = x2.shape[0]
+        dy2 = dy.reshape(n, o)
+        if dy2.stride(-1) != 1 or dy2.stride(0) % 8 != 0 or dy2.data_ptr() % 16 != 0:
+            dy2 = dy2.contiguous()
+        need = ctx.needs_input_grad
+        dx = torch.empty((n, i), dtype=x2.dtype, device=x2.device) if need[0] else None
+        dA = torch.empty_like(A) if need[2] else None
+        dB = torch.empty_like(B) if need[3] else None
+        dm = torch.empty_like(m) if need[4] else None
+        code = rl.dtype_code(dy.dtype)
+        ws = _workspace(dy.device, rl.runlora_dora_workspace_bytes(-1, ctx.bwd, n, i, o, r, code))
+        rl.runlora_dora_backward(ctx.bwd, dy2, ctx.saved, W, A, B, m, c, y, dx, dA, dB, dm, ws, bias=ctx.bias)
+        if dx is not None:
+            dx = dx.view(ctx.x_shape)
+        return dx, None, dA, dB, dm, None, None, None
+
+
+class RunDoRALinear(nn.Module):
+    """DoRA layer: frozen W [d_in, d_out] (+ bias), trainable A [d_in, r], B [r, d_out] (B starts at 0) and
+    magnitudes m [d_out], which start at the column norms of W so that the layer starts as the frozen one.
+    16-bit dtypes, r <= 128.  bwd: the merged backward graph (4, 5, 7 or 8)."""
+
+    def __init__(self, weight, r, alpha=None, bias=None, bwd=5):
+        super().__init__()
+        d_in, d_out = weight.shape
+        self.d_in, self.d_out, self.r, self.bwd = d_in, d_out, r, bwd
+        self.scale = float(alpha) / r if alpha is not None else 1.0
+        self.weight = nn.Parameter(weight.contiguous(), requires_grad=False)
+        self.bias = nn.Parameter(bias.contiguous(), requires_grad=False) if bias is not None else None
+        self.lora_A = nn.Parameter(torch.randn(d_in, r, dtype=weight.dtype, device=weight.device) / math.sqrt(d_in))
+        self.lora_B = nn.Parameter(torch.zeros(r, d_out, dtype=weight.dtype, device=weight.device))
+        self.dora_m = nn.Parameter(weight.float().norm(dim=0).to(weight.dtype))
+
+    def forward(self, x):
+        return RunDoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.dora_m, self.bias, self.scale, self.bwd)
+
+    def extra_repr(self):
+        return f"d_in={self.d_in}, d_out={self.d_out}, r={self.r}, scale={self.scale:g}, bias={self.bias is not None}"
+
+
 def wrap_linears(model, r, alpha=None, targets=None, pair=None, keep_merged=False, dropout=0.0):
     """Replace nn.Linear submodules of `model` by RunLoRALinear (all of them, or those whose attribute
     name is in `targets`); every other parameter of the model is frozen.  Returns the replaced names."""

@@ -217,3 +217,37 @@ def test_vera_module_matches_oracle_and_shares_frozen_factors():
     # a fresh layer (b = 0) is the frozen linear layer
     y0 = other(x.detach())
     assert relerr(to_f64(y0.reshape(-1, d_out)), host["X"] @ host["W"]) < TOL["bf16"]
+
+
+def test_dora_module_matches_oracle_and_starts_as_the_frozen_layer():
+    """RunDoRALinear through autograd: output and the gradients of x, A, B and m against the oracle's DoRA layer
+    (column norm held constant in the backward pass); a fresh layer (B = 0, m = ||W||) is the frozen linear layer."""
+    import torch
+    from paper_2312_03415_amd.module import RunDoRALinear
+    n, d_in, d_out, r = 150, 136, 264, 16
+    L = synth.Layer("doramod", n, d_in, d_out, r, "bf16", 57)
+    st = synth.layer_inputs(L)
+    host = {k: synth.widen(v, "bf16") for k, v in st.items()}
+    mvec = synth.store(0.5 + np.abs(synth.normal(57, 10, (d_out,))), "bf16")
+    bias = synth.store(synth.normal(57, 9, (d_out,)), "bf16")
+    layer = RunDoRALinear(to_device(st["W"], "bf16"), r, alpha=8.0, bias=to_device(bias, "bf16"))
+    assert sorted(k for k, p in layer.named_parameters() if p.requires_grad) == ["dora_m", "lora_A", "lora_B"]
+    x = to_device(st["X"], "bf16").view(3, 50, d_in).requires_grad_(True)
+    y0 = layer(x.detach())
+    torch.cuda.synchronize()
+    assert relerr(to_f64(y0.reshape(-1, d_out)), host["X"] @ host["W"] + synth.widen(bias, "bf16")[None, :]) < TOL["bf16"]
+    with torch.no_grad():
+        layer.lora_A.copy_(to_device(st["A"], "bf16"))
+        layer.lora_B.copy_(to_device(st["B"], "bf16"))
+        layer.dora_m.copy_(to_device(mvec, "bf16"))
+    y = layer(x)
+    y.backward(to_device(st["dY"], "bf16").view(3, 50, d_out))
+    torch.cuda.synchronize()
+    m64, b64 = synth.widen(mvec, "bf16"), synth.widen(bias, "bf16")
+    args = (host["X"], host["W"], host["A"], host["B"], m64)
+    Yw = oracle.dora_forward(*args, 0.5, b64)
+    dXw, dAw, dBw, dmw = oracle.dora_backward(*args, host["dY"], 0.5)
+    assert relerr(to_f64(y.reshape(-1, d_out)), Yw) < TOL["bf16"]
+    assert relerr(to_f64(x.grad.reshape(-1, d_in)), dXw) < TOL["bf16"]
+    assert relerr(to_f64(layer.lora_A.grad), dAw) < TOL["bf16"] and relerr(to_f64(layer.lora_B.grad), dBw) < TOL["bf16"]
+    assert relerr(to_f64(layer.dora_m.grad), dmw) < TOL["bf16"]
