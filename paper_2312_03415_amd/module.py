@@ -279,9 +279,10 @@ class RunDoRAFunction(torch.autograd.Function):
 class RunDoRALinear(nn.Module):
     """DoRA layer: frozen W [d_in, d_out] (+ bias), trainable A [d_in, r], B [r, d_out] (B starts at 0) and
     magnitudes m [d_out], which start at the column norms of W so that the layer starts as the frozen one.
-    16-bit dtypes, r <= 128.  bwd: the merged backward graph (4, 5, 7 or 8)."""
+    16-bit dtypes, r <= 128.  bwd: the merged backward graph (4, 5, 7 or 8); None = the one of the four with the
+    smallest modelled time for the token count of the call (the time model of runlora_select)."""
 
-    def __init__(self, weight, r, alpha=None, bias=None, bwd=5):
+    def __init__(self, weight, r, alpha=None, bias=None, bwd=None):
         super().__init__()
         d_in, d_out = weight.shape
         self.d_in, self.d_out, self.r, self.bwd = d_in, d_out, r, bwd
@@ -291,9 +292,21 @@ class RunDoRALinear(nn.Module):
         self.lora_A = nn.Parameter(torch.randn(d_in, r, dtype=weight.dtype, device=weight.device) / math.sqrt(d_in))
         self.lora_B = nn.Parameter(torch.zeros(r, d_out, dtype=weight.dtype, device=weight.device))
         self.dora_m = nn.Parameter(weight.float().norm(dim=0).to(weight.dtype))
+        self._bwds = {}
+
+    def bwd_for(self, n_tokens):
+        if self.bwd is not None:
+            return self.bwd
+        b = self._bwds.get(n_tokens)
+        if b is None:
+            code = rl.dtype_code(self.weight.dtype)
+            b = min((4, 5, 7, 8), key=lambda v: rl.runlora_model_time_us(1, v, n_tokens, self.d_in, self.d_out, self.r, code))
+            self._bwds[n_tokens] = b
+        return b
 
     def forward(self, x):
-        return RunDoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.dora_m, self.bias, self.scale, self.bwd)
+        return RunDoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.dora_m, self.bias, self.scale,
+                                     self.bwd_for(x.numel() // self.d_in))
 
     def extra_repr(self):
         return f"d_in={self.d_in}, d_out={self.d_out}, r={self.r}, scale={self.scale:g}, bias={self.bias is not None}"
