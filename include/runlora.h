@@ -350,7 +350,11 @@ size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g);
  * launch order (up to cap), forgets them, and returns how many it wrote (or a negative status).
  * `what` points to a static string naming the product in the paper's notation; flops = 2*M*N*K of
  * that product; bytes = one read of each operand plus the output (and addend) in the storage
- * dtype.  Events are host objects created at enable and destroyed at disable; no device memory.
+ * dtype.  us is the time between the two events around the step (all of its kernels, e.g. a split
+ * contraction's reduce pass, plus a few microseconds of event handling); kernel_us is the duration of
+ * the step's main kernel alone (the tile GEMM, the streaming kernel or the merge kernel), taken from
+ * events bound to that kernel's own dispatch: the figure a kernel trace reports for it.
+ * Events are host objects created at enable and destroyed at disable; no device memory.
  */
 typedef struct {
   const char* what;
@@ -358,6 +362,7 @@ typedef struct {
   double flops, bytes;
   int64_t M, N, K;
   int32_t tile_cfg, splits, a_strided, b_kcontig;
+  double kernel_us;
 } rl_step_time_t;
 int runlora_profile_enable(int max_steps);
 int runlora_profile_collect(rl_step_time_t* out, int cap);

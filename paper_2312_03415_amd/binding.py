@@ -74,7 +74,7 @@ class rl_step_time_t(ctypes.Structure):
     _fields_ = [("what", ctypes.c_char_p), ("us", ctypes.c_double), ("flops", ctypes.c_double),
                 ("bytes", ctypes.c_double), ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
                 ("tile_cfg", ctypes.c_int32), ("splits", ctypes.c_int32), ("a_strided", ctypes.c_int32),
-                ("b_kcontig", ctypes.c_int32)]
+                ("b_kcontig", ctypes.c_int32), ("kernel_us", ctypes.c_double)]
 
 
 class RunLoRAError(RuntimeError):
@@ -386,7 +386,7 @@ def runlora_profile_collect(cap=4096):
     k = lib().runlora_profile_collect(buf, cap)
     if k < 0:
         _check(k)
-    keys = ("us", "flops", "bytes", "M", "N", "K", "tile_cfg", "splits", "a_strided", "b_kcontig")
+    keys = ("us", "kernel_us", "flops", "bytes", "M", "N", "K", "tile_cfg", "splits", "a_strided", "b_kcontig")
     return [dict(what=buf[j].what.decode(), **{f: getattr(buf[j], f) for f in keys}) for j in range(k)]
 
 

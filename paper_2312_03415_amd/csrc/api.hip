@@ -98,7 +98,9 @@ Mat weight_mat(const rl_tensor_t* W, int64_t o, bool int4) {
 // optional per-step event timing (runlora_profile_*), one recorder per host thread
 struct Profiler {
   bool on = false;
-  std::vector<hipEvent_t> start, stop;
+  std::vector<hipEvent_t> start, stop;    // around the whole step
+  std::vector<hipEvent_t> kstart, kstop;  // bound to the step's main kernel (launch_main, gemm.hpp)
+  std::vector<char> kbound;
   std::vector<rl_step_time_t> rec;
   size_t used = 0;
 };
@@ -109,6 +111,7 @@ void describe_step(const Step& s, rl_step_time_t* r) {
     const double e = (double)dtype_size(s.d.dtype);
     r->what = s.what;
     r->us = 0.0;
+    r->kernel_us = 0.0;
     r->flops = 2.0 * (double)s.mg.I * (double)s.mg.O * (double)s.mg.R;
     r->bytes = e * (2.0 * (double)s.mg.I * (double)s.mg.O + (double)s.mg.R * (double)(s.mg.I + s.mg.O));
     r->M = s.mg.I; r->N = s.mg.O; r->K = s.mg.R;
@@ -121,6 +124,7 @@ void describe_step(const Step& s, rl_step_time_t* r) {
     const double e = (double)dtype_size(s.d.dtype);
     r->what = s.what;
     r->us = 0.0;
+    r->kernel_us = 0.0;
     r->flops = 0.0;
     r->bytes = 0.0;
     for (int w = 0; w < s.nsk; ++w) {
@@ -139,6 +143,7 @@ void describe_step(const Step& s, rl_step_time_t* r) {
   const double e = (double)dtype_size(d.dtype);
   r->what = s.what;
   r->us = 0.0;
+  r->kernel_us = 0.0;
   r->flops = 2.0 * (double)d.M * (double)d.N * K;
   r->bytes = e * ((double)d.M * K + K * (double)d.N + (double)d.M * (double)d.N * (d.D ? 2.0 : 1.0));
   r->M = d.M; r->N = d.N; r->K = (int64_t)K;
@@ -146,14 +151,14 @@ void describe_step(const Step& s, rl_step_time_t* r) {
   r->a_strided = d.a_strided; r->b_kcontig = d.b_kcontig;
 }
 
-// While set, the layer calls check their arguments and build their schedule but enqueue nothing: an
-// entry point built on top of them validates everything this way before its own first launch.
 // set by the DoRA entry points around their inner layer call: the frozen weight is W diag(g_wcol)
 thread_local const float* g_wcol = nullptr;
 struct WCol {
   explicit WCol(const float* g) { g_wcol = g; }
   ~WCol() { g_wcol = nullptr; }
 };
+// While set, the layer calls check their arguments and build their schedule but enqueue nothing: an
+// entry point built on top of them validates everything this way before its own first launch.
 thread_local bool g_dry_run = false;
 struct DryRun {
   DryRun() { g_dry_run = true; }
@@ -168,12 +173,16 @@ int run_schedule(const Schedule& sch, char* ws, hipStream_t stream) {
     if (timed) {
       hipError_t e = hipEventRecord(g_prof.start[g_prof.used], stream);
       if (e != hipSuccess) return set_hip_error(e, "profile event");
+      g_kernel_events = KernelEvents{g_prof.kstart[g_prof.used], g_prof.kstop[g_prof.used]};
     }
     hipError_t e = s.is_merge ? merge_run(s.d.dtype, s.mg, stream)
                    : s.nsk > 0 ? skinny_run(s.d.dtype, s.nsk, s.sk, s.skplan, partial, stream)
                                : gemm_run(s.d, s.plan, partial, stream);
+    const bool kbound = timed && g_kernel_events.start == nullptr;  // consumed by the step's main launch
+    g_kernel_events = KernelEvents{};
     if (e != hipSuccess) return set_hip_error(e, s.what);
     if (timed) {
+      g_prof.kbound[g_prof.used] = kbound ? 1 : 0;
       e = hipEventRecord(g_prof.stop[g_prof.used], stream);
       if (e != hipSuccess) return set_hip_error(e, "profile event");
       describe_step(s, &g_prof.rec[g_prof.used]);
@@ -815,8 +824,13 @@ extern "C" int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts) {
 extern "C" int runlora_profile_disable(void) {
   for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
   for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
+  for (hipEvent_t e : g_prof.kstart) (void)hipEventDestroy(e);
+  for (hipEvent_t e : g_prof.kstop) (void)hipEventDestroy(e);
   g_prof.start.clear();
   g_prof.stop.clear();
+  g_prof.kstart.clear();
+  g_prof.kstop.clear();
+  g_prof.kbound.clear();
   g_prof.rec.clear();
   g_prof.used = 0;
   g_prof.on = false;
@@ -829,12 +843,19 @@ extern "C" int runlora_profile_enable(int max_steps) {
   g_prof.start.resize(max_steps);
   g_prof.stop.resize(max_steps);
   g_prof.rec.resize(max_steps);
+  g_prof.kstart.assign(max_steps, nullptr);
+  g_prof.kstop.assign(max_steps, nullptr);
+  g_prof.kbound.assign(max_steps, 0);
   for (int k = 0; k < max_steps; ++k) {
     hipError_t e = hipEventCreate(&g_prof.start[k]);
     if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[k]);
+    if (e == hipSuccess) e = hipEventCreate(&g_prof.kstart[k]);
+    if (e == hipSuccess) e = hipEventCreate(&g_prof.kstop[k]);
     if (e != hipSuccess) {
       g_prof.start.resize(k);
       g_prof.stop.resize(k);
+      g_prof.kstart.resize(k);
+      g_prof.kstop.resize(k);
       runlora_profile_disable();
       return set_hip_error(e, "hipEventCreate");
     }
@@ -851,6 +872,8 @@ extern "C" int runlora_profile_collect(rl_step_time_t* out, int cap) {
     hipError_t e = hipEventSynchronize(g_prof.stop[k]);
     float ms = 0.f;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.start[k], g_prof.stop[k]);
+    float kms = ms;
+    if (e == hipSuccess && g_prof.kbound[k]) e = hipEventElapsedTime(&kms, g_prof.kstart[k], g_prof.kstop[k]);
     if (e != hipSuccess) {
       g_prof.used = 0;
       return set_hip_error(e, "profile collect");
@@ -858,6 +881,7 @@ extern "C" int runlora_profile_collect(rl_step_time_t* out, int cap) {
     if (written < cap) {
       out[written] = g_prof.rec[k];
       out[written].us = (double)ms * 1e3;
+      out[written].kernel_us = (double)kms * 1e3;
       ++written;
     }
   }

@@ -2,6 +2,7 @@
 // (tile shape + split of the contraction) and launch.  Internal to the library.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -97,6 +98,23 @@ struct SkinnyArgs;
 hipError_t skinny_launch_bf16(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
 hipError_t skinny_launch_f16(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
 hipError_t skinny_launch_f32(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
+
+// ---- timing of a step's main kernel ------------------------------------------------------------------
+// While a pair of events is set here (per host thread), the next main kernel launched from this thread (the
+// tile GEMM, the streaming kernel, the merge kernel; not the reduce kernels behind them) is launched with
+// them bound to its own dispatch, so that their difference is that kernel's duration alone, as a kernel
+// trace reports it; the pair is consumed (cleared) by that launch.
+struct KernelEvents { hipEvent_t start = nullptr, stop = nullptr; };
+extern thread_local KernelEvents g_kernel_events;
+template <typename Kern, typename... Args>
+inline void launch_main(Kern kern, dim3 grid, dim3 block, unsigned lds, hipStream_t s, Args... args) {
+  if (g_kernel_events.start != nullptr) {
+    hipExtLaunchKernelGGL(kern, grid, block, lds, s, g_kernel_events.start, g_kernel_events.stop, 0, args...);
+    g_kernel_events = KernelEvents{};
+  } else {
+    hipLaunchKernelGGL(kern, grid, block, lds, s, args...);
+  }
+}
 
 // ---- M = W + A B (merge.hpp): 16-bit types, r <= 128 --------------------------------------------
 struct MergeDesc {

@@ -6,6 +6,8 @@
 
 namespace rl {
 
+thread_local KernelEvents g_kernel_events;
+
 static const int kTileBM[CFG_COUNT] = {256, 128, 128, 128, 32, 64, 256, 256};
 static const int kTileBN[CFG_COUNT] = {256, 128, 32, 64, 128, 128, 256, 256};
 static const int kTileBK16[CFG_COUNT] = {64, 64, 64, 64, 64, 64, 32, 32};  // K tile, 16-bit types
