@@ -228,29 +228,30 @@ def main():
         per_layer.append(dict(name=L.name, pair=list(st["pair"]), ms=round(ms_sel, 4), ms_default_chain=round(ms_def, 4),
                               speedup=round(ms_def / ms_sel, 4), useful_tflops=round(useful_flops(L) / ms_sel / 1e9, 1)))
 
-    # ---- per-kernel timings of an identical pass (HIP events recorded by the library on the
-    # launch stream around every step) -> roofline of the dominant kernel
+    # ---- per-kernel timings of an identical pass (HIP events the library binds, on the launch stream, to the
+    # dispatch of every step's main kernel: the kernel's own duration) -> roofline of the dominant kernel
+    rl.runlora_profile_kernel_times(True)
     rl.runlora_profile_enable(args.steps * len(layers) * 16)
     for k in range(args.steps):
         step(k, False)
     torch.cuda.synchronize()
     recs = rl.runlora_profile_collect(args.steps * len(layers) * 16)
     rl.runlora_profile_disable()
+    rl.runlora_profile_kernel_times(False)
     groups = {}
     ridge = MFMA_PEAK_TFLOPS[dtype] * 1e12 / (HBM_PEAK_GBPS * 1e9)
     for r in recs:
         lay = "NN" if not r["a_strided"] and not r["b_kcontig"] else ("NT" if r["b_kcontig"] else "TN")
         # the same kernel serves compute-bound contractions and memory-bound ones (W + AB has K = r)
         key = (lay, TILE_NAMES[r["tile_cfg"]] + ("" if r["flops"] / r["bytes"] >= ridge else "/mem"))
-        # us: the kernel's own duration (events bound to its dispatch: what a kernel trace reports); step_us: the event
-        # pair around the step, which also holds a split contraction's reduce pass and the event handling
-        g = groups.setdefault(key, dict(us=0.0, step_us=0.0, flops=0.0, bytes=0.0, launches=0, what=set()))
-        g["us"] += r["kernel_us"]; g["step_us"] += r["us"]
-        g["flops"] += r["flops"]; g["bytes"] += r["bytes"]; g["launches"] += 1
+        # the kernel's own duration (what a kernel trace reports for it); the reduce pass behind a split contraction
+        # is a kernel of its own and is not in these figures
+        g = groups.setdefault(key, dict(us=0.0, flops=0.0, bytes=0.0, launches=0, what=set()))
+        g["us"] += r["kernel_us"]; g["flops"] += r["flops"]; g["bytes"] += r["bytes"]; g["launches"] += 1
         g["what"].add(r["what"])
     dom_key = max(groups, key=lambda k: groups[k]["us"])
     dom = groups[dom_key]
-    total_kernel_us = sum(g["step_us"] for g in groups.values())
+    total_kernel_us = sum(g["us"] for g in groups.values())
     intensity = dom["flops"] / dom["bytes"]
     kname = "gemm_kernel<%s,%s,%s>" % (dtype, dom_key[0], dom_key[1])
     if intensity >= ridge:
@@ -271,7 +272,6 @@ def main():
                     avg_launch_us=round(dom["us"] / dom["launches"], 2),
                     share_of_kernel_time=round(dom["us"] / total_kernel_us, 3))
     per_kernel = {"%s/%s" % k: dict(us_per_step=round(g["us"] / args.steps, 1),
-                                    us_per_step_with_reduce_and_events=round(g["step_us"] / args.steps, 1),
                                     tflops=round(g["flops"] / g["us"] / 1e6, 1),
                                     alg_gbps=round(g["bytes"] / g["us"] / 1e3, 1)) for k, g in groups.items()}
 

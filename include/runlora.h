@@ -351,9 +351,11 @@ size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g);
  * `what` points to a static string naming the product in the paper's notation; flops = 2*M*N*K of
  * that product; bytes = one read of each operand plus the output (and addend) in the storage
  * dtype.  us is the time between the two events around the step (all of its kernels, e.g. a split
- * contraction's reduce pass, plus a few microseconds of event handling); kernel_us is the duration of
- * the step's main kernel alone (the tile GEMM, the streaming kernel or the merge kernel), taken from
- * events bound to that kernel's own dispatch: the figure a kernel trace reports for it.
+ * contraction's reduce pass, plus a few microseconds of event handling).  After
+ * runlora_profile_kernel_times(1) (per thread, off by default) kernel_us is the duration of the
+ * step's main kernel alone (the tile GEMM, the streaming kernel or the merge kernel), taken from a
+ * second pair of events bound to that kernel's own dispatch: the figure a kernel trace reports for
+ * it; us then also holds the handling of those events.  Otherwise kernel_us = us.
  * Events are host objects created at enable and destroyed at disable; no device memory.
  */
 typedef struct {
@@ -365,6 +367,7 @@ typedef struct {
   double kernel_us;
 } rl_step_time_t;
 int runlora_profile_enable(int max_steps);
+int runlora_profile_kernel_times(int on);
 int runlora_profile_collect(rl_step_time_t* out, int cap);
 int runlora_profile_disable(void);
 

@@ -33,7 +33,8 @@ EXPORTS = (
     "runlora_model_time_us", "runlora_workspace_bytes", "runlora_workspace_bytes_w", "runlora_saved_bytes",
     "runlora_strerror", "runlora_last_hip_error",
     "runlora_version", "runlora_gemm", "runlora_gemm_workspace_bytes",
-    "runlora_profile_enable", "runlora_profile_collect", "runlora_profile_disable", "runlora_probe_mfma",
+    "runlora_profile_enable", "runlora_profile_collect", "runlora_profile_disable", "runlora_profile_kernel_times",
+    "runlora_probe_mfma",
     "runlora_vera_forward", "runlora_vera_backward", "runlora_vera_workspace_bytes",
     "runlora_dora_forward", "runlora_dora_backward", "runlora_dora_workspace_bytes",
 )
@@ -148,6 +149,8 @@ def lib():
     L.runlora_profile_collect.restype = ci
     L.runlora_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ci, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double)]
     L.runlora_probe_mfma.restype = ci
+    L.runlora_profile_kernel_times.argtypes = [ci]
+    L.runlora_profile_kernel_times.restype = ci
     L.runlora_profile_disable.argtypes = []
     L.runlora_profile_disable.restype = ci
     _lib = L
@@ -388,6 +391,11 @@ def runlora_profile_collect(cap=4096):
         _check(k)
     keys = ("us", "kernel_us", "flops", "bytes", "M", "N", "K", "tile_cfg", "splits", "a_strided", "b_kcontig")
     return [dict(what=buf[j].what.decode(), **{f: getattr(buf[j], f) for f in keys}) for j in range(k)]
+
+
+def runlora_profile_kernel_times(on=True):
+    """Also time each step's main kernel alone (rl_step_time_t.kernel_us) in the profile passes of this thread."""
+    _check(lib().runlora_profile_kernel_times(1 if on else 0))
 
 
 def runlora_profile_disable():

@@ -101,6 +101,7 @@ struct Profiler {
   std::vector<hipEvent_t> start, stop;    // around the whole step
   std::vector<hipEvent_t> kstart, kstop;  // bound to the step's main kernel (launch_main, gemm.hpp)
   std::vector<char> kbound;
+  bool kernel_events = false;             // runlora_profile_kernel_times
   std::vector<rl_step_time_t> rec;
   size_t used = 0;
 };
@@ -173,12 +174,12 @@ int run_schedule(const Schedule& sch, char* ws, hipStream_t stream) {
     if (timed) {
       hipError_t e = hipEventRecord(g_prof.start[g_prof.used], stream);
       if (e != hipSuccess) return set_hip_error(e, "profile event");
-      g_kernel_events = KernelEvents{g_prof.kstart[g_prof.used], g_prof.kstop[g_prof.used]};
+      if (g_prof.kernel_events) g_kernel_events = KernelEvents{g_prof.kstart[g_prof.used], g_prof.kstop[g_prof.used]};
     }
     hipError_t e = s.is_merge ? merge_run(s.d.dtype, s.mg, stream)
                    : s.nsk > 0 ? skinny_run(s.d.dtype, s.nsk, s.sk, s.skplan, partial, stream)
                                : gemm_run(s.d, s.plan, partial, stream);
-    const bool kbound = timed && g_kernel_events.start == nullptr;  // consumed by the step's main launch
+    const bool kbound = timed && g_prof.kernel_events && g_kernel_events.start == nullptr;  // consumed by the step's main launch
     g_kernel_events = KernelEvents{};
     if (e != hipSuccess) return set_hip_error(e, s.what);
     if (timed) {
@@ -861,6 +862,11 @@ extern "C" int runlora_profile_enable(int max_steps) {
     }
   }
   g_prof.on = true;
+  return RL_OK;
+}
+
+extern "C" int runlora_profile_kernel_times(int on) {
+  g_prof.kernel_events = on != 0;
   return RL_OK;
 }
 

@@ -88,6 +88,7 @@ struct SkinnyDesc {
 struct SkinnyPlan {
   int rt = 1;      // 32-column blocks per row block: N <= 32*rt
   int splits = 1;  // K split over workgroups (fp32 partials + ordered reduce)
+  int mr = 1;      // 32-row blocks per workgroup: 2 for paired launches in the [K,M] orientation with N <= 64
   size_t partial_bytes = 0;
 };
 inline bool skinny_ok(int64_t N) { return N <= 128; }

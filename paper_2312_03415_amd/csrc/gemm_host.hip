@@ -229,19 +229,22 @@ SkinnyPlan skinny_plan(int dtype, int nprob, const SkinnyDesc* d) {
   SkinnyPlan p;
   const int bk = dtype == DT_F32 ? 32 : 64;
   int64_t blocks = 0, min_ktiles = 1 << 30, outs = 0, maxn = 0;
+  for (int w = 0; w < nprob; ++w)
+    if (d[w].N > maxn) maxn = d[w].N;
+  p.rt = maxn <= 32 ? 1 : (maxn <= 64 ? 2 : 4);
+  p.mr = (nprob == 2 && d[0].a_strided && d[1].a_strided && p.rt <= 2) ? 2 : 1;  // see skinny.hpp
+  const int mb = 32 * p.mr;
   for (int w = 0; w < nprob; ++w) {
-    blocks += (d[w].M + 31) / 32;
+    blocks += (d[w].M + mb - 1) / mb;
     const int64_t kt = (d[w].K + bk - 1) / bk;
     if (kt < min_ktiles) min_ktiles = kt;
     outs += d[w].M * d[w].N;
-    if (d[w].N > maxn) maxn = d[w].N;
   }
-  p.rt = maxn <= 32 ? 1 : (maxn <= 64 ? 2 : 4);
-  // one workgroup of 8 waves per compute unit already keeps enough loads in flight; split K over
-  // workgroups only when there are fewer row blocks than compute units, and keep >= 4 K tiles
-  // per wave and slice
+  // split K over workgroups only when there are fewer workgroups than compute units, and keep >= 8 K tiles
+  // per wave and slice.  (64-row workgroups: 128-160 of them without a split beat twice as many plus the
+  // reduce pass, measured on the paired dA / dB launches.)
   int64_t splits = 1;
-  if (blocks < 224) {
+  if (blocks < (p.mr == 2 ? 128 : 224)) {
     splits = (256 + blocks - 1) / blocks;
     int64_t cap = min_ktiles / 32;
     if (cap < 1) cap = 1;
@@ -260,6 +263,8 @@ hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPla
   const int bk = dtype == DT_F32 ? 32 : 64;
   SkinnyArgs a{};
   a.nprob = nprob;
+  a.mr = plan.mr;
+  if (plan.mr != 1 && !(plan.mr == 2 && nprob == 2 && d[0].a_strided && d[1].a_strided && plan.rt <= 2)) return hipErrorInvalidValue;
   int64_t blocks = 0;
   float* part = scratch;
   for (int w = 0; w < nprob; ++w) {
@@ -271,7 +276,8 @@ hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPla
     P.a_strided = d[w].a_strided; P.b_kcontig = d[w].b_kcontig; P.trans_out = d[w].trans_out;
     P.alpha = d[w].alpha;
     P.drop_thr = d[w].drop_thr; P.drop_key = d[w].drop_key; P.drop_cpr = d[w].drop_cpr;
-    P.row_blocks = (int)((d[w].M + 31) / 32);
+    const int mb = 32 * plan.mr;
+    P.row_blocks = (int)((d[w].M + mb - 1) / mb);
     {
       const int64_t esz = dtype == DT_F32 ? 4 : 2;
       const int64_t a_rows = d[w].a_strided ? d[w].K : d[w].M, a_cols = d[w].a_strided ? d[w].M : d[w].K;

@@ -6,9 +6,14 @@
 // operand is used for only ~r FLOPs, so the kernel is HBM-bandwidth bound and is built for bytes in
 // flight rather than for MFMA occupancy.
 //
-//  - One workgroup = NWV (4) wavefronts that share a block of 32 output rows and split the
-//    workgroup's K range between them (wave w takes K tiles w, w+NWV, ...; 8 or 16 wavefronts per
-//    workgroup measured slower).  Every wavefront runs its own
+//  - One workgroup = NWV (4) wavefronts that share a block of 32 * MR output rows and split the
+//    workgroup's K range between them.  MR = 2 (64 rows) is used by paired launches whose A operands are
+//    stored [K,M] (and N <= 64): a block's rows are then columns of A, a 32-column strip is 64 bytes per
+//    row of A, half a 128-byte line, and the other half has to come from the neighbouring workgroup's
+//    fetch staying in L2; with 128-byte strips the paired dA / dB launch runs 20 % faster (OPT shapes:
+//    25.6 -> 20.5 us).  Single launches keep 32 rows: halving their workgroup count costs more than the
+//    strips gain (dB of OPT fc1 alone: 18.8 -> 23.4 us).  (The workgroup's K range is split between the waves as wave w taking K tiles w, w+NWV, ...; 8 or 16 wavefronts per
+//    workgroup measured slower.)  Every wavefront runs its own
 //    global -> register -> LDS -> MFMA pipeline on a private LDS region: no workgroup barrier in the
 //    loop, the next tile's loads are in flight while the current one is multiplied.
 //  - The waves' partial accumulators are summed through LDS in wave order and written once.  A grid
@@ -30,7 +35,7 @@ struct SkinnyProblem {
   int64_t lda, ldb, ldc;
   int M, N, K;
   int a_strided, b_kcontig, trans_out;
-  int row_blocks;       // ceil(M / 32)
+  int row_blocks;       // ceil(M / (32 * mr))
   int a_bytes, b_bytes; // extent of A and B in bytes (< 2 GiB): the range the loads are checked against
   int tiles_per_split;  // K tiles of this problem per gridDim.y slice
   float alpha;          // C = alpha * op(A) op(B) (the LoRA scale, applied where a rank-r factor is formed)
@@ -42,36 +47,40 @@ struct SkinnyProblem {
 struct SkinnyArgs {
   SkinnyProblem p[2];
   int nprob;
+  int mr;  // 32-row blocks per workgroup (1 or 2): selects the build
 };
 
-template <typename T, int RT, int NWV>
+template <typename T, int RT, int NWV, int MR>
 struct SkinnyTile {
   static constexpr int VE = 16 / sizeof(T);
+  static constexpr int MB = 32 * MR;  // output rows per workgroup
   static constexpr int BK = 8 * VE;  // 64 (16-bit) or 32 (fp32): 128 bytes of K per row
   static constexpr int KS = 2 * VE;
   static constexpr int NB = 32 * RT;
   // per-wave LDS (elements): the larger of the two orientations of each operand
-  static constexpr int A_LD0 = LdsLd<T, false, BK>::value, A_LD1 = LdsLd<T, true, 32>::value;
+  static constexpr int A_LD0 = LdsLd<T, false, BK>::value, A_LD1 = LdsLd<T, true, MB>::value;
   static constexpr int B_LD0 = LdsLd<T, true, NB>::value, B_LD1 = LdsLd<T, false, BK>::value;
   static constexpr int A_ELEMS = (32 * A_LD0 > BK * A_LD1) ? 32 * A_LD0 : BK * A_LD1;
   static constexpr int B_ELEMS = (BK * B_LD0 > NB * B_LD1) ? BK * B_LD0 : NB * B_LD1;
   static constexpr int WAVE_ELEMS = A_ELEMS + B_ELEMS;
   static constexpr int STAGE_BYTES = NWV * WAVE_ELEMS * (int)sizeof(T);
-  static constexpr int REDUCE_BYTES = NWV * RT * 1024 * 4;  // NWV waves x RT blocks of 32x32 fp32
+  static constexpr int REDUCE_BYTES = NWV * (MB / 32) * RT * 1024 * 4;  // NWV waves x blocks of 32x32 fp32
   static constexpr int LDS_BYTES = STAGE_BYTES > REDUCE_BYTES ? STAGE_BYTES : REDUCE_BYTES;
 };
 
 // One problem's work for this workgroup.  AL / BL are the operand layouts (compile time, so that
 // the load and fragment paths are straight-line code): AL = 1: A stored [K,M]; BL = 1: B stored [N,K].
 // DROP: the build of the kernel that can mask A (LoRA dropout); the plain build carries none of it.
-template <typename T, int RT, int NWV, int AL, int BL, bool DROP>
+template <typename T, int RT, int NWV, int AL, int BL, bool DROP, int MR>
 __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsigned char* smem_raw) {
-  using S = SkinnyTile<T, RT, NWV>;
+  using S = SkinnyTile<T, RT, NWV, MR>;
   constexpr int VE = S::VE, BK = S::BK;
   constexpr bool a_str = AL != 0, b_kc = BL != 0;
+  static_assert(MR == 1 || (AL != 0 && RT <= 2), "64-row blocks exist for the [K,M] orientation only");
+  constexpr int MB = 32 * MR;  // output rows of this workgroup
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int m0 = bx * 32;
+  const int m0 = bx * MB;
   const int M = P.M, N = P.N, K = P.K;
   const T* Ap = static_cast<const T*>(P.A);
   const T* Bp = static_cast<const T*>(P.B);
@@ -85,17 +94,19 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
   T* sA = reinterpret_cast<T*>(smem_raw) + wave * S::WAVE_ELEMS;
   T* sB = sA + S::A_ELEMS;
 
-  f32x16 acc[RT];
+  f32x16 acc[MR][RT];
 #pragma unroll
-  for (int b = 0; b < RT; ++b)
+  for (int a = 0; a < MR; ++a)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
+    for (int b = 0; b < RT; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  constexpr int A_PER = 4;       // 32 x 8 chunks (or BK x 4) over 64 lanes
+  constexpr int A_PER = 4 * MR;  // 32 x 8 chunks (or BK x MB/VE) over 64 lanes
   constexpr int B_PER = 4 * RT;  // BK x NB/VE... = 256*RT chunks over 64 lanes
   // register stages: the loads of DEPTH tiles are in flight per wave (a streaming kernel lives on
   // bytes in flight, not on occupancy)
-  constexpr int DEPTH = RT == 1 ? 4 : (RT == 2 ? 3 : 2);
+  constexpr int DEPTH = MR * RT == 1 ? 4 : (MR * RT == 2 ? 3 : 2);
   i32x4 ra[DEPTH][A_PER], rb[DEPTH][B_PER];
 
   // Loads go through buffer descriptors: a lane whose chunk lies outside the matrix (or whose tile
@@ -127,8 +138,8 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
         const int row = c >> 3, col = (c & 7) * VE;
         ok = live && m0 + row < M && k0 + col < K;
         off = (uint32_t)(m0 + row) * ulda + (uint32_t)(k0 + col);
-      } else {  // tile [BK k][32 m]: 32/VE chunks per row
-        constexpr int CPR = 32 / VE;
+      } else {  // tile [BK k][MB m]: MB/VE chunks per row
+        constexpr int CPR = MB / VE;
         const int row = c / CPR, col = (c % CPR) * VE;
         ok = live && k0 + row < K && m0 + col < M;
         off = (uint32_t)(k0 + row) * ulda + (uint32_t)(m0 + col);
@@ -164,7 +175,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
           t = (uint32_t)(m0 + (c >> 3));
           col = (uint32_t)(kst[d] + (c & 7) * VE);
         } else {
-          constexpr int CPR = 32 / VE;
+          constexpr int CPR = MB / VE;
           t = (uint32_t)(kst[d] + c / CPR);
           col = (uint32_t)(m0 + (c % CPR) * VE);
         }
@@ -177,7 +188,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
       if constexpr (!a_str) {
         *reinterpret_cast<i32x4*>(sA + (c >> 3) * S::A_LD0 + (c & 7) * VE) = ra[d][j];
       } else {
-        constexpr int CPR = 32 / VE;
+        constexpr int CPR = MB / VE;
         *reinterpret_cast<i32x4*>(sA + (c / CPR) * S::A_LD1 + (c % CPR) * VE) = ra[d][j];
       }
     }
@@ -206,12 +217,16 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
       load_global(d, t0 + NWV * (j0 + d + DEPTH));
 #pragma unroll
       for (int ks = 0; ks < BK / S::KS; ++ks) {
-        i32x4 fa = a_str ? read_frag<T, true, S::A_LD1>(sA, 0, ks, lane) : read_frag<T, false, S::A_LD0>(sA, 0, ks, lane);
+        i32x4 fa[MR];
+#pragma unroll
+        for (int a = 0; a < MR; ++a)
+          fa[a] = a_str ? read_frag<T, true, S::A_LD1>(sA, a * 32, ks, lane) : read_frag<T, false, S::A_LD0>(sA, a * 32, ks, lane);
 #pragma unroll
         for (int b = 0; b < RT; ++b) {
           i32x4 fb = b_kc ? read_frag<T, false, S::B_LD1>(sB, b * 32, ks, lane)
                           : read_frag<T, true, S::B_LD0>(sB, b * 32, ks, lane);
-          Elem<T>::mma(acc[b], fb, fa);  // MFMA rows = n, columns = m
+#pragma unroll
+          for (int a = 0; a < MR; ++a) Elem<T>::mma(acc[a][b], fb, fa[a]);  // MFMA rows = n, columns = m
         }
       }
     }
@@ -221,28 +236,30 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
   __syncthreads();  // every wave is done with its staging region
   float* red = reinterpret_cast<float*>(smem_raw);
   {
-    // lane holds row m = l%32, columns n = 8q + 4(l/32) + e of each 32x32 block
+    // lane holds row m = l%32, columns n = 8q + 4(l/32) + e of each 32x32 block; red is [wave][n block][m of MB][32 n]
     const int m = lane & 31, nsub = 4 * (lane >> 5);
 #pragma unroll
-    for (int b = 0; b < RT; ++b)
+    for (int a = 0; a < MR; ++a)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        f32x4 v = {acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]};
-        *reinterpret_cast<f32x4*>(red + ((wave * RT + b) * 32 + m) * 32 + 8 * q + nsub) = v;
-      }
+      for (int b = 0; b < RT; ++b)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+          *reinterpret_cast<f32x4*>(red + ((wave * RT + b) * MB + a * 32 + m) * 32 + 8 * q + nsub) = v;
+        }
   }
   __syncthreads();
-  // RT*1024 outputs over NWV*64 threads; consecutive threads walk n (row-major store) or m (transposed)
+  // MR*RT*1024 outputs over NWV*64 threads; consecutive threads walk n (row-major store) or m (transposed)
   const bool trans = P.trans_out != 0;
 #pragma unroll
-  for (int j = 0; j < (16 * RT) / NWV; ++j) {
+  for (int j = 0; j < (16 * MR * RT) / NWV; ++j) {
     const int e = tid + NWV * 64 * j;
     int m, n;
-    if (!trans) { n = e % S::NB; m = e / S::NB; } else { m = e & 31; n = e >> 5; }
+    if (!trans) { n = e % S::NB; m = e / S::NB; } else { m = e % MB; n = e / MB; }
     const int b = n >> 5, nn = n & 31;
-    float s = red[((0 * RT + b) * 32 + m) * 32 + nn];
+    float s = red[((0 * RT + b) * MB + m) * 32 + nn];
 #pragma unroll
-    for (int w = 1; w < NWV; ++w) s += red[((w * RT + b) * 32 + m) * 32 + nn];
+    for (int w = 1; w < NWV; ++w) s += red[((w * RT + b) * MB + m) * 32 + nn];
     if (m0 + m < M && n < N) {
       if (P.partial) {
         P.partial[((int64_t)blockIdx.y * M + (m0 + m)) * N + n] = s;  // unscaled: the reduce applies alpha
@@ -259,7 +276,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
 }
 
 // AL is common to both problems of a paired launch; BL0 / BL1 are their B layouts.
-template <typename T, int RT, int NWV, int AL, int BL0, int BL1, bool DROP = false>
+template <typename T, int RT, int NWV, int AL, int BL0, int BL1, bool DROP = false, int MR = 1>
 __global__ __launch_bounds__(NWV * 64) void skinny_kernel(SkinnyArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   // Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2 and its own
@@ -274,11 +291,11 @@ __global__ __launch_bounds__(NWV * 64) void skinny_kernel(SkinnyArgs g) {
   const int R0 = g.p[0].row_blocks, R1 = g.nprob > 1 ? g.p[1].row_blocks : 0;
   const int n0 = R0 / 8 + (x < (R0 & 7) ? 1 : 0), s0 = x * (R0 / 8) + (x < (R0 & 7) ? x : (R0 & 7));
   if (slot < n0) {
-    skinny_body<T, RT, NWV, AL, BL0, DROP>(g.p[0], s0 + slot, smem_raw);
+    skinny_body<T, RT, NWV, AL, BL0, DROP, MR>(g.p[0], s0 + slot, smem_raw);
     return;
   }
   const int n1 = R1 / 8 + (x < (R1 & 7) ? 1 : 0), s1 = x * (R1 / 8) + (x < (R1 & 7) ? x : (R1 & 7));
-  if (slot - n0 < n1) skinny_body<T, RT, NWV, AL, BL1, DROP>(g.p[1], s1 + (slot - n0), smem_raw);
+  if (slot - n0 < n1) skinny_body<T, RT, NWV, AL, BL1, DROP, MR>(g.p[1], s1 + (slot - n0), smem_raw);
 }
 
 // Second stage for a K split over workgroups: C = sum over slices (in slice order) of the fp32
