@@ -294,6 +294,13 @@ class RunDoRALinear(nn.Module):
         self.dora_m = nn.Parameter(weight.float().norm(dim=0).to(weight.dtype))
         self._bwds = {}
 
+    @classmethod
+    def from_linear(cls, linear, r, alpha=None, bwd=None):
+        """nn.Linear keeps its weight as [d_out, d_in]; the layer holds the transposed copy."""
+        w = linear.weight.detach().t().contiguous()
+        b = linear.bias.detach() if linear.bias is not None else None
+        return cls(w, r, alpha, b, bwd)
+
     def bwd_for(self, n_tokens):
         if self.bwd is not None:
             return self.bwd
@@ -312,16 +319,23 @@ class RunDoRALinear(nn.Module):
         return f"d_in={self.d_in}, d_out={self.d_out}, r={self.r}, scale={self.scale:g}, bias={self.bias is not None}"
 
 
-def wrap_linears(model, r, alpha=None, targets=None, pair=None, keep_merged=False, dropout=0.0):
-    """Replace nn.Linear submodules of `model` by RunLoRALinear (all of them, or those whose attribute
-    name is in `targets`); every other parameter of the model is frozen.  Returns the replaced names."""
+def wrap_linears(model, r, alpha=None, targets=None, pair=None, keep_merged=False, dropout=0.0, adapter="lora"):
+    """Replace nn.Linear submodules of `model` by RunLoRALinear, or by RunDoRALinear with adapter="dora" (all of
+    them, or those whose attribute name is in `targets`); every other parameter of the model is frozen.
+    Returns the replaced names."""
+    if adapter not in ("lora", "dora"):
+        raise ValueError("adapter must be 'lora' or 'dora'")
+    if adapter == "dora" and (pair is not None or keep_merged or dropout):
+        raise ValueError("the DoRA layer takes none of pair / keep_merged / dropout")
     replaced = []
     for name, module in list(model.named_modules()):
         for child_name, child in list(module.named_children()):
             if isinstance(child, nn.Linear) and (targets is None or child_name in targets):
-                setattr(module, child_name, RunLoRALinear.from_linear(child, r, alpha, pair, keep_merged, dropout))
+                new = (RunDoRALinear.from_linear(child, r, alpha) if adapter == "dora"
+                       else RunLoRALinear.from_linear(child, r, alpha, pair, keep_merged, dropout))
+                setattr(module, child_name, new)
                 replaced.append(f"{name}.{child_name}" if name else child_name)
     for pname, p in model.named_parameters():
-        if not (pname.endswith("lora_A") or pname.endswith("lora_B")):
+        if not (pname.endswith("lora_A") or pname.endswith("lora_B") or pname.endswith("dora_m")):
             p.requires_grad_(False)
     return replaced

@@ -137,6 +137,40 @@ def test_wrap_linears_replaces_and_freezes():
     assert model.q_proj._pairs and list(model.q_proj._pairs) == [200]
 
 
+def test_wrap_linears_with_dora_layers():
+    """adapter="dora": bf16 linears become RunDoRALinear, the wrapped model starts as the original one (B = 0, m = the
+    column norms of W), and A, B and m are what trains."""
+    import torch
+    from torch import nn
+    from paper_2312_03415_amd.module import RunDoRALinear, wrap_linears
+
+    class Mlp(nn.Module):
+        def __init__(self):
+            super().__init__()
+            self.up = nn.Linear(64, 136)
+            self.down = nn.Linear(136, 64, bias=False)
+
+        def forward(self, x):
+            return self.down(torch.relu(self.up(x)))
+
+    torch.manual_seed(1)
+    model = Mlp().cuda().to(torch.bfloat16)
+    x = torch.randn(4, 50, 64, device="cuda").to(torch.bfloat16)
+    want = model(x)
+    names = wrap_linears(model, r=8, alpha=16, adapter="dora")
+    assert sorted(names) == ["down", "up"] and isinstance(model.up, RunDoRALinear)
+    trainable = sorted(n for n, p in model.named_parameters() if p.requires_grad)
+    assert trainable == ["down.dora_m", "down.lora_A", "down.lora_B", "up.dora_m", "up.lora_A", "up.lora_B"]
+    got = model(x)
+    assert relerr(to_f64(got.reshape(-1, 64)), to_f64(want.reshape(-1, 64))) < 2 * TOL["bf16"]
+    got.float().square().mean().backward()
+    for layer in (model.up, model.down):
+        assert layer.dora_m.grad is not None and layer.dora_m.grad.float().abs().sum().item() > 0
+        assert layer.lora_B.grad.float().abs().sum().item() > 0
+    with pytest.raises(ValueError):
+        wrap_linears(Mlp(), r=8, adapter="dora", dropout=0.1)
+
+
 def test_layer_dropout_in_training_mode():
     """Training mode with dropout: outputs and gradients match the oracle under the mask of the seed the
     layer drew; eval mode runs without dropout."""
