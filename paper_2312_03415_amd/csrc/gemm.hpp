@@ -129,6 +129,8 @@ struct MergeDesc {
   // optional: store nothing to M; write the squared column sums of W + alpha A B, one row of O floats per
   // row slice of the launch (merge_grid's gy rows; the caller adds them up)
   float* sq_partial = nullptr;
+  // drop_thr != 0: M = W + mask o (alpha A B) with the LoRA dropout keep-mask over M's elements (gemm_engine.hpp)
+  uint32_t drop_thr = 0, drop_key = 0, drop_cpr = 0;
 };
 inline bool merge_ok(int dtype, int64_t r) { return dtype != DT_F32 && r <= 128; }
 // the merge kernel's launch shape: gx workgroups of `cols` columns, gy row slices of bpw 32-row blocks each

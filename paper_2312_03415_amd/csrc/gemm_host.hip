@@ -322,6 +322,7 @@ hipError_t merge_run(int dtype, const MergeDesc& d, hipStream_t stream) {
   a.b_trans = d.b_trans;
   a.wcol = d.wcol;
   a.sq_partial = d.sq_partial;
+  a.drop_thr = d.drop_thr; a.drop_key = d.drop_key; a.drop_cpr = d.drop_cpr;
   return dtype == DT_BF16 ? merge_launch_bf16(a, stream) : merge_launch_f16(a, stream);
 }
 

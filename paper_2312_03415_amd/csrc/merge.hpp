@@ -30,6 +30,9 @@ struct MergeArgs {
   // optional [gridDim.y][O]: nothing is stored to M; each workgroup writes, per column, the sum over its
   // rows of (W + alpha A B)^2 in fp32 (the squared column norms, summed over gridDim.y by the caller)
   float* sq_partial;
+  // drop_thr != 0: the product is masked before it is added, M = W + mask o (alpha A B), with the LoRA dropout
+  // keep-mask of element (row, column) of M (drop_keep4, gemm_engine.hpp; drop_cpr = groups of four columns per row)
+  uint32_t drop_thr, drop_key, drop_cpr;
 };
 
 template <int KSTEPS, int CB>
@@ -147,8 +150,19 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs g) {
 #pragma unroll
     for (int p = 0; p < MT::PASSES; ++p) {
       const int rloc = p * MT::RPP + prow, row = rb * 32 + rloc;
-      const f32x4 s0 = *reinterpret_cast<const f32x4*>(red + rloc * MT::LD + pcol);
-      const f32x4 s1 = *reinterpret_cast<const f32x4*>(red + rloc * MT::LD + pcol + 4);
+      f32x4 s0 = *reinterpret_cast<const f32x4*>(red + rloc * MT::LD + pcol);
+      f32x4 s1 = *reinterpret_cast<const f32x4*>(red + rloc * MT::LD + pcol + 4);
+      if (g.drop_thr != 0u) {  // uniform
+        uint32_t k0[4], k1[4];
+        const uint32_t grp = (uint32_t)row * g.drop_cpr + (uint32_t)((n0 + pcol) >> 2);
+        drop_keep4(grp, g.drop_key, g.drop_thr, k0);
+        drop_keep4(grp + 1, g.drop_key, g.drop_thr, k1);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          s0[e] = k0[e] ? s0[e] : 0.f;
+          s1[e] = k1[e] ? s1[e] : 0.f;
+        }
+      }
       const T* w8 = reinterpret_cast<const T*>(&wcur[p]);
       if (g.sq_partial != nullptr) {  // uniform: rows and columns outside the matrix contribute zeros
 #pragma unroll

@@ -37,8 +37,9 @@ struct Builder {
             bool b_is_w = false, float alpha = 1.f, const void* bias = nullptr, bool mask_out = false) {
     // A rank-r update of a large matrix (Y += T B, dX += Z1 A^T of the default chain) is the merge kernel's
     // operation, M = W + alpha A B, on other operands: one pass over the matrix at streaming speed instead of
-    // a tile GEMM whose contraction is a fraction of a K tile.
-    if (D && K2 == 0 && !a_strided && !bias && !(mask_out && L.drop_thr) && !(b_is_w && L.w_int4) && merge_ok(L.dtype, K)) {
+    // a tile GEMM whose contraction is a fraction of a K tile.  Under LoRA dropout the update of dX is masked
+    // (dX += m o (Z1 A^T)): the kernel masks the product before it adds.
+    if (D && K2 == 0 && !a_strided && !bias && !(b_is_w && L.w_int4) && merge_ok(L.dtype, K)) {
       Step m;
       m.what = what;
       m.is_merge = true;
@@ -48,6 +49,7 @@ struct Builder {
       m.mg.I = M; m.mg.O = N; m.mg.R = K;
       m.mg.alpha = alpha;
       m.mg.b_trans = b_kcontig;
+      if (mask_out && L.drop_thr) { m.mg.drop_thr = L.drop_thr; m.mg.drop_key = L.drop_key; m.mg.drop_cpr = drop_cpr(); }
       out->steps.push_back(m);
       return;
     }
