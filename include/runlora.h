@@ -356,6 +356,8 @@ size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g);
  * step's main kernel alone (the tile GEMM, the streaming kernel or the merge kernel), taken from a
  * second pair of events bound to that kernel's own dispatch: the figure a kernel trace reports for
  * it; us then also holds the handling of those events.  Otherwise kernel_us = us.
+ * tile_cfg names the kernel that ran the step: 0..7 as in rl_gemm_t, 8 / 9 / 10 = the streaming kernel with up to
+ * 32 / 64 / 128 output columns, 11 = the W + alpha A B kernel (also the default chain's rank-r updates).
  * Events are host objects created at enable and destroyed at disable; no device memory.
  */
 typedef struct {
