@@ -97,27 +97,36 @@ __device__ __forceinline__ uint32_t drop_mix(uint32_t x) {
   x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
   return x;
 }
+// bit 7 of byte k of the result is set iff byte k of h is >= thr (1 <= thr <= 255), all four bytes at once:
+// the low seven bits are compared by an addition that carries into bit 7 (0x7F + 0x80 at most: no carry between
+// bytes), the top bits decide the rest.  thr is uniform, so its part is scalar arithmetic.
+__device__ __forceinline__ uint32_t drop_ge_bytes(uint32_t h, uint32_t thr) {
+  const uint32_t lo = (h & 0x7F7F7F7Fu) + (0x80u - (thr & 0x7Fu)) * 0x01010101u;
+  const uint32_t ge = (thr & 0x80u) ? (h & lo) : (h | lo);
+  return ge & 0x80808080u;
+}
 // keep-masks of the four columns of group g: 0xFFFFFFFF / 0 per column
 __device__ __forceinline__ void drop_keep4(uint32_t g, uint32_t key, uint32_t thr, uint32_t (&keep)[4]) {
-  const uint32_t h = drop_mix(g ^ key);
+  const uint32_t f = drop_ge_bytes(drop_mix(g ^ key), thr);
 #pragma unroll
-  for (int k = 0; k < 4; ++k) keep[k] = ((h >> (8 * k)) & 255u) >= thr ? 0xFFFFFFFFu : 0u;
+  for (int k = 0; k < 4; ++k) keep[k] = (uint32_t)((int32_t)(f << (24 - 8 * k)) >> 31);
 }
 // a 16-byte chunk of X whose first column belongs to group g (8 columns = groups g, g+1 for 16-bit
 // types; 4 columns = group g for fp32) with the dropped elements zeroed
 template <typename T>
 __device__ __forceinline__ i32x4 drop_chunk(i32x4 v, uint32_t g, uint32_t key, uint32_t thr) {
-  uint32_t k0[4];
-  drop_keep4(g, key, thr, k0);
   if constexpr (sizeof(T) == 4) {
+    uint32_t k0[4];
+    drop_keep4(g, key, thr, k0);
     return i32x4{(int)((uint32_t)v[0] & k0[0]), (int)((uint32_t)v[1] & k0[1]), (int)((uint32_t)v[2] & k0[2]), (int)((uint32_t)v[3] & k0[3])};
   } else {
-    uint32_t k1[4];
-    drop_keep4(g + 1, key, thr, k1);
-    return i32x4{(int)((uint32_t)v[0] & ((k0[0] & 0xFFFFu) | (k0[1] & 0xFFFF0000u))),
-                 (int)((uint32_t)v[1] & ((k0[2] & 0xFFFFu) | (k0[3] & 0xFFFF0000u))),
-                 (int)((uint32_t)v[2] & ((k1[0] & 0xFFFFu) | (k1[1] & 0xFFFF0000u))),
-                 (int)((uint32_t)v[3] & ((k1[2] & 0xFFFFu) | (k1[3] & 0xFFFF0000u)))};
+    // per hash: flags -> 0xFF / 0x00 per byte -> each byte doubled into a 16-bit lane mask (byte permute)
+    const uint32_t f0 = drop_ge_bytes(drop_mix(g ^ key), thr), f1 = drop_ge_bytes(drop_mix((g + 1) ^ key), thr);
+    const uint32_t m0 = (f0 - (f0 >> 7)) | f0, m1 = (f1 - (f1 >> 7)) | f1;
+    return i32x4{(int)((uint32_t)v[0] & __builtin_amdgcn_perm(m0, m0, 0x01010000u)),
+                 (int)((uint32_t)v[1] & __builtin_amdgcn_perm(m0, m0, 0x03030202u)),
+                 (int)((uint32_t)v[2] & __builtin_amdgcn_perm(m1, m1, 0x01010000u)),
+                 (int)((uint32_t)v[3] & __builtin_amdgcn_perm(m1, m1, 0x03030202u))};
   }
 }
 

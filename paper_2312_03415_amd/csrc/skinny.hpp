@@ -70,7 +70,9 @@ struct SkinnyTile {
 
 // One problem's work for this workgroup.  AL / BL are the operand layouts (compile time, so that
 // the load and fragment paths are straight-line code): AL = 1: A stored [K,M]; BL = 1: B stored [N,K].
-// DROP: the build of the kernel that can mask A (LoRA dropout); the plain build carries none of it.
+// DROP: this problem's A is the layer input X under LoRA dropout and is masked on its way to LDS (a compile-time
+// property of the problem's slot in the launch: a run-time test in the loop cost the whole launch a factor of two,
+// masked problem or not); the plain build carries none of it.
 template <typename T, int RT, int NWV, int AL, int BL, bool DROP, int MR>
 __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsigned char* smem_raw) {
   using S = SkinnyTile<T, RT, NWV, MR>;
@@ -166,7 +168,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
   };
 
   auto store_lds = [&](int d) {
-    if (DROP && P.drop_thr != 0u) {  // wave-uniform: A is X under LoRA dropout
+    if constexpr (DROP) {  // A is X under LoRA dropout
 #pragma unroll
       for (int j = 0; j < A_PER; ++j) {
         const int c = lane + 64 * j;
@@ -276,7 +278,8 @@ __device__ __forceinline__ void skinny_body(const SkinnyProblem& P, int bx, unsi
 }
 
 // AL is common to both problems of a paired launch; BL0 / BL1 are their B layouts.
-template <typename T, int RT, int NWV, int AL, int BL0, int BL1, bool DROP = false, int MR = 1>
+// DROPM: bit w set = problem w of the launch is masked (see skinny_body)
+template <typename T, int RT, int NWV, int AL, int BL0, int BL1, int DROPM = 0, int MR = 1>
 __global__ __launch_bounds__(NWV * 64) void skinny_kernel(SkinnyArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   // Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2 and its own
@@ -291,11 +294,11 @@ __global__ __launch_bounds__(NWV * 64) void skinny_kernel(SkinnyArgs g) {
   const int R0 = g.p[0].row_blocks, R1 = g.nprob > 1 ? g.p[1].row_blocks : 0;
   const int n0 = R0 / 8 + (x < (R0 & 7) ? 1 : 0), s0 = x * (R0 / 8) + (x < (R0 & 7) ? x : (R0 & 7));
   if (slot < n0) {
-    skinny_body<T, RT, NWV, AL, BL0, DROP, MR>(g.p[0], s0 + slot, smem_raw);
+    skinny_body<T, RT, NWV, AL, BL0, (DROPM & 1) != 0, MR>(g.p[0], s0 + slot, smem_raw);
     return;
   }
   const int n1 = R1 / 8 + (x < (R1 & 7) ? 1 : 0), s1 = x * (R1 / 8) + (x < (R1 & 7) ? x : (R1 & 7));
-  if (slot - n0 < n1) skinny_body<T, RT, NWV, AL, BL1, DROP, MR>(g.p[1], s1 + (slot - n0), smem_raw);
+  if (slot - n0 < n1) skinny_body<T, RT, NWV, AL, BL1, (DROPM & 2) != 0, MR>(g.p[1], s1 + (slot - n0), smem_raw);
 }
 
 // Second stage for a K split over workgroups: C = sum over slices (in slice order) of the fp32
