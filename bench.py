@@ -49,8 +49,7 @@ def parse():
     ap.add_argument("--keep-merged", action="store_true",
                     help="let forward2 keep W + AB for backward4/5 (i*o elements held per layer; pairs chosen for that)")
     ap.add_argument("--dropout", type=float, default=0.0,
-                    help="LoRA dropout probability (0 = the paper's setting); the timed pair is then (1,1), the only RunLoRA graphs that exist with it "
-                         "(the default chain, timed beside it, is the faster one under dropout)")
+                    help="LoRA dropout probability (0 = the paper's setting); pairs are then (1,1), the only RunLoRA graphs that exist with it")
     ap.add_argument("--dora", action="store_true",
                     help="run the layers as DoRA (trainable magnitudes m on top of A, B) through runlora_dora_*: forward2 + a merged "
                          "backward (5, or the second number of --pair); the default-chain leg is then the LoRA layer's")

@@ -232,7 +232,10 @@ SkinnyPlan skinny_plan(int dtype, int nprob, const SkinnyDesc* d) {
   for (int w = 0; w < nprob; ++w)
     if (d[w].N > maxn) maxn = d[w].N;
   p.rt = maxn <= 32 ? 1 : (maxn <= 64 ? 2 : 4);
-  p.mr = (nprob == 2 && d[0].a_strided && d[1].a_strided && p.rt <= 2) ? 2 : 1;  // see skinny.hpp
+  // see skinny.hpp; a masked problem (LoRA dropout) is bound by its waves' mask arithmetic, which 32-row workgroups
+  // spread over twice as many waves
+  const bool masked = d[0].drop_thr != 0 || (nprob == 2 && d[1].drop_thr != 0);
+  p.mr = (nprob == 2 && d[0].a_strided && d[1].a_strided && p.rt <= 2 && !masked) ? 2 : 1;
   const int mb = 32 * p.mr;
   for (int w = 0; w < nprob; ++w) {
     blocks += (d[w].M + mb - 1) / mb;

@@ -131,11 +131,10 @@ class RunLoRALinear(nn.Module):
     def forward(self, x):
         n = x.numel() // self.d_in
         if self.training and self.dropout > 0.0:
-            # with dropout only forward1 / backward1 and the default chain exist, and the default chain is the
-            # fastest of them (it keeps XA, so the masked X is read once less); a fresh seed per call from
-            # torch's CPU generator, so that torch.manual_seed makes runs repeatable
+            # with dropout only forward1 / backward1 (or the default chain) exist; a fresh seed per call
+            # from torch's CPU generator, so that torch.manual_seed makes runs repeatable
             self.last_dropout_seed = int(torch.randint(0, 2 ** 31 - 1, (1,)).item())
-            pair = self.pair if self.pair in ((0, 0), (0, 1), (1, 1)) else (0, 0)
+            pair = self.pair if self.pair in ((0, 0), (0, 1), (1, 1)) else (1, 1)
             return RunLoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.bias, self.scale, pair, False,
                                          (self.dropout, self.last_dropout_seed))
         return RunLoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.bias, self.scale,
