@@ -8,7 +8,7 @@
 //
 //  - One workgroup = NWV (4) wavefronts that share a block of 32 * MR output rows and split the
 //    workgroup's K range between them.  MR = 2 (64 rows) is used by paired launches whose A operands are
-//    stored [K,M] (and N <= 64): a block's rows are then columns of A, a 32-column strip is 64 bytes per
+//    stored [K,M] (N <= 64, no LoRA dropout mask: a masked problem is bound by its waves' mask arithmetic): a block's rows are then columns of A, a 32-column strip is 64 bytes per
 //    row of A, half a 128-byte line, and the other half has to come from the neighbouring workgroup's
 //    fetch staying in L2; with 128-byte strips the paired dA / dB launch runs 20 % faster (OPT shapes:
 //    25.6 -> 20.5 us).  Single launches keep 32 rows: halving their workgroup count costs more than the
