@@ -13,6 +13,7 @@
 //    32x32 block give A B in fp32, the wave passes it through its private LDS region to turn the
 //    MFMA's register layout into rows, adds W (prefetched one row block ahead, 16 bytes per lane,
 //    whole 128/256-byte row segments per wave instruction), rounds once and stores 16 bytes per lane.
+//    W is read with non-temporal loads: nothing reads it again soon, while M is read by the next kernel.
 #pragma once
 #include "gemm_engine.hpp"
 
@@ -118,7 +119,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs g) {
     for (int p = 0; p < MT::PASSES; ++p) {
       const int row = rb * 32 + p * MT::RPP + prow;
       i32x4 v = {0, 0, 0, 0};
-      if (col_ok && row < g.I) v = *reinterpret_cast<const i32x4*>(Wp + (int64_t)row * g.ldw + n0 + pcol);
+      if (col_ok && row < g.I) v = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(Wp + (int64_t)row * g.ldw + n0 + pcol));
       wreg[p] = v;
     }
   };
