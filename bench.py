@@ -32,8 +32,8 @@ TILE_NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256
 TRAFFIC_BYTES = {
     # profiles/bench_opt13b_hbm_traffic.txt: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per launch, all
     # launches of the matrix-core kernel of that layout together (all of its builds)
-    ("opt13b", "gemm_kernel<bf16,NN,256x256mc>"): int((133409 * 2.0 + 65536) * 1024),
-    ("opt13b", "gemm_kernel<bf16,NT,256x256mc>"): int((132455 * 2.0 + 65536) * 1024),
+    ("opt13b", "gemm_kernel<bf16,NN,256x256mc>"): int((133129 * 2.0 + 65536) * 1024),
+    ("opt13b", "gemm_kernel<bf16,NT,256x256mc>"): int((132490 * 2.0 + 65536) * 1024),
 }
 
 
