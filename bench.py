@@ -1,24 +1,32 @@
 #!/usr/bin/env python3
 """Benchmark of the LoRA-linear hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload opt13b|llama7b] [--rank R]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b|opt13b|qlora] [--rank R]
 
 A step = forward + backward of every layer of the workload, each in the (forward, backward) pair
 that runlora_select picks, on seeded synthetic inputs already resident in HBM.  The default
-workload is the OPT-1.3B-shaped MLP pair (tokens 8x512 = 4096, fc1 2048->8192, fc2 8192->2048,
-rank 16, bf16).  Input/output sets are rotated so that the 256 MB Infinity Cache cannot serve
-them between steps.  The same steps are also timed in the default chain (same kernels, one per
-product, XA kept) for the speedup figure.
+workload is the largest single-GPU configuration: the seven adapted linears of a Llama-7B-shaped
+decoder block (tokens 4x2048 = 8192; q/k/v/o 4096->4096, gate/up 4096->11008, down 11008->4096;
+rank 32; bf16), with the same block at ranks 8 and 128 timed as extra keys.  `--workload opt13b`
+is the OPT-1.3B-shaped MLP pair (tokens 8x512 = 4096, fc1 2048->8192, fc2 8192->2048, rank 16).
+Input/output sets are rotated so that the 256 MB Infinity Cache cannot serve them between steps.
+The same steps are also timed in the default chain (same kernels, one per product, XA kept) for
+the speedup figure.
 
 Prints ONE JSON line: the headline value is useful TFLOP/s = (fewest FLOPs any legal pair needs,
 Table 1 of arxiv 2312.03415 plus the default chain) / measured time; `roofline` describes the
-dominant kernel from per-launch HIP-event timings of an identical pass; `cpu_baseline` is the fp64
-CPU oracle's default chain on a bounded token sample, on this machine's host cores.
+dominant kernel (the matrix-core GEMM with everything it launches: a cut-off tail launch, the
+reduce pass of a split contraction) from HIP events bound to each kernel's own dispatch in an
+identical pass; `cpu_baseline` is the fp64 CPU oracle's default chain on a bounded token sample of
+one projection, on this machine's host cores.
 """
 import argparse
 import json
+import os
+import re
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
@@ -26,15 +34,20 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 HBM_PEAK_GBPS = 8000.0
 TILE_NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x256mc3", "256x256mc", "stream32", "stream64", "stream128", "merge"]
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), scaled by what the same counters read for a copy kernel of known size; None until
-# measured for the workload.
-TRAFFIC_BYTES = {
-    # profiles/bench_opt13b_hbm_traffic.txt: (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0) KiB per launch, all
-    # launches of the matrix-core kernel of that layout together (all of its builds)
-    ("opt13b", "gemm_kernel<bf16,NN,256x256mc>"): int((133129 * 2.0 + 65536) * 1024),
-    ("opt13b", "gemm_kernel<bf16,NT,256x256mc>"): int((132490 * 2.0 + 65536) * 1024),
-}
+ROOT = os.path.dirname(os.path.abspath(__file__))
+
+
+def traffic_from_profile(workload, kernel):
+    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload
+    (profiles/bench_<workload>_hbm_traffic.txt: FETCH_SIZE and WRITE_SIZE runs of this very command, scaled by
+    what the same counters read for a copy of known size); None if no summary covers it."""
+    path = os.path.join(ROOT, "profiles", "bench_%s_hbm_traffic.txt" % workload)
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"^traffic_bytes_per_launch\s+%s\s*=\s*(\d+)" % re.escape(kernel), text, re.M)
+    return int(m.group(1)) if m else None
 
 
 def parse():
@@ -42,8 +55,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="opt13b", choices=["opt13b", "llama7b", "qlora"])
+    ap.add_argument("--workload", default="llama7b", choices=["llama7b", "opt13b", "qlora"])
     ap.add_argument("--rank", type=int, default=None, help="LoRA rank override (llama7b: 8/32/128)")
+    ap.add_argument("--no-extra-ranks", action="store_true", help="llama7b: skip the extra timings of the block at ranks 8 and 128")
     ap.add_argument("--sets", type=int, default=4, help="rotating input/output sets (together beyond the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--keep-merged", action="store_true",
@@ -85,10 +99,13 @@ def main():
         print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4, "copies": 5}))
         return
 
+    def with_rank(layers, r):
+        return [synth.Layer(L.name, L.n, L.i, L.o, r, L.dtype, L.index) for L in layers]
+
     if args.workload == "opt13b":
         layers = synth.config_opt13b_mlp("bf16")
         if args.rank:
-            layers = [synth.Layer(L.name, L.n, L.i, L.o, args.rank, L.dtype, L.index) for L in layers]
+            layers = with_rank(layers, args.rank)
         wl_name = "OPT-1.3B-shaped MLP pair, tokens 8x512=4096, fc1 2048x8192 + fc2 8192x2048, r=%d" % layers[0].r
     elif args.workload == "llama7b":
         layers = synth.config_llama7b(args.rank or 32, "bf16")
@@ -96,7 +113,7 @@ def main():
     else:
         layers = synth.config_qlora()
         if args.rank:
-            layers = [synth.Layer(L.name, L.n, L.i, L.o, args.rank, L.dtype, L.index) for L in layers]
+            layers = with_rank(layers, args.rank)
         wl_name = "frozen W 5120x13824 as int4 (groups of 64, fp16 scales), tokens 4096, r=%d, bf16 activations" % layers[0].r
     int4 = args.workload == "qlora"
     dtype = layers[0].dtype
@@ -109,56 +126,68 @@ def main():
         return torch.from_numpy(stored).to(dev)
 
     # ---- inputs (seeded, synthetic), `sets` device copies per layer --------------------------
-    host_inputs = []
-    state = []
-    for L in layers:
-        st = synth.layer_inputs(L)
-        host_inputs.append(st)
-        base = {k: to_dev(v) for k, v in st.items()}
-        if int4:  # the frozen weight in its 4-bit form; the dense copy is only the CPU baseline's
-            q, scale = synth.int4_weight(L)
-            base["W"] = rl.Int4Weight.from_host(q, scale)
-            st["W"] = synth.store(q.astype(np.float64) * np.repeat(scale.astype(np.float64), 64, axis=0)[:L.i], dtype)
-        sets = []
-        for s in range(args.sets):
-            t = {k: (v if (s == 0 or k == "W" and int4) else v.clone()) for k, v in base.items()}
-            t["Y"] = torch.empty((L.n, L.o), dtype=tdt, device=dev)
-            t["T"] = torch.empty((L.n, L.r), dtype=tdt, device=dev)
-            t["dX"] = torch.empty((L.n, L.i), dtype=tdt, device=dev)
-            t["dA"] = torch.empty((L.i, L.r), dtype=tdt, device=dev)
-            t["dB"] = torch.empty((L.r, L.o), dtype=tdt, device=dev)
-            t["M"] = torch.empty((L.i, L.o), dtype=tdt, device=dev) if args.keep_merged else None
-            if args.dora:
-                t["m"] = to_dev(synth.store(0.5 + np.abs(synth.normal(synth.BASE_SEED + L.index, 10, (L.o,))), dtype))
-                t["c"] = torch.empty((L.o,), dtype=torch.float32, device=dev)
-                t["dm"] = torch.empty((L.o,), dtype=tdt, device=dev)
-            if args.vera:
-                t["d"] = to_dev(synth.store(synth.normal(synth.BASE_SEED + L.index, 10, (L.r,)), dtype))
-                t["b"] = to_dev(synth.store(synth.normal(synth.BASE_SEED + L.index, 11, (L.o,)), dtype))
-                t["dd"] = torch.empty((L.r,), dtype=tdt, device=dev)
-                t["db"] = torch.empty((L.o,), dtype=tdt, device=dev)
-            sets.append(t)
-        if args.dora:
-            fwd, bwd = 2, (int(args.pair.split(",")[1]) if args.pair else 5)
-        elif args.dropout > 0.0:
-            fwd, bwd = 1, 1
-        elif args.pair:
-            fwd, bwd = (int(v) for v in args.pair.split(","))
-        else:
-            fwd, bwd = rl.runlora_select(L.n, L.i, L.o, L.r, rl.RL_INT4_G64 if int4 else code,
-                                         criterion=2 if args.keep_merged else None)
-        wd = rl.RL_INT4_G64 if int4 else None
-        ws_bytes = max(rl.runlora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code, wd),
-                       rl.runlora_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code, wd))
-        if args.vera:
-            ws_bytes = max(rl.runlora_vera_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code),
-                           rl.runlora_vera_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code))
-        if args.dora:
-            ws_bytes = max(ws_bytes, rl.runlora_dora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code))
-        ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
-        state.append(dict(L=L, sets=sets, pair=(fwd, bwd), ws=ws))
+    # (the generator is numpy, which releases the interpreter lock in its array operations: the layers are drawn
+    # side by side on the host's cores)
+    with ThreadPoolExecutor(max_workers=min(8, len(layers))) as ex:
+        host_inputs = list(ex.map(synth.layer_inputs, layers))
 
-    def step(k, default_chain, only=None):
+    def make_state(layers, host_inputs, shared=None):
+        """Device state of one block: per layer `sets` rotating copies of inputs and outputs, the pair, the workspace.
+        shared: a state of the same layers at another rank whose X, W, dY (rank-independent) are reused."""
+        state = []
+        for li, (L, st) in enumerate(zip(layers, host_inputs)):
+            base = {k: to_dev(v) for k, v in st.items()}
+            if int4:  # the frozen weight in its 4-bit form; the dense copy is only the CPU baseline's
+                q, scale = synth.int4_weight(L)
+                base["W"] = rl.Int4Weight.from_host(q, scale)
+                st["W"] = synth.store(q.astype(np.float64) * np.repeat(scale.astype(np.float64), 64, axis=0)[:L.i], dtype)
+            sets = []
+            for s in range(args.sets):
+                if shared is not None:
+                    t = {k: shared[li]["sets"][s][k] for k in ("X", "W", "dY", "Y", "dX")}
+                    t.update({k: base[k] if s == 0 else base[k].clone() for k in ("A", "B")})
+                else:
+                    t = {k: (v if (s == 0 or k == "W" and int4) else v.clone()) for k, v in base.items()}
+                    t["Y"] = torch.empty((L.n, L.o), dtype=tdt, device=dev)
+                    t["dX"] = torch.empty((L.n, L.i), dtype=tdt, device=dev)
+                t["T"] = torch.empty((L.n, L.r), dtype=tdt, device=dev)
+                t["dA"] = torch.empty((L.i, L.r), dtype=tdt, device=dev)
+                t["dB"] = torch.empty((L.r, L.o), dtype=tdt, device=dev)
+                t["M"] = torch.empty((L.i, L.o), dtype=tdt, device=dev) if args.keep_merged else None
+                if args.dora:
+                    t["m"] = to_dev(synth.store(0.5 + np.abs(synth.normal(synth.BASE_SEED + L.index, 10, (L.o,))), dtype))
+                    t["c"] = torch.empty((L.o,), dtype=torch.float32, device=dev)
+                    t["dm"] = torch.empty((L.o,), dtype=tdt, device=dev)
+                if args.vera:
+                    t["d"] = to_dev(synth.store(synth.normal(synth.BASE_SEED + L.index, 10, (L.r,)), dtype))
+                    t["b"] = to_dev(synth.store(synth.normal(synth.BASE_SEED + L.index, 11, (L.o,)), dtype))
+                    t["dd"] = torch.empty((L.r,), dtype=tdt, device=dev)
+                    t["db"] = torch.empty((L.o,), dtype=tdt, device=dev)
+                sets.append(t)
+            if args.dora:
+                fwd, bwd = 2, (int(args.pair.split(",")[1]) if args.pair else 5)
+            elif args.dropout > 0.0:
+                fwd, bwd = 1, 1
+            elif args.pair:
+                fwd, bwd = (int(v) for v in args.pair.split(","))
+            else:
+                fwd, bwd = rl.runlora_select(L.n, L.i, L.o, L.r, rl.RL_INT4_G64 if int4 else code,
+                                             criterion=2 if args.keep_merged else None)
+            wd = rl.RL_INT4_G64 if int4 else None
+            ws_bytes = max(rl.runlora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code, wd),
+                           rl.runlora_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code, wd))
+            if args.vera:
+                ws_bytes = max(rl.runlora_vera_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code),
+                               rl.runlora_vera_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code))
+            if args.dora:
+                ws_bytes = max(ws_bytes, rl.runlora_dora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code))
+            ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+            state.append(dict(L=L, sets=sets, pair=(fwd, bwd), ws=ws))
+        return state
+
+    state = make_state(layers, host_inputs)
+
+    def step(state, k, default_chain, only=None):
         for st in (state if only is None else [only]):
             t = st["sets"][k % args.sets]
             fwd, bwd = (0, 0) if default_chain else st["pair"]
@@ -178,18 +207,18 @@ def main():
             rl.runlora_backward(bwd, t["dY"], saved, t["W"], t["A"], t["B"], t["dX"], t["dA"], t["dB"],
                                 workspace=st["ws"])
 
-    def timed(default_chain):
+    def timed(state, default_chain):
         for k in range(args.warmup):
-            step(k, default_chain)
+            step(state, k, default_chain)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(args.steps):
-            step(k, default_chain)
+            step(state, k, default_chain)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / args.steps
 
-    sec_sel = timed(False)
-    sec_def = timed(True)
+    sec_sel = timed(state, False)
+    sec_def = timed(state, True)
 
     # ---- useful FLOPs: the fewest any legal pair needs ---------------------------------------
     def useful_flops(L):
@@ -211,11 +240,11 @@ def main():
     # `steps` iterations, HIP events on the launch stream around each iteration
     def layer_ms(st, default_chain):
         for k in range(args.warmup):
-            step(k, default_chain, st)
+            step(state, k, default_chain, st)
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
         for k, (e0, e1) in enumerate(ev):
             e0.record()
-            step(k, default_chain, st)
+            step(state, k, default_chain, st)
             e1.record()
         torch.cuda.synchronize()
         ts = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
@@ -228,32 +257,40 @@ def main():
         per_layer.append(dict(name=L.name, pair=list(st["pair"]), ms=round(ms_sel, 4), ms_default_chain=round(ms_def, 4),
                               speedup=round(ms_def / ms_sel, 4), useful_tflops=round(useful_flops(L) / ms_sel / 1e9, 1)))
 
-    # ---- per-kernel timings of an identical pass (HIP events the library binds, on the launch stream, to the
-    # dispatch of every step's main kernel: the kernel's own duration) -> roofline of the dominant kernel
+    # ---- per-kernel timings of an identical pass: the library binds a pair of HIP events, on the launch stream, to
+    # the dispatch of every kernel a step launches (the figure a kernel trace reports) -> roofline of the dominant kernel
     rl.runlora_profile_kernel_times(True)
     rl.runlora_profile_enable(args.steps * len(layers) * 16)
     for k in range(args.steps):
-        step(k, False)
+        step(state, k, False)
     torch.cuda.synchronize()
     recs = rl.runlora_profile_collect(args.steps * len(layers) * 16)
     rl.runlora_profile_disable()
     rl.runlora_profile_kernel_times(False)
     groups = {}
     ridge = MFMA_PEAK_TFLOPS[dtype] * 1e12 / (HBM_PEAK_GBPS * 1e9)
+    MC = (TILE_NAMES.index("256x256mc3"), TILE_NAMES.index("256x256mc"))
     for r in recs:
         lay = "NN" if not r["a_strided"] and not r["b_kcontig"] else ("NT" if r["b_kcontig"] else "TN")
-        # the same kernel serves compute-bound contractions and memory-bound ones (W + AB has K = r)
-        key = (lay, TILE_NAMES[r["tile_cfg"]] + ("" if r["flops"] / r["bytes"] >= ridge else "/mem"))
-        # the kernel's own duration (what a kernel trace reports for it); the reduce pass behind a split contraction
-        # is a kernel of its own and is not in these figures
-        g = groups.setdefault(key, dict(us=0.0, flops=0.0, bytes=0.0, launches=0, what=set()))
+        dense = r["flops"] / r["bytes"] >= ridge
+        # every compute-bound product on the matrix-core kernel is one group, whatever its operand layout and build:
+        # a step's time there is the sum over all kernels it launched (main launch, tail launch, reduce pass).  The
+        # same kernels also serve memory-bound products (W + AB has K = r): those are groups of their own.
+        if r["tile_cfg"] in MC and dense:
+            key = ("gemm_mc_kernel", "")
+        else:
+            key = (lay, TILE_NAMES[r["tile_cfg"]] + ("" if dense else "/mem"))
+        g = groups.setdefault(key, dict(us=0.0, flops=0.0, bytes=0.0, launches=0, kernels=0, what=set(), by_build={}))
         g["us"] += r["kernel_us"]; g["flops"] += r["flops"]; g["bytes"] += r["bytes"]; g["launches"] += 1
+        g["kernels"] += max(r["kernels"], 1)
         g["what"].add(r["what"])
+        b = g["by_build"].setdefault(lay + ("/split" if r["splits"] > 1 else ""), [0.0, 0])
+        b[0] += r["main_us"]; b[1] += 1
     dom_key = max(groups, key=lambda k: groups[k]["us"])
     dom = groups[dom_key]
     total_kernel_us = sum(g["us"] for g in groups.values())
     intensity = dom["flops"] / dom["bytes"]
-    kname = "gemm_kernel<%s,%s,%s>" % (dtype, dom_key[0], dom_key[1])
+    kname = dom_key[0] if not dom_key[1] else "gemm_kernel<%s,%s,%s>" % (dtype, dom_key[0], dom_key[1])
     if intensity >= ridge:
         ach = dom["flops"] / dom["us"] / 1e6
         roofline = dict(bound="mfma", achieved=round(ach, 1), peak=MFMA_PEAK_TFLOPS[dtype], unit="TFLOP/s",
@@ -267,31 +304,49 @@ def main():
         roofline["mfma_probe_tflops"] = {"zeros": round(rl.runlora_probe_mfma(False), 1),
                                          "random": round(rl.runlora_probe_mfma(True), 1)}
         roofline["frac_of_random_data_probe"] = round(ach / roofline["mfma_probe_tflops"]["random"], 4)
-    roofline.update(traffic=TRAFFIC_BYTES.get((args.workload, kname)), kernel=kname,
+    roofline.update(traffic=traffic_from_profile(args.workload, kname), kernel=kname,
                     products=sorted(dom["what"]), launches_per_step=dom["launches"] / args.steps,
+                    kernels_per_step=dom["kernels"] / args.steps,
                     avg_launch_us=round(dom["us"] / dom["launches"], 2),
+                    gflop_per_launch=round(dom["flops"] / dom["launches"] / 1e9, 2),
+                    avg_main_kernel_us={k: round(v[0] / v[1], 2) for k, v in sorted(dom["by_build"].items())},
                     share_of_kernel_time=round(dom["us"] / total_kernel_us, 3))
-    per_kernel = {"%s/%s" % k: dict(us_per_step=round(g["us"] / args.steps, 1),
-                                    tflops=round(g["flops"] / g["us"] / 1e6, 1),
-                                    alg_gbps=round(g["bytes"] / g["us"] / 1e3, 1)) for k, g in groups.items()}
+    per_kernel = {("%s/%s" % k).rstrip("/"): dict(us_per_step=round(g["us"] / args.steps, 1),
+                                                  tflops=round(g["flops"] / g["us"] / 1e6, 1),
+                                                  alg_gbps=round(g["bytes"] / g["us"] / 1e3, 1)) for k, g in groups.items()}
 
-    # ---- CPU baseline: the oracle's default chain on a bounded token sample ---------------------
+    # ---- llama7b: the same block at the configuration's other ranks (X, W, dY shared; A, B and the rank-r buffers new)
+    extra = {}
+    if args.workload == "llama7b" and not args.rank and not args.no_extra_ranks and not (args.dora or args.vera or args.dropout):
+        for r in (8, 128):
+            lr = with_rank(layers, r)
+            hi = [{"A": synth.store(synth.normal(synth.BASE_SEED, 16 * L.index + synth.STREAM_A, (L.i, L.r), 1.0 / L.i), dtype),
+                   "B": synth.store(synth.normal(synth.BASE_SEED, 16 * L.index + synth.STREAM_B, (L.r, L.o), 0.1 / L.r), dtype)}
+                  for L in lr]
+            st_r = make_state(lr, hi, shared=state)
+            s_sel, s_def = timed(st_r, False), timed(st_r, True)
+            fu = sum(useful_flops(L) for L in lr)
+            extra["r%d" % r] = dict(ms_per_step=round(s_sel * 1e3, 4), ms_per_step_default_chain=round(s_def * 1e3, 4),
+                                    useful_tflops=round(fu / s_sel / 1e12, 2), speedup_over_default_chain=round(s_def / s_sel, 4),
+                                    pairs={st["L"].name: list(st["pair"]) for st in st_r})
+            del st_r
+
+    # ---- CPU baseline: the oracle's default chain on a bounded token sample of the first layer ----
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
         sample = 512
-        t_cpu, fl_cpu = 0.0, 0
-        for L, st in zip(layers, host_inputs):
-            h = {k: synth.widen(v, dtype) for k, v in st.items()}
-            X, dY = h["X"][:sample].copy(), h["dY"][:sample].copy()
-            t0 = time.perf_counter()
-            _, T = oracle.forward(0, X, h["W"], h["A"], h["B"])
-            oracle.backward(0, X, h["W"], h["A"], h["B"], dY, T)
-            t_cpu += time.perf_counter() - t0
-            fl_cpu += rl.runlora_flops(0, 0, sample, L.i, L.o, L.r) + rl.runlora_flops(1, 0, sample, L.i, L.o, L.r)
+        L, st = layers[0], host_inputs[0]
+        h = {k: synth.widen(v, dtype) for k, v in st.items()}
+        X, dY = h["X"][:sample].copy(), h["dY"][:sample].copy()
+        t0 = time.perf_counter()
+        _, T = oracle.forward(0, X, h["W"], h["A"], h["B"])
+        oracle.backward(0, X, h["W"], h["A"], h["B"], dY, T)
+        t_cpu = time.perf_counter() - t0
+        fl_cpu = rl.runlora_flops(0, 0, sample, L.i, L.o, L.r) + rl.runlora_flops(1, 0, sample, L.i, L.o, L.r)
         cpu = dict(value=round(fl_cpu / t_cpu / 1e12, 5), unit="TFLOP/s", cores=oracle.num_threads(), kind="oracle",
-                   sample="default chain fwd+bwd, fp64, first %d of %d tokens of each layer, full weights; %.1f s"
-                          % (sample, layers[0].n, t_cpu))
+                   sample="default chain fwd+bwd, fp64, layer %s (%dx%d, r=%d), first %d of %d tokens, full weights; %.1f s"
+                          % (L.name, L.i, L.o, L.r, sample, L.n, t_cpu))
 
     out = {
         "metric": "LoRA-linear fwd+bwd useful TFLOP/s + speedup over default chain, bf16",
@@ -306,7 +361,7 @@ def main():
         "speedup_over_default_chain": round(sec_def / sec_sel, 4),
         "time_reduction_pct": round(100.0 * (sec_def - sec_sel) / sec_def, 2),
         "useful_gflop_per_step": round(f_useful / 1e9, 2),
-        "per_layer": per_layer, "roofline": roofline, "kernels": per_kernel, "cpu_baseline": cpu,
+        "per_layer": per_layer, "other_ranks": extra, "roofline": roofline, "kernels": per_kernel, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

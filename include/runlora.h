@@ -68,6 +68,7 @@ typedef enum {
   RL_ERR_ALIGN = -6,          /* pointer / ld / dimension alignment rule violated             */
   RL_ERR_ALIAS = -7,          /* an output buffer overlaps an input buffer                    */
   RL_ERR_WORKSPACE = -8,      /* workspace missing or smaller than runlora_workspace_bytes()  */
+                              /* (runlora_last_hip_error() names the size needed)             */
   RL_ERR_UNSUPPORTED = -9,    /* legal request this build does not implement (e.g. merged-W   */
                               /* graphs on an int4 W)                                         */
   RL_ERR_HIP = -10            /* a HIP launch failed; runlora_last_hip_error() has the text   */
@@ -350,12 +351,13 @@ size_t runlora_gemm_workspace_bytes(const rl_gemm_t* g);
  * launch order (up to cap), forgets them, and returns how many it wrote (or a negative status).
  * `what` points to a static string naming the product in the paper's notation; flops = 2*M*N*K of
  * that product; bytes = one read of each operand plus the output (and addend) in the storage
- * dtype.  us is the time between the two events around the step (all of its kernels, e.g. a split
- * contraction's reduce pass, plus a few microseconds of event handling).  After
- * runlora_profile_kernel_times(1) (per thread, off by default) kernel_us is the duration of the
- * step's main kernel alone (the tile GEMM, the streaming kernel or the merge kernel), taken from a
- * second pair of events bound to that kernel's own dispatch: the figure a kernel trace reports for
- * it; us then also holds the handling of those events.  Otherwise kernel_us = us.
+ * dtype.  us is the time between the two events around the step (all of its kernels plus a few microseconds of
+ * event handling).  After runlora_profile_kernel_times(1) (per thread, off by default) every kernel the step
+ * launches (its main kernel, the launch for cut-off tile columns if the plan has one, the reduce pass behind a
+ * split contraction) gets a pair of events bound to its own dispatch: kernel_us is the sum of those kernels'
+ * durations (what a kernel trace reports for them, added up), main_us the first (main) kernel's alone, kernels
+ * how many were timed; us then also holds the handling of those events.  Otherwise kernel_us = main_us = us
+ * and kernels = 0.
  * tile_cfg names the kernel that ran the step: 0..7 as in rl_gemm_t, 8 / 9 / 10 = the streaming kernel with up to
  * 32 / 64 / 128 output columns, 11 = the W + alpha A B kernel (also the default chain's rank-r updates).
  * Events are host objects created at enable and destroyed at disable; no device memory.
@@ -367,6 +369,8 @@ typedef struct {
   int64_t M, N, K;
   int32_t tile_cfg, splits, a_strided, b_kcontig;
   double kernel_us;
+  double main_us;
+  int32_t kernels;
 } rl_step_time_t;
 int runlora_profile_enable(int max_steps);
 int runlora_profile_kernel_times(int on);
@@ -383,7 +387,7 @@ int runlora_profile_disable(void);
 int runlora_probe_mfma(void* scratch, size_t scratch_bytes, int random_data, void* stream, double* tflops);
 
 const char* runlora_strerror(int code);
-const char* runlora_last_hip_error(void); /* text of the last RL_ERR_HIP on this thread */
+const char* runlora_last_hip_error(void); /* text of the last RL_ERR_HIP (and the byte counts of the last RL_ERR_WORKSPACE) on this thread */
 int runlora_version(void);
 
 #ifdef __cplusplus

@@ -75,7 +75,8 @@ class rl_step_time_t(ctypes.Structure):
     _fields_ = [("what", ctypes.c_char_p), ("us", ctypes.c_double), ("flops", ctypes.c_double),
                 ("bytes", ctypes.c_double), ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
                 ("tile_cfg", ctypes.c_int32), ("splits", ctypes.c_int32), ("a_strided", ctypes.c_int32),
-                ("b_kcontig", ctypes.c_int32), ("kernel_us", ctypes.c_double)]
+                ("b_kcontig", ctypes.c_int32), ("kernel_us", ctypes.c_double), ("main_us", ctypes.c_double),
+                ("kernels", ctypes.c_int32)]
 
 
 class RunLoRAError(RuntimeError):
@@ -161,7 +162,7 @@ def _check(code):
     if code != RL_OK:
         L = lib()
         text = L.runlora_strerror(code).decode()
-        if code == RL_ERR_HIP:
+        if code in (RL_ERR_HIP, RL_ERR_WORKSPACE) and L.runlora_last_hip_error():
             text += " (" + L.runlora_last_hip_error().decode() + ")"
         raise RunLoRAError(code, text)
 
@@ -389,12 +390,12 @@ def runlora_profile_collect(cap=4096):
     k = lib().runlora_profile_collect(buf, cap)
     if k < 0:
         _check(k)
-    keys = ("us", "kernel_us", "flops", "bytes", "M", "N", "K", "tile_cfg", "splits", "a_strided", "b_kcontig")
+    keys = ("us", "kernel_us", "main_us", "kernels", "flops", "bytes", "M", "N", "K", "tile_cfg", "splits", "a_strided", "b_kcontig")
     return [dict(what=buf[j].what.decode(), **{f: getattr(buf[j], f) for f in keys}) for j in range(k)]
 
 
 def runlora_profile_kernel_times(on=True):
-    """Also time each step's main kernel alone (rl_step_time_t.kernel_us) in the profile passes of this thread."""
+    """Also time each of a step's kernels alone (rl_step_time_t.kernel_us / main_us) in the profile passes of this thread."""
     _check(lib().runlora_profile_kernel_times(1 if on else 0))
 
 

@@ -99,8 +99,8 @@ Mat weight_mat(const rl_tensor_t* W, int64_t o, bool int4) {
 struct Profiler {
   bool on = false;
   std::vector<hipEvent_t> start, stop;    // around the whole step
-  std::vector<hipEvent_t> kstart, kstop;  // bound to the step's main kernel (launch_main, gemm.hpp)
-  std::vector<char> kbound;
+  std::vector<hipEvent_t> kstart, kstop;  // KernelEvents::kMax pairs per step, bound to its kernels (launch_timed, gemm.hpp)
+  std::vector<char> kbound;               // how many of a step's pairs its launches consumed
   bool kernel_events = false;             // runlora_profile_kernel_times
   std::vector<rl_step_time_t> rec;
   size_t used = 0;
@@ -113,6 +113,8 @@ void describe_step(const Step& s, rl_step_time_t* r) {
     r->what = s.what;
     r->us = 0.0;
     r->kernel_us = 0.0;
+    r->main_us = 0.0;
+    r->kernels = 0;
     r->flops = 2.0 * (double)s.mg.I * (double)s.mg.O * (double)s.mg.R;
     r->bytes = e * (2.0 * (double)s.mg.I * (double)s.mg.O + (double)s.mg.R * (double)(s.mg.I + s.mg.O));
     r->M = s.mg.I; r->N = s.mg.O; r->K = s.mg.R;
@@ -126,6 +128,8 @@ void describe_step(const Step& s, rl_step_time_t* r) {
     r->what = s.what;
     r->us = 0.0;
     r->kernel_us = 0.0;
+    r->main_us = 0.0;
+    r->kernels = 0;
     r->flops = 0.0;
     r->bytes = 0.0;
     for (int w = 0; w < s.nsk; ++w) {
@@ -145,6 +149,8 @@ void describe_step(const Step& s, rl_step_time_t* r) {
   r->what = s.what;
   r->us = 0.0;
   r->kernel_us = 0.0;
+  r->main_us = 0.0;
+  r->kernels = 0;
   r->flops = 2.0 * (double)d.M * (double)d.N * K;
   r->bytes = e * ((double)d.M * K + K * (double)d.N + (double)d.M * (double)d.N * (d.D ? 2.0 : 1.0));
   r->M = d.M; r->N = d.N; r->K = (int64_t)K;
@@ -174,16 +180,24 @@ int run_schedule(const Schedule& sch, char* ws, hipStream_t stream) {
     if (timed) {
       hipError_t e = hipEventRecord(g_prof.start[g_prof.used], stream);
       if (e != hipSuccess) return set_hip_error(e, "profile event");
-      if (g_prof.kernel_events) g_kernel_events = KernelEvents{g_prof.kstart[g_prof.used], g_prof.kstop[g_prof.used]};
+      if (g_prof.kernel_events) {
+        KernelEvents ke;
+        for (int k = 0; k < KernelEvents::kMax; ++k) {
+          ke.start[k] = g_prof.kstart[g_prof.used * KernelEvents::kMax + k];
+          ke.stop[k] = g_prof.kstop[g_prof.used * KernelEvents::kMax + k];
+        }
+        ke.avail = KernelEvents::kMax;
+        g_kernel_events = ke;
+      }
     }
     hipError_t e = s.is_merge ? merge_run(s.d.dtype, s.mg, stream)
                    : s.nsk > 0 ? skinny_run(s.d.dtype, s.nsk, s.sk, s.skplan, partial, stream)
                                : gemm_run(s.d, s.plan, partial, stream);
-    const bool kbound = timed && g_prof.kernel_events && g_kernel_events.start == nullptr;  // consumed by the step's main launch
+    const int kbound = (timed && g_prof.kernel_events) ? g_kernel_events.used : 0;  // pairs the step's launches consumed
     g_kernel_events = KernelEvents{};
     if (e != hipSuccess) return set_hip_error(e, s.what);
     if (timed) {
-      g_prof.kbound[g_prof.used] = kbound ? 1 : 0;
+      g_prof.kbound[g_prof.used] = (char)kbound;
       e = hipEventRecord(g_prof.stop[g_prof.used], stream);
       if (e != hipSuccess) return set_hip_error(e, "profile event");
       describe_step(s, &g_prof.rec[g_prof.used]);
@@ -823,10 +837,10 @@ extern "C" int runlora_gemm(const rl_gemm_t* g, const rl_opts_t* opts) {
 // ---- per-step timing ------------------------------------------------------------------------------
 
 extern "C" int runlora_profile_disable(void) {
-  for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
-  for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
-  for (hipEvent_t e : g_prof.kstart) (void)hipEventDestroy(e);
-  for (hipEvent_t e : g_prof.kstop) (void)hipEventDestroy(e);
+  for (hipEvent_t e : g_prof.start) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : g_prof.stop) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : g_prof.kstart) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : g_prof.kstop) if (e) (void)hipEventDestroy(e);
   g_prof.start.clear();
   g_prof.stop.clear();
   g_prof.kstart.clear();
@@ -844,20 +858,21 @@ extern "C" int runlora_profile_enable(int max_steps) {
   g_prof.start.resize(max_steps);
   g_prof.stop.resize(max_steps);
   g_prof.rec.resize(max_steps);
-  g_prof.kstart.assign(max_steps, nullptr);
-  g_prof.kstop.assign(max_steps, nullptr);
+  constexpr int KM = KernelEvents::kMax;
+  g_prof.start.assign(max_steps, nullptr);
+  g_prof.stop.assign(max_steps, nullptr);
+  g_prof.kstart.assign((size_t)max_steps * KM, nullptr);
+  g_prof.kstop.assign((size_t)max_steps * KM, nullptr);
   g_prof.kbound.assign(max_steps, 0);
   for (int k = 0; k < max_steps; ++k) {
     hipError_t e = hipEventCreate(&g_prof.start[k]);
     if (e == hipSuccess) e = hipEventCreate(&g_prof.stop[k]);
-    if (e == hipSuccess) e = hipEventCreate(&g_prof.kstart[k]);
-    if (e == hipSuccess) e = hipEventCreate(&g_prof.kstop[k]);
+    for (int q = 0; q < KM && e == hipSuccess; ++q) {
+      e = hipEventCreate(&g_prof.kstart[(size_t)k * KM + q]);
+      if (e == hipSuccess) e = hipEventCreate(&g_prof.kstop[(size_t)k * KM + q]);
+    }
     if (e != hipSuccess) {
-      g_prof.start.resize(k);
-      g_prof.stop.resize(k);
-      g_prof.kstart.resize(k);
-      g_prof.kstop.resize(k);
-      runlora_profile_disable();
+      runlora_profile_disable();  // destroys what was created (the rest is still null)
       return set_hip_error(e, "hipEventCreate");
     }
   }
@@ -878,8 +893,15 @@ extern "C" int runlora_profile_collect(rl_step_time_t* out, int cap) {
     hipError_t e = hipEventSynchronize(g_prof.stop[k]);
     float ms = 0.f;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.start[k], g_prof.stop[k]);
-    float kms = ms;
-    if (e == hipSuccess && g_prof.kbound[k]) e = hipEventElapsedTime(&kms, g_prof.kstart[k], g_prof.kstop[k]);
+    float kms = ms, main_ms = ms;
+    const int nk = g_prof.kbound[k];
+    if (nk > 0) kms = 0.f;
+    for (int q = 0; q < nk && e == hipSuccess; ++q) {
+      float one = 0.f;
+      e = hipEventElapsedTime(&one, g_prof.kstart[k * KernelEvents::kMax + q], g_prof.kstop[k * KernelEvents::kMax + q]);
+      kms += one;
+      if (q == 0) main_ms = one;
+    }
     if (e != hipSuccess) {
       g_prof.used = 0;
       return set_hip_error(e, "profile collect");
@@ -888,6 +910,8 @@ extern "C" int runlora_profile_collect(rl_step_time_t* out, int cap) {
       out[written] = g_prof.rec[k];
       out[written].us = (double)ms * 1e3;
       out[written].kernel_us = (double)kms * 1e3;
+      out[written].main_us = (double)main_ms * 1e3;
+      out[written].kernels = nk;
       ++written;
     }
   }

@@ -100,18 +100,23 @@ hipError_t skinny_launch_bf16(int rt, const SkinnyArgs& a, dim3 grid, int splits
 hipError_t skinny_launch_f16(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
 hipError_t skinny_launch_f32(int rt, const SkinnyArgs& a, dim3 grid, int splits, hipStream_t s);
 
-// ---- timing of a step's main kernel ------------------------------------------------------------------
-// While a pair of events is set here (per host thread), the next main kernel launched from this thread (the
-// tile GEMM, the streaming kernel, the merge kernel; not the reduce kernels behind them) is launched with
-// them bound to its own dispatch, so that their difference is that kernel's duration alone, as a kernel
-// trace reports it; the pair is consumed (cleared) by that launch.
-struct KernelEvents { hipEvent_t start = nullptr, stop = nullptr; };
+// ---- timing of a step's kernels ----------------------------------------------------------------------
+// While event pairs are set here (per host thread), every kernel of the step launched from this thread (the tile
+// GEMM, a cut-off tail launch, the streaming kernel, the merge kernel and the reduce kernels behind them) is
+// launched with the next unused pair bound to its own dispatch, so that the pair's difference is that kernel's
+// duration alone, as a kernel trace reports it.  Pair 0 is the step's first (main) kernel.
+struct KernelEvents {
+  static constexpr int kMax = 4;
+  hipEvent_t start[kMax] = {nullptr, nullptr, nullptr, nullptr}, stop[kMax] = {nullptr, nullptr, nullptr, nullptr};
+  int avail = 0, used = 0;
+};
 extern thread_local KernelEvents g_kernel_events;
 template <typename Kern, typename... Args>
-inline void launch_main(Kern kern, dim3 grid, dim3 block, unsigned lds, hipStream_t s, Args... args) {
-  if (g_kernel_events.start != nullptr) {
-    hipExtLaunchKernelGGL(kern, grid, block, lds, s, g_kernel_events.start, g_kernel_events.stop, 0, args...);
-    g_kernel_events = KernelEvents{};
+inline void launch_timed(Kern kern, dim3 grid, dim3 block, unsigned lds, hipStream_t s, Args... args) {
+  KernelEvents& ke = g_kernel_events;
+  if (ke.used < ke.avail) {
+    hipExtLaunchKernelGGL(kern, grid, block, lds, s, ke.start[ke.used], ke.stop[ke.used], 0, args...);
+    ++ke.used;
   } else {
     hipLaunchKernelGGL(kern, grid, block, lds, s, args...);
   }

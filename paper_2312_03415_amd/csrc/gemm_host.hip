@@ -204,17 +204,17 @@ hipError_t splitk_reduce_launch(int dtype, const float* partial, int splits, int
   if (blocks < 1) blocks = 1;
   switch (dtype) {
     case DT_BF16:
-      hipLaunchKernelGGL(splitk_reduce_kernel<__bf16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
+      launch_timed(splitk_reduce_kernel<__bf16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
                          static_cast<__bf16*>(C), ldc, static_cast<const __bf16*>(D), ldd, alpha,
                          static_cast<const __bf16*>(bias), drop.thr, drop.key, drop.cpr);
       break;
     case DT_F16:
-      hipLaunchKernelGGL(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
+      launch_timed(splitk_reduce_kernel<_Float16>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
                          static_cast<_Float16*>(C), ldc, static_cast<const _Float16*>(D), ldd, alpha,
                          static_cast<const _Float16*>(bias), drop.thr, drop.key, drop.cpr);
       break;
     case DT_F32:
-      hipLaunchKernelGGL(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
+      launch_timed(splitk_reduce_kernel<float>, dim3(blocks), dim3(256), 0, s, partial, splits, M, N,
                          static_cast<float*>(C), ldc, static_cast<const float*>(D), ldd, alpha,
                          static_cast<const float*>(bias), drop.thr, drop.key, drop.cpr);
       break;
