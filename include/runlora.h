@@ -171,7 +171,7 @@ typedef struct {
  *          kept elements are scaled by 256/(256-thr).  The forward records thr and seed in *saved and
  *          the backward regenerates the mask from them.  With dropout only RL_FWD_DEFAULT / RL_FWD1 and
  *          RL_BWD_DEFAULT / RL_BWD1 exist (the others merge AB into W or form X^T dY; they return
- *          RL_ERR_UNSUPPORTED), r must be <= 128 and n*i < 2^34.
+ *          RL_ERR_UNSUPPORTED), r must be <= 128 and n * ld(X) < 2^30 (the masked products run on the streaming kernel).
  */
 typedef struct {
   void* stream;
@@ -261,11 +261,17 @@ int runlora_dora_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* 
 size_t runlora_dora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype);
 
 /*
- * Choose the (forward, backward) pair for one layer shape ("choosing best forward and backward
- * computation graph based on FLOPs and time estimations", abstract).  Pure host function,
+ * Choose the (forward, backward) pair of computation graphs for one layer shape, by estimated time
+ * or by operation count (the selection step named in the abstract).  Pure host function,
  * thread-safe, no HIP call.  Uses the time model unless the environment variable
  * RUNLORA_CRITERION=flops asks for the Table 1 FLOP criterion.  dtype is the activation dtype;
  * pass RL_INT4_G64 to restrict the choice to the graphs an int4 W supports.
+ * Debugging overrides: RUNLORA_FORCE_FWD=<rl_fwd_variant_t id> and RUNLORA_FORCE_BWD=<rl_bwd_variant_t
+ * id> in the environment pin that side of the pair.  The other side stays the selector's, except that
+ * it is moved to keep the pair legal (a forced default backward takes the default forward with it; a
+ * forced non-default forward turns a selected default backward into RL_BWD1).  RL_ERR_VARIANT if a
+ * value is not an id or both are forced to an illegal pair, RL_ERR_UNSUPPORTED if a forced graph does
+ * not exist for an int4 W.  runlora_select_by ignores them.
  */
 int runlora_select(int64_t n_tokens, int64_t d_in, int64_t d_out, int64_t r, int dtype,
                    int* fwd_variant, int* bwd_variant);
@@ -296,7 +302,10 @@ double runlora_model_time_us(int is_bwd, int variant, int64_t n, int64_t i, int6
 size_t runlora_saved_bytes(int fwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype, int keep_merged);
 
 /* Scratch bytes needed by a forward variant (bwd < 0), a backward variant (fwd < 0), or the
- * larger of the two, for a dense W of the layer dtype.  0 for an unknown variant or dtype. */
+ * larger of the two, for a dense W of the layer dtype and tensors with dense rows (ld = columns).
+ * Which kernel a rank-r product runs on depends on its operands' extents in memory, so a call on
+ * tensors with padded rows whose extent reaches 2 GiB may need more: it then returns
+ * RL_ERR_WORKSPACE and runlora_last_hip_error() names the size.  0 for an unknown variant or dtype. */
 size_t runlora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r,
                                int dtype);
 /* Same with W's dtype explicit: w_dtype = dtype (dense) or RL_INT4_G64. */

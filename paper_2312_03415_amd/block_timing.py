@@ -4,13 +4,12 @@ on every attention and MLP linear, only the way the adapter layers are computed 
 
     python -m paper_2312_03415_amd.block_timing --model llama7b --batch 4 --seq 2048 --rank 32
 
-Three ways to run the same block on the same synthetic weights and inputs:
+Two ways to run the same block on the same synthetic weights and inputs:
   runlora   every linear is a RunLoRALinear with the pair runlora_select picks for its shape
   default   the same modules pinned to the default chain (pair (0, 0)): this library's kernels, one launch
             per product, XA kept for the backward
-  torch     x @ W + bias + s (x @ A) @ B under torch's autograd (the vendor GEMM library), for context
 
-Attention, normalisation and activation are torch's own operators in all three; weights are N(0, 1/d_in),
+Attention, normalisation and activation are torch's own operators in both; weights are N(0, 1/d_in),
 inputs N(0, 1), the upstream gradient N(0, 1); no dataset or checkpoint is involved.  Prints one JSON line.
 """
 import argparse
@@ -30,23 +29,6 @@ MODELS = {
     "opt1.3b": dict(d=2048, heads=32, ffn=8192, gated=False, bias=True, rms=False),
     "opt6.7b": dict(d=4096, heads=32, ffn=16384, gated=False, bias=True, rms=False),
 }
-
-
-class TorchLoRALinear(nn.Module):
-    """The adapter layer as plain torch operators (weight orientation [d_in, d_out] like RunLoRALinear)."""
-
-    def __init__(self, weight, r, alpha, bias):
-        super().__init__()
-        d_in, d_out = weight.shape
-        self.weight = nn.Parameter(weight, requires_grad=False)
-        self.bias = nn.Parameter(bias, requires_grad=False) if bias is not None else None
-        self.lora_A = nn.Parameter(torch.randn(d_in, r, dtype=weight.dtype, device=weight.device) / math.sqrt(d_in))
-        self.lora_B = nn.Parameter(torch.zeros(r, d_out, dtype=weight.dtype, device=weight.device))
-        self.scale = alpha / r
-
-    def forward(self, x):
-        y = x @ self.weight + ((x @ self.lora_A) @ self.lora_B) * self.scale
-        return y if self.bias is None else y + self.bias
 
 
 class RMSNorm(nn.Module):
@@ -98,10 +80,7 @@ def build_block(cfg, kind, r, alpha, dtype, device, seed):
         bias = (torch.randn(d_out, generator=g) * 0.02).to(dtype).to(device) if cfg["bias"] else None
         A = (torch.randn(d_in, r, generator=g) / math.sqrt(d_in)).to(dtype).to(device)
         B = (torch.randn(r, d_out, generator=g) * math.sqrt(0.1 / r)).to(dtype).to(device)
-        if kind == "torch":
-            lin = TorchLoRALinear(w, r, alpha, bias)
-        else:
-            lin = RunLoRALinear(w, r, alpha, bias, pair=(0, 0) if kind == "default" else None)
+        lin = RunLoRALinear(w, r, alpha, bias, pair=(0, 0) if kind == "default" else None)
         with torch.no_grad():
             lin.lora_A.copy_(A)
             lin.lora_B.copy_(B)
@@ -139,7 +118,7 @@ def main(argv=None):
     ap.add_argument("--dtype", choices=("bf16", "f16"), default="bf16")
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--kinds", default="runlora,default,torch")
+    ap.add_argument("--kinds", default="runlora,default")
     args = ap.parse_args(argv)
 
     if not torch.cuda.is_available():
@@ -156,6 +135,8 @@ def main(argv=None):
            "dtype": args.dtype, "data": "synthetic", "iters": args.iters, "ms_fwd_bwd": {}}
     ys = {}
     for kind in args.kinds.split(","):
+        if kind not in ("runlora", "default"):
+            raise SystemExit(f"unknown kind {kind!r}")
         block = build_block(cfg, kind, args.rank, alpha, dtype, device, seed=7)
         x = x0.clone().requires_grad_(True)
         ms, ys[kind] = time_block(block, x, dy, args.iters, args.warmup)
@@ -167,15 +148,12 @@ def main(argv=None):
         torch.cuda.empty_cache()
     t = out["ms_fwd_bwd"]
     if "runlora" in t:
-        for base in ("default", "torch"):
-            if base in t:
-                out[f"speedup_vs_{base}"] = round(t[base] / t["runlora"], 4)
-                out[f"saving_vs_{base}_pct"] = round(100.0 * (t[base] - t["runlora"]) / t[base], 2)
-        # the three blocks compute the same function: report how far the outputs are apart
-        for base in ("default", "torch"):
-            if base in ys:
-                d = (ys["runlora"].double() - ys[base].double()).norm() / ys[base].double().norm()
-                out[f"rel_diff_vs_{base}"] = float(f"{d.item():.3e}")
+        if "default" in t:
+            out["speedup_vs_default"] = round(t["default"] / t["runlora"], 4)
+            out["saving_vs_default_pct"] = round(100.0 * (t["default"] - t["runlora"]) / t["default"], 2)
+            # both blocks compute the same function: report how far the outputs are apart
+            d = (ys["runlora"].double() - ys["default"].double()).norm() / ys["default"].double().norm()
+            out["rel_diff_vs_default"] = float(f"{d.item():.3e}")
     print(json.dumps(out))
     return out
 

@@ -102,8 +102,6 @@ def main():
             tiles[fam][cfg] = dict(tk=tk, fix=sum(fix) / 3.0, fix_d=fix_d)
             print(fam, NAMES[cfg], [round(v, 3) for v in tk], round(tiles[fam][cfg]["fix"], 2), round(fix_d, 2), flush=True)
 
-    slow = 0.0  # partial and second-segment K tiles cost what any other K tile costs
-
     # W + AB kernel: per-step event times of the merged forward on two sizes -> rate and fixed cost
     def merge_time(i, o, r=32, n=256, sets=4):
         X = torch.randn(n, i, device="cuda").to(bf)
@@ -163,7 +161,6 @@ def main():
   static const ModelConstants c = {
       {
 %s},
-      %.2f,
       {%.2f, %.2f},
       %.2f,
       %.2f,
@@ -175,7 +172,7 @@ def main():
 }
 
 }  // namespace rl
-""" % (body, slow, rates[0], rates[1], sum(fixes) / 2.0, reduce_tbps, launch, merge_tbps, merge_fix)
+""" % (body, rates[0], rates[1], sum(fixes) / 2.0, reduce_tbps, launch, merge_tbps, merge_fix)
     with open(args.out, "w") as fh:
         fh.write(out)
     print("wrote", args.out)

@@ -216,7 +216,10 @@ uint32_t drop_key_of(uint32_t seed) {
 
 int check_workspace(const Schedule& sch, const rl_opts_t* opts) {
   if (sch.workspace_bytes == 0) return RL_OK;
-  if (!opts || !opts->workspace || opts->workspace_bytes < sch.workspace_bytes) return RL_ERR_WORKSPACE;
+  if (!opts || !opts->workspace || opts->workspace_bytes < sch.workspace_bytes) {
+    std::snprintf(g_hip_error, sizeof(g_hip_error), "this call needs a workspace of %zu bytes", sch.workspace_bytes);
+    return RL_ERR_WORKSPACE;
+  }
   if ((reinterpret_cast<uintptr_t>(opts->workspace) & 255) != 0) return RL_ERR_ALIGN;
   return RL_OK;
 }
@@ -251,7 +254,7 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
   L.wcol = g_wcol;
   if (opts && opts->dropout_p != 0.f) {
     if (!(opts->dropout_p > 0.f && opts->dropout_p < 1.f)) return RL_ERR_SHAPE;
-    if (variant == RL_FWD2 || r > 128 || n * i >= (1LL << 34)) return RL_ERR_UNSUPPORTED;
+    if (variant == RL_FWD2 || r > 128 || n * X->ld >= (1LL << 30)) return RL_ERR_UNSUPPORTED;
     int thr = (int)(opts->dropout_p * 256.f + 0.5f);
     thr = thr < 1 ? 1 : (thr > 255 ? 255 : thr);
     L.drop_thr = (uint32_t)thr;
@@ -283,7 +286,9 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
     if (saved->ldt < r) return RL_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(saved->T) & 15) != 0 || saved->ldt % q != 0) return RL_ERR_ALIGN;
     Range rt = range_of(saved->T, n, saved->ldt, r, esz);
-    if (overlap(rt, ry) || overlap(rt, range_of(X->data, n, X->ld, i, esz))) return RL_ERR_ALIAS;
+    if (overlap(rt, ry) || overlap(rt, range_of(X->data, n, X->ld, i, esz)) || overlap(rt, weight_range(W, i, o, esz, w_int4)) ||
+        overlap(rt, range_of(A->data, i, A->ld, r, esz)) || overlap(rt, range_of(B->data, r, B->ld, o, esz)))
+      return RL_ERR_ALIAS;
     op.T.ptr = saved->T;
     op.T.ld = saved->ldt;
   }
@@ -371,7 +376,7 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   L.wcol = g_wcol;
   if (saved->dropout_thr != 0u) {
     if (saved->dropout_thr > 255u) return RL_ERR_SAVED_MISMATCH;
-    if (variant > RL_BWD1 || r > 128 || n * i >= (1LL << 34)) return RL_ERR_UNSUPPORTED;
+    if (variant > RL_BWD1 || r > 128 || n * saved->ldx >= (1LL << 30)) return RL_ERR_UNSUPPORTED;
     L.drop_thr = saved->dropout_thr;
     L.drop_key = drop_key_of(saved->dropout_seed);
   }
@@ -703,12 +708,17 @@ extern "C" size_t runlora_workspace_bytes_w(int fwd, int bwd, int64_t n, int64_t
   LayerDims L{n, i, o, r, dt, w_dtype == RL_INT4_G64};
   size_t need = 0;
   Schedule sch;
+  // dense rows (ld = columns): which kernel a rank-r product runs on, and with it the scratch, depends on the
+  // operands' extents; a call on tensors with padded rows may need more and says how much (RL_ERR_WORKSPACE)
   if (fwd >= 0) {
     FwdOperands op;
+    op.X.ld = i; op.W.ld = o; op.A.ld = r; op.B.ld = o; op.Y.ld = o; op.T.ld = r; op.M.ld = o;
     if (build_forward(fwd, L, op, nullptr, &sch) && sch.workspace_bytes > need) need = sch.workspace_bytes;
   }
   if (bwd >= 0) {
     BwdOperands op;
+    op.dY.ld = o; op.X.ld = i; op.W.ld = o; op.A.ld = r; op.B.ld = o; op.T.ld = r; op.dX.ld = i; op.dA.ld = r; op.dB.ld = o;
+    op.M.ld = o;
     if (build_backward(bwd, L, op, nullptr, &sch) && sch.workspace_bytes > need) need = sch.workspace_bytes;
   }
   return need;

@@ -142,12 +142,15 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   if (d.Bscale != nullptr && cfg != CFG_BIG && cfg != CFG_MID && cfg != CFG_MC3) return hipErrorInvalidValue;  // see gemm_plan_int4
   if (d.Bscale != nullptr && d.a_strided) return hipErrorInvalidValue;
   if (cfg == CFG_MC3 || cfg == CFG_MC4) {
-    // the matrix-core kernel addresses each operand with 32-bit byte offsets, clamps a strided
-    // operand's last columns to [dim-8, dim) and wants every K slice to hold at least one K tile
+    // the matrix-core kernel addresses each operand with 32-bit byte offsets into a buffer descriptor whose
+    // extent is the operand's bytes plus 3 KB (gemm_mc.hpp, kBias): the 16-bit elements of an operand, rows x ld,
+    // must stay below 2^31 - 2048 so that neither wraps; it also clamps a strided operand's last columns to
+    // [dim-8, dim) and wants every K slice to hold at least one K tile
     bool ok = d.dtype != DT_F32 && plan.bk == 32;
+    constexpr int64_t kMaxElems = (1LL << 31) - 2048;
     for (int s = 0; s < d.nseg; ++s) {
       const int64_t a_rows = d.a_strided ? d.K[s] : d.M, b_rows = d.b_kcontig ? d.N : d.K[s];
-      if (a_rows * d.lda[s] >= (1LL << 31) || b_rows * d.ldb[s] >= (1LL << 31)) ok = false;
+      if (a_rows * d.lda[s] >= kMaxElems || b_rows * d.ldb[s] >= kMaxElems) ok = false;
     }
     if ((d.a_strided && d.M < 8) || (!d.b_kcontig && d.N < 8)) ok = false;
     if (!ok) cfg = CFG_BIG;
@@ -268,7 +271,6 @@ hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPla
   a.nprob = nprob;
   a.mr = plan.mr;
   if (plan.mr != 1 && !(plan.mr == 2 && nprob == 2 && d[0].a_strided && d[1].a_strided && plan.rt <= 2)) return hipErrorInvalidValue;
-  int64_t blocks = 0;
   float* part = scratch;
   for (int w = 0; w < nprob; ++w) {
     SkinnyProblem& P = a.p[w];
@@ -297,12 +299,10 @@ hipError_t skinny_run(int dtype, int nprob, const SkinnyDesc* d, const SkinnyPla
       P.partial = part;
       part += (size_t)plan.splits * (size_t)d[w].M * (size_t)d[w].N;
     }
-    blocks += P.row_blocks;
   }
   // one slot list per XCD: ceil(R0/8) + ceil(R1/8) workgroups on each (see skinny_kernel)
   int64_t per_xcd = 0;
   for (int w = 0; w < nprob; ++w) per_xcd += (a.p[w].row_blocks + 7) / 8;
-  (void)blocks;
   dim3 grid((unsigned)(8 * per_xcd), (unsigned)plan.splits, 1);
   switch (dtype) {
     case DT_BF16: return skinny_launch_bf16(plan.rt, a, grid, plan.splits, stream);

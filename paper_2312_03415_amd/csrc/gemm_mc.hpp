@@ -7,15 +7,17 @@
 //    16 accumulator blocks of 32x32 = 256 accumulator registers, which leaves the other half of
 //    the 512-entry register file for double-buffered operand fragments.  A K step (16) is
 //    16 MFMAs fed by 8 LDS reads of 16 bytes: half the LDS traffic per MFMA of a 128x64 sub-tile.
-//  - K tile = 32.  LDS is a ring of NS (4) stages of 32 KB (A 256x32 + B 256x32); global memory
-//    goes straight to LDS (16-byte LDS-DMA loads, no register staging).  Three K tiles are in
-//    flight while one is multiplied, so a load has ~3000 MFMA cycles to land.
+//  - K tile = 32.  LDS is a ring of NS = 3 stages of 32 KB (A 256x32 + B 256x32; 4 and 5 stages measured the
+//    same, and the LDS behind three stages holds the epilogue's staging area); global memory goes straight to
+//    LDS (16-byte LDS-DMA loads, no register staging).  While one K tile is multiplied the next one has landed
+//    and the one after it is in flight, so a load has ~2000 MFMA cycles to land.
 //  - The load stream is continuous over everything a persistent workgroup does: when the K tiles
 //    of one output tile are exhausted it goes on with the next output tile, so the first tiles of
 //    the next output tile arrive while the current one is being stored.
-//  - One s_barrier per K tile, placed among the MFMAs of the tile's second K step.  It orders
+//  - One s_barrier per K tile, placed behind the first MFMA of the tile's second K step.  It orders
 //    "everyone has read stage s" before "stage s is refilled" and "my loads of tile t+1 have
-//    landed" (s_waitcnt vmcnt(8(NS-2)), loads return in order) before "anyone reads tile t+1".
+//    landed" (s_waitcnt vmcnt(8 (NS-2)): the eight loads of a K tile per wave return in order, so at most one
+//    tile's worth outstanding means tile t+1 is in) before "anyone reads tile t+1".
 //  - A partial K tile (K % 32 != 0, e.g. the rank-r segment with r = 8 or 16) takes the same route:
 //    its out-of-range 16-byte chunks are fetched from an in-range address of the same row and the
 //    fragment registers that hold k >= K are zeroed on both operands after the LDS read.

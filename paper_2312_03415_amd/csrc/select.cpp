@@ -1,6 +1,6 @@
 // Selector: Table 1 FLOP counts, a per-kernel time model for MI355X, and the choice of the
-// (forward, backward) pair ("choosing best forward and backward computation graph based on FLOPs
-// and time estimations", abstract of arxiv 2312.03415).  Pure host code, no HIP call.
+// (forward, backward) pair of computation graphs by operation count or by estimated time (the
+// selection step named in the abstract of arxiv 2312.03415).  Pure host code, no HIP call.
 #include <cstdlib>
 #include <cstring>
 
@@ -66,13 +66,12 @@ static double gemm_time_us(const GemmDesc& d, const GemmPlan& p) {
   const int64_t kt0 = (d.K[0] + p.bk - 1) / p.bk, kt1 = d.nseg > 1 ? (d.K[1] + p.bk - 1) / p.bk : 0;
   double ktiles = (double)(kt0 + kt1);
   if (p.splits > 1) ktiles = (double)p.tiles_per_split;
-  double slow = 0;
-  (void)kt1;  // the matrix-core kernel runs partial and second-segment K tiles at the speed of any other
+  // (partial and second-segment K tiles run at the speed of any other)
   const bool addend = d.D != nullptr && p.splits == 1;
   // int4 B on the matrix-core kernel: the dequantisation behind the MFMAs costs ~20 % per K tile
   // (measured on the 5120 x 13824 layer)
   const double q = (d.b_int4 && p.cfg == CFG_MC3) ? 1.2 : 1.0;
-  double us = rounds * (ktiles * tm.tk_us[lay] * share * q + (addend ? tm.tfix_d_us : tm.tfix_us) + slow * mc.slow_tile_us);
+  double us = rounds * (ktiles * tm.tk_us[lay] * share * q + (addend ? tm.tfix_d_us : tm.tfix_us));
   if (p.splits > 1)
     us += (double)d.M * d.N * (4.0 * (p.splits + 1) + (d.D ? e : 0.0) + e) / (mc.reduce_tbps * 1e12) * 1e6 + mc.launch_us;
   return us;
@@ -194,8 +193,32 @@ extern "C" int runlora_select_by(int criterion, int64_t n, int64_t i, int64_t o,
   return RL_OK;
 }
 
+// value of a debugging override (a small non-negative integer in the environment), or -1
+static int env_variant(const char* name, int max_id) {
+  const char* v = std::getenv(name);
+  if (!v || !*v) return -1;
+  char* end = nullptr;
+  const long id = std::strtol(v, &end, 10);
+  return (end && *end == '\0' && id >= 0 && id <= max_id) ? (int)id : -2;  // -2: set but not a variant id
+}
+
 extern "C" int runlora_select(int64_t n, int64_t i, int64_t o, int64_t r, int dtype, int* fwd, int* bwd) {
   const char* env = std::getenv("RUNLORA_CRITERION");
   int criterion = (env && std::strcmp(env, "flops") == 0) ? 0 : 1;
-  return runlora_select_by(criterion, n, i, o, r, dtype, fwd, bwd);
+  int rc = runlora_select_by(criterion, n, i, o, r, dtype, fwd, bwd);
+  if (rc != RL_OK) return rc;
+  // RUNLORA_FORCE_FWD / RUNLORA_FORCE_BWD pin one side of the pair (debugging: run a whole model in one graph)
+  const int ff = env_variant("RUNLORA_FORCE_FWD", RL_FWD2), fb = env_variant("RUNLORA_FORCE_BWD", RL_BWD8);
+  if (ff == -2 || fb == -2) return RL_ERR_VARIANT;
+  if (ff >= 0) *fwd = ff;
+  if (fb >= 0) *bwd = fb;
+  if (ff >= 0 || fb >= 0) {
+    if (*bwd == RL_BWD_DEFAULT && *fwd != RL_FWD_DEFAULT) {
+      if (fb >= 0 && ff >= 0) return RL_ERR_VARIANT;  // the default backward needs the default forward's XA
+      if (fb >= 0) *fwd = RL_FWD_DEFAULT; else *bwd = RL_BWD1;
+    }
+    const bool merged = *fwd == RL_FWD2 || *bwd == RL_BWD4 || *bwd == RL_BWD5 || *bwd == RL_BWD7 || *bwd == RL_BWD8;
+    if (dtype == RL_INT4_G64 && merged) return RL_ERR_UNSUPPORTED;
+  }
+  return RL_OK;
 }

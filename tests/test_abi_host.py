@@ -83,6 +83,26 @@ def test_select_time_model_returns_legal_pairs():
     assert rl.lib().runlora_select(8, 8, 8, 8, rl.RL_F16, None, ctypes.byref(b)) == rl.RL_ERR_NULL
 
 
+def test_select_honours_the_debugging_overrides(monkeypatch):
+    n, i, o, r = 8192, 4096, 4096, 32
+    free = rl.runlora_select(n, i, o, r, rl.RL_BF16)
+    monkeypatch.setenv("RUNLORA_FORCE_FWD", "2")
+    assert rl.runlora_select(n, i, o, r, rl.RL_BF16) == (2, free[1] if free[1] != 0 else 1)
+    monkeypatch.setenv("RUNLORA_FORCE_BWD", "4")
+    assert rl.runlora_select(n, i, o, r, rl.RL_BF16) == (2, 4)
+    assert rl.runlora_select(n, i, o, r, rl.RL_BF16, criterion=1) == free        # runlora_select_by ignores them
+    f, b = ctypes.c_int(), ctypes.c_int()
+    assert rl.lib().runlora_select(n, i, o, r, rl.RL_INT4_G64, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_UNSUPPORTED
+    monkeypatch.setenv("RUNLORA_FORCE_BWD", "0")
+    assert rl.lib().runlora_select(n, i, o, r, rl.RL_BF16, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_VARIANT   # (2, 0) is illegal
+    monkeypatch.delenv("RUNLORA_FORCE_FWD")
+    assert rl.runlora_select(n, i, o, r, rl.RL_BF16) == (0, 0)                    # the default backward brings its forward
+    monkeypatch.setenv("RUNLORA_FORCE_BWD", "nine")
+    assert rl.lib().runlora_select(n, i, o, r, rl.RL_BF16, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_VARIANT
+    monkeypatch.delenv("RUNLORA_FORCE_BWD")
+    assert rl.runlora_select(n, i, o, r, rl.RL_BF16) == free
+
+
 def test_select_with_kept_merged_weight():
     """Criterion 2 prices forward2 + backward4/5 without the second W + AB pass: it may only move the
     choice towards such a pair, never to a slower one under the plain model."""
@@ -186,6 +206,46 @@ def test_forward_rejects_bad_arguments_before_touching_the_gpu():
     assert call_fwd(2, b) == rl.RL_ERR_UNSUPPORTED          # X (W + AB) needs a dense W
     b["W"].scales = 0x50000004
     assert call_fwd(1, b) == rl.RL_ERR_ALIGN
+
+
+def test_workspace_size_holds_for_operands_beyond_two_gib():
+    """An X (or dY) whose extent reaches 2 GiB leaves the streaming kernel (31-bit byte offsets) for the tile GEMM,
+    whose split contraction needs fp32 partials: the size the library reports must be the size the call then asks
+    for.  Checked through the text of RL_ERR_WORKSPACE, which names the need (nothing is launched)."""
+    n, i, o, r = 1 << 19, 4096, 256, 16          # n * i * 2 bytes = 4 GiB
+    L = rl.lib()
+    br = ctypes.byref
+    base, step = 0x10000000000, 0x1000000000
+    small = rl.rl_opts_t(None, 0x70000000, 256)
+
+    def told():
+        return int(re.search(r"(\d+) bytes", L.runlora_last_hip_error().decode()).group(1))
+
+    a = fwd_args(n, i, o, r)
+    for k, name in enumerate(("X", "W", "A", "B", "Y")):
+        a[name].data = base + k * step
+    need = rl.runlora_workspace_bytes(1, -1, n, i, o, r, rl.RL_BF16)
+    assert need >= n * r * 2
+    assert call_fwd(1, a, opts=small) == rl.RL_ERR_WORKSPACE and told() == need
+    # backward1: dA = X^T Z1 over 2^19 tokens falls to the tile GEMM with its contraction split over workgroups
+    dY, W, A, B = T(base, n, o), T(base + step, i, o), T(base + 2 * step, i, r), T(base + 3 * step, r, o)
+    dX, dA, dB = T(base + 4 * step, n, i), T(base + 5 * step, i, r), T(base + 6 * step, r, o)
+    saved = rl.rl_saved_t(1, rl.RL_BF16, n, i, o, r, base + 7 * step, i, None, 0)
+    need = rl.runlora_workspace_bytes(-1, 1, n, i, o, r, rl.RL_BF16)
+    assert need > 2 * n * r * 2                  # Z1, Z2 and fp32 partials
+    assert L.runlora_backward(1, br(dY), br(saved), br(W), br(A), br(B), br(dX), br(dA), br(dB), br(small)) == rl.RL_ERR_WORKSPACE
+    assert told() == need
+    # under LoRA dropout the masked products exist on the streaming kernel only: such an X is refused outright
+    assert call_fwd(1, a, opts=rl.rl_opts_t(None, 0x70000000, 1 << 40, 0.0, None, 0.1, 1)) == rl.RL_ERR_UNSUPPORTED
+
+
+def test_default_forward_checks_its_T_buffer_against_every_input():
+    a = fwd_args()
+    ws = rl.rl_opts_t(None, 0x70000000, 1 << 30)
+    for name in ("X", "W", "A", "B", "Y"):
+        saved = rl.rl_saved_t()
+        saved.T, saved.ldt = a[name].data, 8
+        assert call_fwd(0, a, saved, ws) == rl.RL_ERR_ALIAS, name
 
 
 def test_backward_rejects_bad_arguments_before_touching_the_gpu():

@@ -98,6 +98,35 @@ def test_gemm_exact_on_small_integers():
             assert np.array_equal(to_f64(C), want), (dtype, cfg)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("layout", list(LAYOUTS))
+def test_matrix_core_builds_exact_on_small_integers(layout, dtype):
+    """Every build of the matrix-core kernel on integer-valued inputs, bit for bit against the oracle: 512 x 768
+    outputs (2 x 3 whole tiles: the short epilogue; with the contraction split in two: the fp32-partials epilogue;
+    with a bias of zeros: the general epilogue), 520 x 776 (ragged tiles), K = 32 * 8 + 8 (a partial last K
+    tile) and a second segment of 8."""
+    import torch
+    a_str, b_kc = LAYOUTS[layout]
+    rng = np.random.default_rng(4)
+    K, K2 = 264, 8
+    td = torch_dtype(dtype)
+    for M, N in ((512, 768), (520, 776)):
+        Ah = rng.integers(-2, 3, size=(K, M) if a_str else (M, K)).astype(np.float64)
+        Bh = rng.integers(-2, 3, size=(N, K) if b_kc else (K, N)).astype(np.float64)
+        A2h = rng.integers(-2, 3, size=(K2, M) if a_str else (M, K2)).astype(np.float64)
+        B2h = rng.integers(-2, 3, size=(N, K2) if b_kc else (K2, N)).astype(np.float64)
+        A, B, A2, B2 = (to_device(synth.store(v, dtype), dtype) for v in (Ah, Bh, A2h, B2h))
+        want = oracle.matmul(Ah, Bh, ta=a_str, tb=b_kc) + oracle.matmul(A2h, B2h, ta=a_str, tb=b_kc)
+        assert np.abs(want).max() <= 256   # exact in bf16's 8-bit significand
+        zero_bias = torch.zeros(N, dtype=td, device="cuda")
+        for splits, bias in ((1, None), (2, None), (1, zero_bias), (3, zero_bias)):
+            print(f"case mc-exact layout={layout} dtype={dtype} M={M} N={N} splits={splits} bias={bias is not None}", flush=True)
+            C = torch.full((M, N), float("nan"), dtype=td, device="cuda")
+            rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, A2=A2, B2=B2, tile_cfg=6, splits=splits, bias=bias)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_f64(C), want), (M, N, splits, bias is not None)
+
+
 def test_gemm_strided_rows_and_aliased_addend():
     """Leading dimensions larger than the row length; D aliasing C (the '+=' of the default chain)."""
     import torch

@@ -208,13 +208,13 @@ def test_layer_dropout_in_training_mode():
 
 
 @pytest.mark.parametrize("model", ["opt1.3b", "llama7b"])
-def test_block_timing_script_runs_the_same_block_three_ways(model, capsys):
-    """The decoder-block timing script: RunLoRA layers, the default chain and torch's own operators
-    compute the same block output (bf16 rounding apart) and the script reports one time for each."""
+def test_block_timing_script_runs_the_same_block_both_ways(model, capsys):
+    """The decoder-block timing script: RunLoRA layers and the default chain compute the same block
+    output (bf16 rounding apart) and the script reports one time for each."""
     from paper_2312_03415_amd import block_timing
     out = block_timing.main(["--model", model, "--batch", "1", "--seq", "192", "--rank", "8", "--iters", "2", "--warmup", "1"])
-    assert set(out["ms_fwd_bwd"]) == {"runlora", "default", "torch"} and all(v > 0 for v in out["ms_fwd_bwd"].values())
-    assert out["rel_diff_vs_default"] < 2e-2 and out["rel_diff_vs_torch"] < 2e-2
+    assert set(out["ms_fwd_bwd"]) == {"runlora", "default"} and all(v > 0 for v in out["ms_fwd_bwd"].values())
+    assert out["rel_diff_vs_default"] < 2e-2
     assert len(out["pairs"]) == (7 if model == "llama7b" else 6)
     assert json.loads(capsys.readouterr().out.strip().splitlines()[-1])["model"] == model
 

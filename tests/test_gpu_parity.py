@@ -132,12 +132,18 @@ def test_exact_on_small_integers():
             assert np.array_equal(got[k], want[k]), (f, b, k)
 
 
-def test_run_to_run_identical():
-    """No atomics anywhere: repeated runs give identical bits (token reductions are ordered)."""
-    L = synth.Layer("determinism", 1000, 264, 392, 16, "bf16", 8)
+@pytest.mark.parametrize("shape,pair", [((1000, 264, 392, 16), (1, 1)), ((1000, 264, 392, 16), (2, 4)),
+                                        ((4096, 2048, 2048, 16), (1, 1)), ((4096, 2048, 2048, 16), (2, 3))])
+def test_run_to_run_identical(shape, pair):
+    """No atomics anywhere: repeated runs give identical bits (token reductions and split contractions are summed
+    in a fixed order).  The second shape has 16 x 8 tiles of 256 x 256 at K >= 2048: its Y and dX products run on the
+    matrix-core kernel with the contraction split in two, X^T dY on the 128 x 128 tile GEMM with a split, and its
+    token reductions split K over workgroups."""
+    n, i, o, r = shape
+    L = synth.Layer("determinism", n, i, o, r, "bf16", 8)
     dev, _ = layer_on_device(L)
-    first = run_pair(L, dev, 1, 1)
-    for _ in range(5):
-        again = run_pair(L, dev, 1, 1)
+    first = run_pair(L, dev, *pair)
+    for _ in range(10):
+        again = run_pair(L, dev, *pair)
         for k in first:
             assert np.array_equal(first[k], again[k]), k
