@@ -202,6 +202,25 @@ int runlora_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved
                      rl_tensor_t* dX, rl_tensor_t* dA, rl_tensor_t* dB, const rl_opts_t* opts);
 
 /*
+ * runlora_forward for callers that can neither allocate device memory nor hand over a workspace (code under HIP
+ * graph capture, serving loops and harnesses that forbid hipMalloc): same arguments, same kernels, same results
+ * bit for bit, but the variant's scratch (T = XA of RL_FWD1, W + AB of RL_FWD2, fp32 partials of a split
+ * contraction) lives in a fixed array of RL_STATIC_SCRATCH_BYTES inside the library's device image instead of
+ * opts->workspace, which is ignored.  The call allocates and frees nothing on the device.
+ *   - A call whose variant and shape need more scratch than the array holds returns RL_ERR_WORKSPACE before
+ *     anything is enqueued (runlora_workspace_bytes(variant, -1, ...) tells the need; runlora_last_hip_error()
+ *     has both figures as text).
+ *   - Every GPU the library runs on holds its own copy of the array until the process ends; the copy used is
+ *     that of the calling thread's current device.
+ *   - All calls on one GPU share that GPU's array, and it keeps the last call's contents (no call relies on
+ *     them: every scratch element is written before it is read).  Calls that may overlap on one GPU (different
+ *     streams, or several host threads) race on it: order them on one stream.
+ */
+#define RL_STATIC_SCRATCH_BYTES (16u << 20)
+int runlora_forward_static(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
+                           const rl_tensor_t* B, rl_tensor_t* Y, rl_saved_t* saved, const rl_opts_t* opts);
+
+/*
  * VeRA on the same computation graphs.  The paper's conclusion names VeRA among the LoRA variants its
  * method extends to and gives no formulas; the layer here is the published one in this header's
  * orientation: A [i,r] and B [r,o] frozen (random, shared between layers), trainable vectors d [r], b [o],

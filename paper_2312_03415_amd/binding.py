@@ -29,7 +29,7 @@ RL_ERR_NULL, RL_ERR_SHAPE, RL_ERR_DTYPE, RL_ERR_VARIANT, RL_ERR_SAVED_MISMATCH =
 RL_ERR_ALIGN, RL_ERR_ALIAS, RL_ERR_WORKSPACE, RL_ERR_UNSUPPORTED, RL_ERR_HIP = -6, -7, -8, -9, -10
 
 EXPORTS = (
-    "runlora_forward", "runlora_backward", "runlora_select", "runlora_select_by", "runlora_flops",
+    "runlora_forward", "runlora_forward_static", "runlora_backward", "runlora_select", "runlora_select_by", "runlora_flops",
     "runlora_model_time_us", "runlora_workspace_bytes", "runlora_workspace_bytes_w", "runlora_saved_bytes",
     "runlora_strerror", "runlora_last_hip_error",
     "runlora_version", "runlora_gemm", "runlora_gemm_workspace_bytes",
@@ -105,6 +105,8 @@ def lib():
     i64, ci, ip = ctypes.c_int64, ctypes.c_int, ctypes.POINTER(ctypes.c_int)
     L.runlora_forward.argtypes = [ci, tp, tp, tp, tp, tp, sp, op]
     L.runlora_forward.restype = ci
+    L.runlora_forward_static.argtypes = [ci, tp, tp, tp, tp, tp, sp, op]
+    L.runlora_forward_static.restype = ci
     L.runlora_backward.argtypes = [ci, tp, sp, tp, tp, tp, tp, tp, tp, op]
     L.runlora_backward.restype = ci
     vp = ctypes.c_void_p
@@ -241,6 +243,22 @@ def runlora_forward(variant, X, W, A, B, Y, saved, workspace=None, stream=None, 
     o = _opts(workspace, stream, scale, bias, dropout_p, dropout_seed)
     _check(lib().runlora_forward(variant, _ref(dx), _ref(dw), _ref(da), _ref(db), _ref(dy), ctypes.byref(saved),
                                  ctypes.byref(o)))
+    return Y
+
+
+STATIC_SCRATCH_BYTES = 16 << 20  # RL_STATIC_SCRATCH_BYTES of runlora.h
+
+
+def runlora_forward_static(variant, X, W, A, B, Y, saved, stream=None, scale=None, bias=None, dropout_p=None,
+                           dropout_seed=0):
+    """runlora_forward with the variant's scratch in the library's fixed device array (no workspace argument, no
+    device allocation); raises RL_ERR_WORKSPACE if the call needs more than STATIC_SCRATCH_BYTES."""
+    if bias is not None and (bias.dtype != X.dtype or bias.numel() != Y.shape[1]):
+        raise ValueError("bias must have d_out elements of the activation dtype")
+    dx, dw, da, db, dy = (tensor_desc(t) for t in (X, W, A, B, Y))
+    o = _opts(None, stream, scale, bias, dropout_p, dropout_seed)
+    _check(lib().runlora_forward_static(variant, _ref(dx), _ref(dw), _ref(da), _ref(db), _ref(dy), ctypes.byref(saved),
+                                        ctypes.byref(o)))
     return Y
 
 

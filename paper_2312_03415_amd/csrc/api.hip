@@ -1,6 +1,7 @@
 // C ABI of the library (include/runlora.h): argument checks, variant schedules -> launches.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "../../include/runlora.h"
@@ -9,6 +10,13 @@
 #include "vera.hpp"
 
 using namespace rl;
+
+// Scratch of runlora_forward_static: a fixed array in this library's device image instead of a caller-provided
+// workspace (each GPU the library runs on holds its own copy until the process ends).  In host code the name is a
+// stand-in, not a device address: the address is looked up once per device (static_scratch below) and that
+// pointer is what the host hands to the kernels.
+constexpr size_t kStaticScratchBytes = (size_t)RL_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -214,6 +222,27 @@ uint32_t drop_key_of(uint32_t seed) {
   return x;
 }
 
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// address of this device's copy of `scratch` (device = the calling thread's current device)
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return set_hip_error(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return RL_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return set_hip_error(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return RL_OK;
+}
+
 int check_workspace(const Schedule& sch, const rl_opts_t* opts) {
   if (sch.workspace_bytes == 0) return RL_OK;
   if (!opts || !opts->workspace || opts->workspace_bytes < sch.workspace_bytes) {
@@ -226,8 +255,10 @@ int check_workspace(const Schedule& sch, const rl_opts_t* opts) {
 
 }  // namespace
 
-extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
-                               const rl_tensor_t* B, rl_tensor_t* Y, rl_saved_t* saved, const rl_opts_t* opts) {
+namespace {
+// use_static: the scratch is this device's copy of the library's fixed array instead of opts->workspace
+int forward_impl(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A, const rl_tensor_t* B,
+                 rl_tensor_t* Y, rl_saved_t* saved, const rl_opts_t* opts, bool use_static) {
   if (!X || !W || !A || !B || !Y || !saved) return RL_ERR_NULL;
   if (variant < RL_FWD_DEFAULT || variant > RL_FWD2) return RL_ERR_VARIANT;
   const int dtype = X->dtype;
@@ -294,8 +325,25 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
   }
   Schedule sch;
   char* ws = opts ? static_cast<char*>(opts->workspace) : nullptr;
-  if (!build_forward(variant, L, op, ws, &sch)) return RL_ERR_VARIANT;
-  if ((rc = check_workspace(sch, opts)) != RL_OK) return rc;
+  if (use_static) {
+    // size the schedule first (no HIP call yet), then lay it out in the fixed array
+    if (!build_forward(variant, L, op, nullptr, &sch)) return RL_ERR_VARIANT;
+    if (sch.workspace_bytes > kStaticScratchBytes) {
+      std::snprintf(g_hip_error, sizeof(g_hip_error), "runlora_forward_static: this call needs %zu bytes of scratch, the fixed array holds %zu",
+                    sch.workspace_bytes, kStaticScratchBytes);
+      return RL_ERR_WORKSPACE;
+    }
+    void* p = nullptr;
+    ws = nullptr;
+    if (!g_dry_run && sch.workspace_bytes > 0) {
+      if ((rc = static_scratch(&p)) != RL_OK) return rc;
+      ws = static_cast<char*>(p);
+    }
+    if (!build_forward(variant, L, op, ws, &sch)) return RL_ERR_VARIANT;
+  } else {
+    if (!build_forward(variant, L, op, ws, &sch)) return RL_ERR_VARIANT;
+    if ((rc = check_workspace(sch, opts)) != RL_OK) return rc;
+  }
 
   hipStream_t stream = opts ? static_cast<hipStream_t>(opts->stream) : nullptr;
   rc = run_schedule(sch, ws, stream);
@@ -312,6 +360,17 @@ extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tenso
   if (variant != RL_FWD_DEFAULT) { saved->T = nullptr; saved->ldt = 0; }
   if (variant != RL_FWD2) { saved->M = nullptr; saved->ldm = 0; }
   return RL_OK;
+}
+}  // namespace
+
+extern "C" int runlora_forward(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
+                               const rl_tensor_t* B, rl_tensor_t* Y, rl_saved_t* saved, const rl_opts_t* opts) {
+  return forward_impl(variant, X, W, A, B, Y, saved, opts, false);
+}
+
+extern "C" int runlora_forward_static(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A,
+                                      const rl_tensor_t* B, rl_tensor_t* Y, rl_saved_t* saved, const rl_opts_t* opts) {
+  return forward_impl(variant, X, W, A, B, Y, saved, opts, true);
 }
 
 extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_saved_t* saved, const rl_tensor_t* W,

@@ -248,6 +248,33 @@ def test_default_forward_checks_its_T_buffer_against_every_input():
         assert call_fwd(0, a, saved, ws) == rl.RL_ERR_ALIAS, name
 
 
+def test_static_scratch_forward_checks_arguments_and_size_before_touching_the_gpu():
+    """runlora_forward_static: the same argument checks as runlora_forward, and a call that needs more scratch than
+    the library's fixed array is refused with both figures in the error text; no workspace argument is needed."""
+    L = rl.lib()
+    ref = lambda x: ctypes.byref(x) if x is not None else None
+
+    def call(variant, a):
+        return L.runlora_forward_static(variant, ref(a["X"]), ref(a["W"]), ref(a["A"]), ref(a["B"]), ref(a["Y"]),
+                                        ctypes.byref(rl.rl_saved_t()), None)
+
+    a = fwd_args()
+    assert call(9, a) == rl.RL_ERR_VARIANT
+    b = fwd_args(); b["W"].rows = 40
+    assert call(1, b) == rl.RL_ERR_SHAPE
+    b = fwd_args(); b["Y"].data = b["X"].data
+    assert call(1, b) == rl.RL_ERR_ALIAS
+    assert call(0, a) == rl.RL_ERR_NULL                      # the default chain still needs the caller's T buffer
+    big = fwd_args(512, 4096, 4096, 16)                      # forward2 would form W + AB: 32 MiB
+    assert rl.runlora_workspace_bytes(2, -1, 512, 4096, 4096, 16, rl.RL_BF16) > rl.STATIC_SCRATCH_BYTES
+    assert call(2, big) == rl.RL_ERR_WORKSPACE
+    text = L.runlora_last_hip_error().decode()
+    assert str(rl.STATIC_SCRATCH_BYTES) in text and str(rl.runlora_workspace_bytes(2, -1, 512, 4096, 4096, 16, rl.RL_BF16)) in text
+    header = open(os.path.join(ROOT, "include", "runlora.h")).read()
+    m = re.search(r"#define RL_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", header)
+    assert m and int(m.group(1)) << int(m.group(2)) == rl.STATIC_SCRATCH_BYTES
+
+
 def test_backward_rejects_bad_arguments_before_touching_the_gpu():
     n, i, o, r = 64, 32, 48, 8
     base, step = 0x10000000, 0x1000000
