@@ -340,13 +340,14 @@ size_t runlora_workspace_bytes_w(int fwd, int bwd, int64_t n, int64_t i, int64_t
  *              (a_strided = 1 with b_kcontig = 1 is not provided)
  *   K2 = 0     no second segment.   D = NULL: no addend (D may alias C).
  *   tile_cfg   -1 = library heuristic; 0..5 = 256x256, 128x128, 128x32, 128x64, 32x128, 64x128
- *              output tile per workgroup in the generic engine; 6 / 7 = the matrix-core kernel for
- *              the large contractions (256x256 tile, K tile 32, 4 wavefronts, LDS ring of 3
- *              stages filled by LDS-DMA loads, epilogue staged through LDS so that whole row
- *              segments are stored; 16-bit types, fp32 falls back to 0; a call whose M and N are
- *              multiples of 256 and that has no addend, bias or alpha runs a build with a shorter
- *              epilogue, same results; 7 once meant a ring of 4 stages, which measured the same,
- *              and is kept as a second name of 6); 8 = the
+ *              output tile per workgroup in the generic engine; 6 / 7 = the matrix-core kernels for
+ *              the large contractions (256x256 tile, 4 wavefronts, operands straight from global
+ *              memory to LDS by LDS-DMA loads, epilogue staged through LDS so that whole row segments
+ *              are stored; 16-bit types, fp32 falls back to 0; a call whose M and N are multiples of
+ *              256 and that has no addend, bias or alpha runs a build with a shorter epilogue, same
+ *              results): 6 = K tile 32, LDS ring of 3 stages, 32x32x16 products (also the route of an
+ *              int4 W); 7 = K tile 64, 2 LDS stages, 16x16x32 products (what the heuristic picks for
+ *              dense operands); 8 = the
  *              streaming kernel for rank-r products (N <= 128, no second segment, no addend:
  *              4 wavefronts per 32 output rows split the contraction)
  *   trans_out  1 = store C transposed, as [N,M] with ldc >= M (streaming kernel only); else 0

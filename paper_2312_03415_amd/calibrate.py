@@ -22,10 +22,11 @@ from . import binding as rl
 HERE = os.path.dirname(os.path.abspath(__file__))
 TILE_BM = [256, 128, 128, 128, 32, 64, 256, 256]
 TILE_BN = [256, 128, 32, 64, 128, 128, 256, 256]
-TILE_BK16 = [64, 64, 64, 64, 64, 64, 32, 32]
+TILE_BK16 = [64, 64, 64, 64, 64, 64, 32, 64]
 WG_PER_CU = [1, 2, 3, 2, 3, 3, 1, 1]
-NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x256x32 matrix-core (id 6)", "256x256x32 matrix-core (id 7)"]
+NAMES = ["256x256", "128x128", "128x32", "128x64", "32x128", "64x128", "256x256x32 matrix-core (id 6)", "256x256x64 matrix-core (id 7)"]
 LAYOUTS = {"NN": (0, 0), "NT": (0, 1), "TN": (1, 0)}
+LAYOUT_ID = {"NN": 0, "NT": 1, "TN": 2}
 
 
 def timeit(fn, iters=8, warm=2):
@@ -137,12 +138,18 @@ def main():
         fixes.append(max(ts - bytes_s / rate / 1e6, 0.0))
     print("stream_tbps", [round(v, 2) for v in rates], "fix", [round(v, 2) for v in fixes], flush=True)
 
-    # second stage of a split contraction: a half-filling 256x256 grid split in two vs its one-round model
-    t2 = gemm_time(bf, "NT", 4096, 2048, 8192, 7, splits=2)
-    model_round = 64 * tiles[0][7]["tk"][1] + tiles[0][7]["fix"]
-    extra = max(t2 - model_round, 2.0)
-    reduce_tbps = 4096.0 * 2048 * (4 * 3 + 2) / extra / 1e6
-    print("reduce_tbps", round(reduce_tbps, 2), flush=True)
+    # second stage of a split contraction (partials written, read back and summed by the reduce kernel): what two split
+    # launches take beyond their one-round model, a large output split in two on the matrix-core kernel and a small
+    # one split sixteen ways on the 128x128 tile, gives a rate over the partials' bytes and a fixed cost
+    def split_extra(layout, M, N, K, cfg, splits):
+        t = gemm_time(bf, layout, M, N, K, cfg, splits=splits)
+        kt = K // TILE_BK16[cfg] // splits
+        return max(t - (kt * tiles[0][cfg]["tk"][LAYOUT_ID[layout]] + tiles[0][cfg]["fix"]), 1.0)
+    x_big, b_big = split_extra("NT", 4096, 2048, 8192, 7, 2), 4096.0 * 2048 * (4 * 3 + 2)
+    x_small, b_small = split_extra("NN", 128, 4096, 4096, 1, 16), 128.0 * 4096 * (4 * 17 + 2)
+    reduce_tbps = (b_big - b_small) / max(x_big - x_small, 1.0) / 1e6
+    reduce_fix = max(x_small - b_small / reduce_tbps / 1e6 - launch, 0.0)
+    print("reduce_tbps", round(reduce_tbps, 2), "fix", round(reduce_fix, 2), "(extras", round(x_big, 1), round(x_small, 1), ")", flush=True)
 
     def row(t):
         return "{{%.3f, %.3f, %.3f}, %.2f, %.2f, %d}" % (t["tk"][0], t["tk"][1], t["tk"][2], t["fix"], t["fix_d"], t["wg"])
@@ -167,12 +174,13 @@ def main():
       %.2f,
       %.2f,
       %.2f,
+      %.2f,
   };
   return c;
 }
 
 }  // namespace rl
-""" % (body, rates[0], rates[1], sum(fixes) / 2.0, reduce_tbps, launch, merge_tbps, merge_fix)
+""" % (body, rates[0], rates[1], sum(fixes) / 2.0, reduce_tbps, reduce_fix, launch, merge_tbps, merge_fix)
     with open(args.out, "w") as fh:
         fh.write(out)
     print("wrote", args.out)

@@ -24,6 +24,7 @@ struct GemmDesc {
   int64_t ldc = 0;
   const void* D = nullptr;  // optional addend, same dtype as C (may alias C)
   int64_t ldd = 0;
+  bool has_addend = false;  // an addend is part of the product (also set when only shapes are modelled and D is null)
   // B[0] is symmetric int4 (packed nibbles, ldb[0] in elements) with fp16 group scales
   // [rows/64, ldbs]; nullptr = dense.  16-bit types, A stored [M,K].
   const void* Bscale = nullptr;
@@ -39,8 +40,10 @@ struct GemmDesc {
 
 enum TileCfg {
   CFG_BIG = 0, CFG_MID, CFG_TALL32, CFG_TALL64, CFG_WIDE32, CFG_WIDE64,
-  CFG_MC3,  // matrix-core kernel (gemm_mc.hpp, 16-bit types): 256x256x32, 4 waves, 3-stage LDS ring
-  CFG_MC4,  // the same kernel (once its 4-stage ring, which measured the same; the id the heuristics pick for dense B)
+  CFG_MC3,  // matrix-core kernel (gemm_mc.hpp, 16-bit types): 256x256x32, 4 waves, 3-stage LDS ring, 32x32x16 products
+            // (the int4 route of the frozen weight runs here)
+  CFG_MC4,  // matrix-core kernel (gemm_mc64.hpp, 16-bit types): 256x256x64, 4 waves, 2 LDS stages, 16x16x32 products
+            // (the id the heuristics pick for dense B)
   CFG_COUNT
 };
 

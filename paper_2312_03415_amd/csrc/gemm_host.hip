@@ -10,7 +10,7 @@ thread_local KernelEvents g_kernel_events;
 
 static const int kTileBM[CFG_COUNT] = {256, 128, 128, 128, 32, 64, 256, 256};
 static const int kTileBN[CFG_COUNT] = {256, 128, 32, 64, 128, 128, 256, 256};
-static const int kTileBK16[CFG_COUNT] = {64, 64, 64, 64, 64, 64, 32, 32};  // K tile, 16-bit types
+static const int kTileBK16[CFG_COUNT] = {64, 64, 64, 64, 64, 64, 32, 64};  // K tile, 16-bit types
 
 GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg,
                    int force_splits, bool b_int4) {
@@ -54,7 +54,7 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   if (force_splits > 0) {
     splits = force_splits;
   } else if (cfg == CFG_MC3 || cfg == CFG_MC4 || cfg == CFG_BIG) {
-    if (tiles < 160 && ktiles >= 32) splits = (int)((256 + tiles - 1) / tiles);
+    if (tiles < 160 && (int64_t)ktiles * p.bk >= 1024) splits = (int)((256 + tiles - 1) / tiles);
   } else if (tiles < 256 && ktiles >= 8) {
     // fill the chip (aim at ~512 workgroups) but keep >= 4 K tiles per slice
     int64_t want = (512 + tiles - 1) / tiles;
@@ -74,7 +74,7 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   // exact number of rounds and the cut-off part is small enough to be split along K, run that part
   // as a launch of its own (half a round with the contraction in two, plus its reduce).
   if (force_cfg < 0 && force_splits <= 0 && (p.cfg == CFG_MC4 || (b_int4 && p.cfg == CFG_MC3)) && p.splits == 1 &&
-      tiles > 256 && ktiles >= 64) {
+      tiles > 256 && (int64_t)ktiles * p.bk >= 2048) {
     for (int t = p.nbn - 1; t >= 1 && t >= p.nbn - 16; --t) {
       const int64_t main_tiles = (int64_t)p.nbm * t, tail_tiles = (int64_t)p.nbm * (p.nbn - t);
       if (tail_tiles > 128) break;
@@ -146,7 +146,7 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
     // extent is the operand's bytes plus 3 KB (gemm_mc.hpp, kBias): the 16-bit elements of an operand, rows x ld,
     // must stay below 2^31 - 2048 so that neither wraps; it also clamps a strided operand's last columns to
     // [dim-8, dim) and wants every K slice to hold at least one K tile
-    bool ok = d.dtype != DT_F32 && plan.bk == 32;
+    bool ok = d.dtype != DT_F32 && plan.bk == (cfg == CFG_MC4 ? 64 : 32);
     constexpr int64_t kMaxElems = (1LL << 31) - 2048;
     for (int s = 0; s < d.nseg; ++s) {
       const int64_t a_rows = d.a_strided ? d.K[s] : d.M, b_rows = d.b_kcontig ? d.N : d.K[s];

@@ -69,7 +69,7 @@ struct Builder {
     if (K2 > 0) { d.A[1] = A2->ptr; d.lda[1] = A2->ld; d.B[1] = B2->ptr; d.ldb[1] = B2->ld; d.K[1] = K2; }
     d.C = const_cast<void*>(C.ptr);
     d.ldc = C.ld;
-    if (D) { d.D = D->ptr; d.ldd = D->ld; }
+    if (D) { d.D = D->ptr; d.ldd = D->ld; d.has_addend = true; }
     if (b_is_w && L.w_int4) {
       d.b_int4 = true;
       d.Bscale = B.scales;

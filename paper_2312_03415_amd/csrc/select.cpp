@@ -67,13 +67,14 @@ static double gemm_time_us(const GemmDesc& d, const GemmPlan& p) {
   double ktiles = (double)(kt0 + kt1);
   if (p.splits > 1) ktiles = (double)p.tiles_per_split;
   // (partial and second-segment K tiles run at the speed of any other)
-  const bool addend = d.D != nullptr && p.splits == 1;
+  const bool has_d = d.has_addend || d.D != nullptr;
+  const bool addend = has_d && p.splits == 1;
   // int4 B on the matrix-core kernel: the dequantisation behind the MFMAs costs ~20 % per K tile
   // (measured on the 5120 x 13824 layer)
   const double q = (d.b_int4 && p.cfg == CFG_MC3) ? 1.2 : 1.0;
   double us = rounds * (ktiles * tm.tk_us[lay] * share * q + (addend ? tm.tfix_d_us : tm.tfix_us));
   if (p.splits > 1)
-    us += (double)d.M * d.N * (4.0 * (p.splits + 1) + (d.D ? e : 0.0) + e) / (mc.reduce_tbps * 1e12) * 1e6 + mc.launch_us;
+    us += (double)d.M * d.N * (4.0 * (p.splits + 1) + (has_d ? e : 0.0) + e) / (mc.reduce_tbps * 1e12) * 1e6 + mc.reduce_fix_us + mc.launch_us;
   return us;
 }
 

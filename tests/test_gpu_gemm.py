@@ -119,12 +119,13 @@ def test_matrix_core_builds_exact_on_small_integers(layout, dtype):
         want = oracle.matmul(Ah, Bh, ta=a_str, tb=b_kc) + oracle.matmul(A2h, B2h, ta=a_str, tb=b_kc)
         assert np.abs(want).max() <= 256   # exact in bf16's 8-bit significand
         zero_bias = torch.zeros(N, dtype=td, device="cuda")
-        for splits, bias in ((1, None), (2, None), (1, zero_bias), (3, zero_bias)):
-            print(f"case mc-exact layout={layout} dtype={dtype} M={M} N={N} splits={splits} bias={bias is not None}", flush=True)
-            C = torch.full((M, N), float("nan"), dtype=td, device="cuda")
-            rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, A2=A2, B2=B2, tile_cfg=6, splits=splits, bias=bias)
-            torch.cuda.synchronize()
-            assert np.array_equal(to_f64(C), want), (M, N, splits, bias is not None)
+        for cfg in (6, 7):   # K tile 32 / K tile 64 where that kernel has the build (else it runs as 6)
+            for splits, bias in ((1, None), (2, None), (1, zero_bias), (3, zero_bias)):
+                print(f"case mc-exact layout={layout} dtype={dtype} M={M} N={N} cfg={cfg} splits={splits} bias={bias is not None}", flush=True)
+                C = torch.full((M, N), float("nan"), dtype=td, device="cuda")
+                rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, A2=A2, B2=B2, tile_cfg=cfg, splits=splits, bias=bias)
+                torch.cuda.synchronize()
+                assert np.array_equal(to_f64(C), want), (M, N, cfg, splits, bias is not None)
 
 
 def test_gemm_strided_rows_and_aliased_addend():
