@@ -22,8 +22,8 @@
 //    own loads of the next tile (all of them: nothing younger is in flight), then the workgroup barrier (the next
 //    tile has landed for everyone; everyone has read the last fragments of this tile, which were fetched during K
 //    step 0); behind the following MFMAs come the next tile's first fragments and the 16 loads that refill this
-//    tile's stage with the tile after the next, one load behind every third MFMA.  A load thus has a whole K tile
-//    (128 MFMAs) to land.
+//    tile's stage with the tile after the next, one load behind every fourth MFMA.  A load thus has about a K tile
+//    (64 to 128 MFMAs) to land; cycle counters read in the kernel show no time lost in that wait or at the barrier.
 //  - The load stream is continuous over everything a persistent workgroup does (one workgroup per compute unit
 //    walks output tiles): the next output tile's first K tiles arrive while the current one is being stored.
 //  - A partial K tile (K % 64 != 0, e.g. the rank-r segment) takes the same route: its out-of-range 16-byte chunks
@@ -302,7 +302,8 @@ __device__ __forceinline__ void gemm_mc64_body(const GemmArgs& g) {
   // step's fragment i is read into the same registers right there: A fragments 0..6 are single-buffered.  Fragment 7,
   // which would be fetched behind the very last MFMA, and the B fragments, all live until the last MFMA, are
   // double-buffered; every read of a K step is then issued at least 8 MFMAs before the step ends.
-  i32x4 fa[7], fa7[2], fb[2][8];
+  i32x4 fa[2][8], fb[2][8];  // (of fa[1] only fragment 7 is used)
+#define FA(buf, i) fa[(i) == 7 ? (buf) : 0][i]
   // One 16-wide operand fragment of K step KSR from the stage at byte offset `soff` (all reads through inline
   // assembly: the compiler makes every LDS read it tracks wait for all outstanding LDS-DMA loads, which would
   // serialise the ring; reads it cannot see are waited for by hand, below).
@@ -325,7 +326,7 @@ __device__ __forceinline__ void gemm_mc64_body(const GemmArgs& g) {
   // everything the hand-issued LDS reads fetched for the K step that multiplies out of buffer `buf` has arrived
   auto wait_frags = [&](int buf) {
     asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fa[4]), "+v"(fa[5]), "+v"(fa[6]), "+v"(fa7[buf]),
+                 : "+v"(FA(buf, 0)), "+v"(FA(buf, 1)), "+v"(FA(buf, 2)), "+v"(FA(buf, 3)), "+v"(FA(buf, 4)), "+v"(FA(buf, 5)), "+v"(FA(buf, 6)), "+v"(FA(buf, 7)),
                    "+v"(fb[buf][0]), "+v"(fb[buf][1]), "+v"(fb[buf][2]), "+v"(fb[buf][3]), "+v"(fb[buf][4]), "+v"(fb[buf][5]),
                    "+v"(fb[buf][6]), "+v"(fb[buf][7]));
   };
@@ -333,8 +334,7 @@ __device__ __forceinline__ void gemm_mc64_body(const GemmArgs& g) {
   auto mask_frags = [&](int buf, int ks, int kvalid) {
     if (ks * 32 + 8 * grp >= kvalid) {
 #pragma unroll
-      for (int a = 0; a < 7; ++a) fa[a] = i32x4{0, 0, 0, 0};
-      fa7[buf] = i32x4{0, 0, 0, 0};
+      for (int a = 0; a < 8; ++a) FA(buf, a) = i32x4{0, 0, 0, 0};
 #pragma unroll
       for (int b = 0; b < 8; ++b) fb[buf][b] = i32x4{0, 0, 0, 0};
     }
@@ -357,8 +357,7 @@ __device__ __forceinline__ void gemm_mc64_body(const GemmArgs& g) {
     MC_FENCE();
     static_for<64>([&](auto qc) {
       constexpr int q = decltype(qc)::value;
-      if constexpr (q < 56) Elem16<T>::mma(acc[q >> 3][q & 7], fb[bufc][q & 7], fa[q >> 3]);
-      else Elem16<T>::mma(acc[7][q & 7], fb[bufc][q & 7], fa7[bufc]);
+      Elem16<T>::mma(acc[q >> 3][q & 7], fb[bufc][q & 7], FA(bufc, q >> 3));
       MC_FENCE();
       if constexpr (SYNC && q == 0) {
         asm volatile("" ::: "memory");
@@ -368,7 +367,7 @@ __device__ __forceinline__ void gemm_mc64_body(const GemmArgs& g) {
         MC_FENCE();
       }
       if constexpr ((q & 7) == 7 && q < 56) {
-        fa[q >> 3] = read_frag_op(P::A_STR, fragA, soff, std::integral_constant<int, (q >> 3)>{}, ksr_c);
+        fa[0][q >> 3] = read_frag_op(P::A_STR, fragA, soff, std::integral_constant<int, (q >> 3)>{}, ksr_c);
         MC_FENCE();
       }
       if constexpr (q >= 8 && q < 16) {
@@ -376,7 +375,7 @@ __device__ __forceinline__ void gemm_mc64_body(const GemmArgs& g) {
         MC_FENCE();
       }
       if constexpr (q == 16) {
-        fa7[bufr] = read_frag_op(P::A_STR, fragA, soff, std::integral_constant<int, 7>{}, ksr_c);
+        fa[bufr][7] = read_frag_op(P::A_STR, fragA, soff, std::integral_constant<int, 7>{}, ksr_c);
         MC_FENCE();
       }
       behind(qc);
@@ -398,8 +397,7 @@ __device__ __forceinline__ void gemm_mc64_body(const GemmArgs& g) {
   {
     using K0c = std::integral_constant<int, 0>;
     static_for<8>([&](auto b) { fb[0][decltype(b)::value] = read_frag_op(P::B_STR, fragB, 0u, b, K0c{}); });
-    static_for<7>([&](auto a) { fa[decltype(a)::value] = read_frag_op(P::A_STR, fragA, 0u, a, K0c{}); });
-    fa7[0] = read_frag_op(P::A_STR, fragA, 0u, std::integral_constant<int, 7>{}, K0c{});
+    static_for<8>([&](auto a) { fa[0][decltype(a)::value] = read_frag_op(P::A_STR, fragA, 0u, a, K0c{}); });
   }
   // the only K tiles that can be partial: the last one of each segment
   const int pu0 = (K0 % BK) != 0 ? nt0 - 1 : -1, pu1 = (K1 % BK) != 0 ? ntk - 1 : -1;
@@ -430,12 +428,13 @@ __device__ __forceinline__ void gemm_mc64_body(const GemmArgs& g) {
       kstep(std::integral_constant<int, 1>{}, std::false_type{}, 0, 1, soff, nothing);
       mask(1, 1);
       // K step 1: the next tile has landed and this tile's stage is free behind the barrier; the next tile's first
-      // fragments, then the refill of this stage with the cursor's tile, one load behind every third MFMA from the
-      // 17th on; the cursor moves on behind the last load
+      // fragments, and the refill of this stage with the cursor's tile, one load behind every fourth MFMA of the whole K
+      // step (the compute unit's address path takes about as long for the four waves' 64 loads as the waves take for a
+      // K step: bunched more closely, the loads hold up the MFMAs behind them); the cursor moves on behind the last load
       kstep(std::integral_constant<int, 0>{}, std::true_type{}, 1, 0, soffn, [&](auto qc) {
         constexpr int q = decltype(qc)::value;
-        if constexpr (q >= 17 && q < 17 + 3 * P::LPT && (q - 17) % 3 == 0) {
-          issue_load(st, std::integral_constant<int, (q - 17) / 3>{});
+        if constexpr (q >= 2 && (q - 2) % 4 == 0) {
+          issue_load(st, std::integral_constant<int, (q - 2) / 4>{});
           MC_FENCE();
         }
         if constexpr (q == 63) { cursor_advance(); MC_FENCE(); }
@@ -581,6 +580,7 @@ __device__ __forceinline__ void gemm_mc64_body(const GemmArgs& g) {
   // the LDS-DMA writes still in flight target this workgroup's LDS: let them land before it is released
   __builtin_amdgcn_s_waitcnt(mc_wait_imm(0, true));
 #undef MC_FENCE
+#undef FA
 }
 
 template <typename T, int AL, int BL, int PLAIN>

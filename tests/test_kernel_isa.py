@@ -65,3 +65,39 @@ def test_k_loop_of_the_matrix_core_kernel(asm, al, bl, ns, bq, plain):
     for b in blocks(text):
         if b and b[-1].startswith("s_cbranch_execnz"):
             assert not any(i.startswith(("buffer_load", "global_load")) for i in b), "a load sits in a per-lane (waterfall) loop"
+
+
+@pytest.mark.parametrize("al,bl,plain", [(0, 0, 1), (0, 1, 1), (1, 0, 1), (0, 0, 0), (0, 1, 0), (0, 1, 2), (0, 0, 2)])
+def test_k_loop_of_the_matrix_core_kernel_with_k_tile_64(asm, al, bl, plain):
+    """gemm_mc64_kernel: a K tile is two straight-line K steps of 64 MFMAs (16x16x32) with tied accumulators and nothing
+    between them but the fragment reads, the 16 refill loads and, in the second, one wait + barrier; no spills, no
+    accumulator traffic between the two register files, no load in a per-lane loop."""
+    name = f"_ZN2rl16gemm_mc64_kernelIDF16bLi{al}ELi{bl}ELi{plain}EEEvNS_8GemmArgsE"
+    start = asm.index("\n" + name + ":")
+    text = asm[start:asm.index("s_endpgm", start)]
+    meta = asm[asm.index(".name:           " + name):]
+    meta = meta[:meta.index(".wavefront_size")]
+    assert re.search(r"\.vgpr_spill_count:\s+0\b", meta), "the kernel spills vector registers"
+    ksteps = [b for b in blocks(text) if sum(i.startswith("v_mfma_f32_16x16x32") for i in b) >= 64]
+    assert len(ksteps) == 2, "expected the two K steps of a tile as two straight-line blocks of 64 MFMAs"
+    syncs = 0
+    for b in ksteps:
+        first = next(k for k, i in enumerate(b) if i.startswith("v_mfma"))
+        last = max(k for k, i in enumerate(b) if i.startswith("v_mfma"))
+        body = b[first:last + 1]
+        assert sum(i.startswith("v_mfma") for i in body) == 64
+        assert not any(i.startswith(("scratch_", "v_accvgpr")) for i in body), "spill or accumulator copies inside a K step"
+        for i in body:
+            m = re.match(r"v_mfma_f32_16x16x32_\w+\s+(a\[\d+:\d+\]), \S+, \S+, (a\[\d+:\d+\])", i)
+            if i.startswith("v_mfma"):
+                assert m and m.group(1) == m.group(2), "accumulator not tied: " + i
+        waits = [i for i in body if re.match(r"s_waitcnt\s+vmcnt\(0\)", i)]
+        assert len(waits) <= 1
+        syncs += len(waits)
+        n_loads = sum(i.startswith("buffer_load") for i in body)
+        assert n_loads in (0, 16)
+        assert len(body) <= 64 + 90, "too many instructions between the MFMAs of a K step"
+    assert syncs == 1, "exactly one of the two K steps waits for the loads"
+    for b in blocks(text):
+        if b and b[-1].startswith("s_cbranch_execnz"):
+            assert not any(i.startswith(("buffer_load", "global_load")) for i in b), "a load sits in a per-lane (waterfall) loop"
