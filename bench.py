@@ -277,7 +277,7 @@ def main():
         # a step's time there is the sum over all kernels it launched (main launch, tail launch, reduce pass).  The
         # same kernels also serve memory-bound products (W + AB has K = r): those are groups of their own.
         if r["tile_cfg"] in MC and dense:
-            key = ("gemm_mc_kernel", "")
+            key = ("gemm_mc64_kernel" if r["tile_cfg"] == MC[1] else "gemm_mc_kernel", "")
         else:
             key = (lay, TILE_NAMES[r["tile_cfg"]] + ("" if dense else "/mem"))
         g = groups.setdefault(key, dict(us=0.0, flops=0.0, bytes=0.0, launches=0, kernels=0, what=set(), by_build={}))
@@ -300,10 +300,10 @@ def main():
         roofline = dict(bound="hbm", achieved=round(ach, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
                         frac=round(ach / HBM_PEAK_GBPS, 4))
     if roofline["bound"] == "mfma":
-        # what a bare MFMA loop sustains on this (power-limited) GPU: on zeros, and on random operands
+        # what back-to-back MFMAs sustain on this (power-limited) GPU: on zeros, and on N(0,1)-like operands
         roofline["mfma_probe_tflops"] = {"zeros": round(rl.runlora_probe_mfma(False), 1),
-                                         "random": round(rl.runlora_probe_mfma(True), 1)}
-        roofline["frac_of_random_data_probe"] = round(ach / roofline["mfma_probe_tflops"]["random"], 4)
+                                         "gaussian": round(rl.runlora_probe_mfma(True), 1)}
+        roofline["frac_of_gaussian_data_probe"] = round(ach / roofline["mfma_probe_tflops"]["gaussian"], 4)
     roofline.update(traffic=traffic_from_profile(args.workload, kname), kernel=kname,
                     products=sorted(dom["what"]), launches_per_step=dom["launches"] / args.steps,
                     kernels_per_step=dom["kernels"] / args.steps,

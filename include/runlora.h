@@ -82,7 +82,11 @@ typedef enum {
   RL_FWD_DEFAULT = 0, /* T = XA kept for the backward; Y = XW; Y += T B.  One kernel per product. */
   RL_FWD1 = 1,        /* Y = (XW) + ((XA)B): T = XA, then one GEMM over the concatenated          */
                       /* contraction [X|T] [W;B]; T is scratch, not kept.                         */
-  RL_FWD2 = 2         /* Y = X (W + AB): M = W + AB, then Y = X M  (Eq. 2).                       */
+  RL_FWD2 = 2,        /* Y = X (W + AB): M = W + AB, then Y = X M  (Eq. 2).                       */
+  RL_FWD3 = 3         /* RL_FWD1's graph in ONE kernel: every workgroup of the GEMM forms its rows */
+                      /* of T = XA next to X W (X is read once, T never reaches memory), rounds    */
+                      /* them and contracts them with B as a last K tile.  r <= 32, dense W, no    */
+                      /* dropout; otherwise the call runs as RL_FWD1.  No workspace when it applies.*/
 } rl_fwd_variant_t;
 
 /*
@@ -407,8 +411,9 @@ int runlora_profile_collect(rl_step_time_t* out, int cap);
 int runlora_profile_disable(void);
 
 /*
- * Measure what the matrix cores sustain on this GPU with nothing else running: a loop of
- * independent bf16 MFMAs on zeros (random_data = 0) or on random operands (random_data = 1).
+ * Measure what the matrix cores sustain on this GPU with nothing else running: back-to-back bf16
+ * MFMAs (16x16x32, the matrix-core GEMM's product; one wave per SIMD, operands held in registers)
+ * on zeros (random_data = 0) or on operands drawn roughly from N(0, 1) (random_data = 1).
  * The chip is power-limited, so the two differ; the second is the ceiling for N(0,1)-like data.
  * scratch: device buffer of at least 512 KiB (overwritten).  Synchronises the stream.  Result in
  * TFLOP/s through *tflops (host).  For measurement reports only.

@@ -18,9 +18,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librunlora.so")
 
 RL_F32, RL_F16, RL_BF16, RL_INT4_G64 = 0, 1, 2, 3
-FWD_DEFAULT, FWD1, FWD2 = 0, 1, 2
+FWD_DEFAULT, FWD1, FWD2, FWD3 = 0, 1, 2, 3
 BWD_DEFAULT, BWD1, BWD2, BWD3, BWD4, BWD5, BWD6, BWD7, BWD8 = 0, 1, 2, 3, 4, 5, 6, 7, 8
-FWD_VARIANTS = (FWD_DEFAULT, FWD1, FWD2)
+FWD_VARIANTS = (FWD_DEFAULT, FWD1, FWD2, FWD3)
 BWD_VARIANTS = (BWD_DEFAULT, BWD1, BWD2, BWD3, BWD4, BWD5, BWD6, BWD7, BWD8)
 BWD_MERGED = (BWD4, BWD5, BWD7, BWD8)  # the graphs that read W + AB as a matrix
 

@@ -260,7 +260,7 @@ namespace {
 int forward_impl(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const rl_tensor_t* A, const rl_tensor_t* B,
                  rl_tensor_t* Y, rl_saved_t* saved, const rl_opts_t* opts, bool use_static) {
   if (!X || !W || !A || !B || !Y || !saved) return RL_ERR_NULL;
-  if (variant < RL_FWD_DEFAULT || variant > RL_FWD2) return RL_ERR_VARIANT;
+  if (variant < RL_FWD_DEFAULT || variant > RL_FWD3) return RL_ERR_VARIANT;
   const int dtype = X->dtype;
   const int dt = internal_dtype(dtype);
   if (dt < 0) return RL_ERR_DTYPE;
@@ -395,7 +395,7 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   if (dA && (rc = check_tensor(dA, i, r, dtype)) != RL_OK) return rc;
   if (dB && (rc = check_tensor(dB, r, o, dtype)) != RL_OK) return rc;
   // the forward's record must describe this very layer
-  if (saved->fwd_variant < RL_FWD_DEFAULT || saved->fwd_variant > RL_FWD2) return RL_ERR_SAVED_MISMATCH;
+  if (saved->fwd_variant < RL_FWD_DEFAULT || saved->fwd_variant > RL_FWD3) return RL_ERR_SAVED_MISMATCH;
   if (saved->dtype != dtype || saved->n != n || saved->i != i || saved->o != o || saved->r != r)
     return RL_ERR_SAVED_MISMATCH;
   if (!saved->X) return RL_ERR_NULL;
@@ -563,7 +563,7 @@ extern "C" int runlora_vera_backward(int variant, const rl_tensor_t* dY, const r
 extern "C" size_t runlora_vera_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype) {
   const int dt = internal_dtype(dtype);
   if (dt < 0 || n < 1 || i < 1 || o < 1 || r < 1) return 0;
-  if (fwd > RL_FWD2 || bwd > RL_BWD8 || (fwd < 0 && bwd < 0)) return 0;
+  if (fwd > RL_FWD3 || bwd > RL_BWD8 || (fwd < 0 && bwd < 0)) return 0;
   return 2 * align256((size_t)r * (size_t)o * dtype_size(dt)) + runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype);
 }
 
@@ -624,7 +624,7 @@ extern "C" int runlora_dora_forward(int variant, const rl_tensor_t* X, const rl_
                                     const rl_tensor_t* B, const void* m, rl_tensor_t* Y, rl_saved_t* saved, float* c,
                                     const rl_opts_t* opts) {
   if (!X || !W || !A || !B || !Y || !saved || !c) return RL_ERR_NULL;
-  if (variant != RL_FWD2) return variant < RL_FWD_DEFAULT || variant > RL_FWD2 ? RL_ERR_VARIANT : RL_ERR_UNSUPPORTED;
+  if (variant != RL_FWD2) return variant < RL_FWD_DEFAULT || variant > RL_FWD3 ? RL_ERR_VARIANT : RL_ERR_UNSUPPORTED;
   DoraLayout v;
   int rc = dora_layout(W, A, B, m, X->rows, opts, &v);
   if (rc != RL_OK) return rc;
@@ -739,7 +739,7 @@ extern "C" int runlora_dora_backward(int variant, const rl_tensor_t* dY, const r
 extern "C" size_t runlora_dora_workspace_bytes(int fwd, int bwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype) {
   const int dt = internal_dtype(dtype);
   if (dt < 0 || dt == DT_F32 || n < 1 || i < 1 || o < 1 || r < 1 || r > 128) return 0;
-  if (fwd > RL_FWD2 || bwd > RL_BWD8 || (fwd < 0 && bwd < 0)) return 0;
+  if (fwd > RL_FWD3 || bwd > RL_BWD8 || (fwd < 0 && bwd < 0)) return 0;
   return dora_head_bytes(n, i, o, r, dt, nullptr, nullptr) + runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype);
 }
 
@@ -750,6 +750,7 @@ extern "C" size_t runlora_saved_bytes(int fwd, int64_t n, int64_t i, int64_t o, 
   switch (fwd) {
     case RL_FWD_DEFAULT: return (size_t)n * (size_t)r * e;  // T = XA
     case RL_FWD1: return 0;
+    case RL_FWD3: return 0;
     case RL_FWD2: return keep_merged ? (size_t)i * (size_t)o * e : 0;
     default: return 0;
   }

@@ -36,7 +36,15 @@ struct GemmDesc {
   // LoRA dropout (drop_thr != 0): zero output element (m, n) of alpha * (the products) where the mask
   // drops element (m, n) of X; key and threshold as in gemm_engine.hpp, drop_cpr = columns of X / 4
   uint32_t drop_thr = 0, drop_key = 0, drop_cpr = 0;
+  // One-pass LoRA forward, C = A[0] B[0] + round(t_alpha A[0] LA) B[1] in one kernel: nseg = 2, A[1] unused,
+  // K[1] = R <= kFuseMaxR, LA stored [K[0], R] row-major; A [M,K], B [K,N], dense B, no addend, no K split
+  // (plan with gemm_plan_fused).  fuse_t is also set when only shapes are modelled and LA is null.
+  const void* LA = nullptr;
+  int64_t ldla = 0;
+  float t_alpha = 1.f;
+  bool fuse_t = false;
 };
+constexpr int64_t kFuseMaxR = 32;
 
 enum TileCfg {
   CFG_BIG = 0, CFG_MID, CFG_TALL32, CFG_TALL64, CFG_WIDE32, CFG_WIDE64,
@@ -65,6 +73,9 @@ struct GemmPlan {
 // override the heuristics (used by the tuning sweeps and tests).
 GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg = -1,
                    int force_splits = 0, bool b_int4 = false);
+
+// Plan for the one-pass LoRA forward (GemmDesc::fuse_t): a tile shape of the generic engine, the contraction whole.
+GemmPlan gemm_plan_fused(int dtype, int64_t M, int64_t N, int64_t K0, int64_t R);
 
 // Plan of the launch that computes the columns [main.tail_n0, N) cut off from `main`.
 GemmPlan gemm_tail_plan(const GemmPlan& main, int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1);

@@ -56,6 +56,14 @@ struct GemmArgs {
   // drop_thr != 0: output element (m, n) of alpha * (the products) is zeroed where the dropout mask
   // drops element (m, n) of X (the adapter's share of dX); drop_cpr = groups of four columns per row
   uint32_t drop_thr, drop_key, drop_cpr;
+  // One-pass LoRA forward (gemm_kernel's FUSE build, Y = X W + (s X A) B of Section 2's forward 1 in one kernel):
+  // LA = the adapter's A [K[0], R] row-major (R <= 32), t_alpha = s.  The kernel then forms T = t_alpha * A[0] LA
+  // for its own rows next to the main product, rounds it to T's type and contracts it with B[1] ([R, N]) as one more
+  // K tile; A[1] is not read.  nullptr = an ordinary launch.
+  const void* LA;
+  int64_t ldla;
+  int R;
+  float t_alpha;
 };
 
 // ---- per-type pieces --------------------------------------------------------------------------
@@ -297,16 +305,33 @@ struct GemmTile {
   static constexpr int A_CPR = A_COLS / VE, B_CPR = B_COLS / VE;  // 16-byte chunks per tile row
   static constexpr int A_CHUNKS = A_ROWS * A_CPR, B_CHUNKS = B_ROWS * B_CPR;
   static constexpr int A_PER = (A_CHUNKS + NT - 1) / NT, B_PER = (B_CHUNKS + NT - 1) / NT;
+  // FUSE build: a [BK][RP] slice of the adapter's A per stage, K-strided like W; the 32-row blocks of T = X A of
+  // a row of waves are dealt round-robin to its WN waves
+  static constexpr int RP = 32;
+  static constexpr int L_LD = LdsLd<T, true, RP>::value;
+  static constexpr int L_ELEMS = BK * L_LD;
+  static constexpr int L_CPR = RP / VE, L_CHUNKS = BK * L_CPR, L_PER = (L_CHUNKS + NT - 1) / NT;
+  static constexpr int TT = (TM + WN - 1) / WN;
+  static constexpr int FUSE_STAGE_ELEMS = STAGE_ELEMS + L_ELEMS;
+  static constexpr int FUSE_LDS_BYTES = 2 * FUSE_STAGE_ELEMS * (int)sizeof(T);
   static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % KS == 0, "tile shape");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
 // BQ: B of segment 0 is int4 with group scales (see GemmArgs); it is dequantised on its way from
 // the load registers to LDS, so the matrix cores see ordinary T operands.
-template <typename T, int AL, int BL, int BM, int BN, int BK, int WM, int WN, bool BQ = false>
+// FUSE: the one-pass LoRA forward (see GemmArgs::LA): X stored [M,K], W stored [K,N], no K split.  Next to the main
+// product every wave accumulates its share of T = X LA (one more 32-column block per 32 rows, fed from the X
+// fragments already in registers and a [BK][32] slice of LA staged like W); behind the last K tile of segment 0
+// the workgroup writes alpha-scaled, rounded T into the A half of the free LDS stage, where the K tile of segment 1
+// (B[1], rows >= R zero) finds it as its A operand.
+template <typename T, int AL, int BL, int BM, int BN, int BK, int WM, int WN, bool BQ = false, bool FUSE = false>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
   using G = GemmTile<T, AL, BL, BM, BN, BK, WM, WN>;
   constexpr int NT = G::NT, VE = G::VE;
+  constexpr int STAGE_ELEMS = FUSE ? G::FUSE_STAGE_ELEMS : G::STAGE_ELEMS;
+  static_assert(!FUSE || (AL == 0 && BL == 0 && !BQ && BK >= G::RP), "the one-pass forward: X [M,K], W [K,N], dense");
+  static_assert(!FUSE || G::FUSE_LDS_BYTES <= 160 * 1024, "LDS budget");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   T* smem = reinterpret_cast<T*>(smem_raw);
 
@@ -347,6 +372,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
   i32x4 ra[G::A_PER], rb[G::B_PER];
   uint32_t rq[BQ ? G::B_PER : 1];  // packed int4 words of the tile in flight (BQ, segment 0)
   bool quant_tile = false;         // the tile in flight is one of the int4 segment
+  [[maybe_unused]] i32x4 rl[FUSE ? G::L_PER : 1];    // slice of LA of the tile in flight
+  [[maybe_unused]] f32x16 tacc[FUSE ? G::TT : 1];    // T blocks of this wave: row blocks a with a % WN == wn
+  if constexpr (FUSE) {
+#pragma unroll
+    for (int a = 0; a < G::TT; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) tacc[a][v] = 0.f;
+  }
 
   auto load_global = [&](int t) {
     const int s = t < nt0 ? 0 : 1;
@@ -355,8 +388,22 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
     const T* Ap = static_cast<const T*>(g.A[s]);
     const T* Bp = static_cast<const T*>(g.B[s]);
     const int64_t lda = g.lda[s], ldb = g.ldb[s];
+    if constexpr (FUSE) {
+      if (s == 0) {
+#pragma unroll
+        for (int j = 0; j < G::L_PER; ++j) {
+          const int c = tid + j * NT;
+          const int row = c / G::L_CPR, col = (c % G::L_CPR) * VE;
+          i32x4 v = {0, 0, 0, 0};
+          if ((G::L_CHUNKS % NT == 0 || c < G::L_CHUNKS) && k0 + row < Ks && col < g.R)
+            v = *reinterpret_cast<const i32x4*>(static_cast<const T*>(g.LA) + (int64_t)(k0 + row) * g.ldla + col);
+          rl[j] = v;
+        }
+      }
+    }
 #pragma unroll
     for (int j = 0; j < G::A_PER; ++j) {
+      if (FUSE && s == 1) break;  // the A operand of segment 1 is T, formed in the kernel
       const int c = tid + j * NT;
       const int row = c / G::A_CPR, col = (c % G::A_CPR) * VE;
       i32x4 v = {0, 0, 0, 0};
@@ -396,14 +443,39 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
     }
   };
 
-  auto store_lds = [&](int stage) {
-    T* sA = smem + stage * G::STAGE_ELEMS;
+  // t_tile (FUSE): the tile being stored is the one of segment 1: its A half is T out of the accumulators
+  auto store_lds = [&](int stage, [[maybe_unused]] bool t_tile) {
+    T* sA = smem + stage * STAGE_ELEMS;
     T* sB = sA + G::A_ELEMS;
+    if (FUSE && t_tile) {
+      if constexpr (FUSE) {
+        // lane l of a 32x32 block holds row l % 32 and, for q = 0..3, columns 8 q + 4 (l / 32) + {0..3}
 #pragma unroll
-    for (int j = 0; j < G::A_PER; ++j) {
-      const int c = tid + j * NT;
-      if (G::A_CHUNKS % NT == 0 || c < G::A_CHUNKS)
-        *reinterpret_cast<i32x4*>(sA + (c / G::A_CPR) * G::A_LD + (c % G::A_CPR) * VE) = ra[j];
+        for (int a = 0; a < G::TM; ++a) {
+          if (a % WN != wn) continue;
+          T* row = sA + (wm * G::WTM + a * 32 + (lane & 31)) * G::A_LD + 4 * (lane >> 5);
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) row[8 * q + e] = from_f32<T>(g.t_alpha * tacc[a / WN][4 * q + e]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < G::A_PER; ++j) {
+        const int c = tid + j * NT;
+        if (G::A_CHUNKS % NT == 0 || c < G::A_CHUNKS)
+          *reinterpret_cast<i32x4*>(sA + (c / G::A_CPR) * G::A_LD + (c % G::A_CPR) * VE) = ra[j];
+      }
+      if constexpr (FUSE) {
+        T* sL = sB + G::B_ELEMS;
+#pragma unroll
+        for (int j = 0; j < G::L_PER; ++j) {
+          const int c = tid + j * NT;
+          if (G::L_CHUNKS % NT == 0 || c < G::L_CHUNKS)
+            *reinterpret_cast<i32x4*>(sL + (c / G::L_CPR) * G::L_LD + (c % G::L_CPR) * VE) = rl[j];
+        }
+      }
     }
 #pragma unroll
     for (int j = 0; j < G::B_PER; ++j) {
@@ -420,7 +492,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
 
   if (t_begin < t_end) {
     load_global(t_begin);
-    store_lds(0);
+    store_lds(0, false);  // (a FUSE launch has K[0] >= 1: its first tile is never the T tile)
   }
   __syncthreads();
 
@@ -428,10 +500,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
   for (int t = t_begin; t < t_end; ++t) {
     const bool more = (t + 1 < t_end);
     if (more) load_global(t + 1);
-    const T* sA = smem + stage * G::STAGE_ELEMS;
+    const T* sA = smem + stage * STAGE_ELEMS;
     const T* sB = sA + G::A_ELEMS;
+    [[maybe_unused]] const bool main_tile = t < nt0;
 #pragma unroll
     for (int ks = 0; ks < BK / G::KS; ++ks) {
+      if (FUSE && !main_tile && ks >= G::RP / G::KS) break;  // T is RP wide: the rest of the A half is not its
       i32x4 fa[G::TM], fb[G::TN];
 #pragma unroll
       for (int a = 0; a < G::TM; ++a)
@@ -443,8 +517,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(GemmArgs g) {
       for (int a = 0; a < G::TM; ++a)
 #pragma unroll
         for (int b = 0; b < G::TN; ++b) Elem<T>::mma(acc[a][b], fb[b], fa[a]);  // rows of the MFMA = n
+      if constexpr (FUSE) {
+        if (main_tile) {
+          const i32x4 fl = read_frag<T, true, G::L_LD>(sB + G::B_ELEMS, 0, ks, lane);
+#pragma unroll
+          for (int a = 0; a < G::TM; ++a)
+            if (a % WN == wn) Elem<T>::mma(tacc[a / WN], fl, fa[a]);
+        }
+      }
     }
-    if (more) store_lds(stage ^ 1);
+    if (more) store_lds(stage ^ 1, FUSE && t + 1 >= nt0);
     __syncthreads();
     stage ^= 1;
   }

@@ -103,6 +103,14 @@ GemmPlan gemm_plan_int4(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1)
   return gemm_plan(dtype, M, N, K0, K1, -1, 0, true);
 }
 
+GemmPlan gemm_plan_fused(int dtype, int64_t M, int64_t N, int64_t K0, int64_t R) {
+  // the shape rules of gemm_plan with the generic engine's 256x256 tile where the matrix-core kernel would run;
+  // the workgroup that owns an output tile needs the whole contraction of its rows of T: no split
+  int cfg = gemm_plan(dtype, M, N, K0, R).cfg;
+  if (cfg == CFG_MC3 || cfg == CFG_MC4) cfg = CFG_BIG;
+  return gemm_plan(dtype, M, N, K0, R, cfg, 1);
+}
+
 hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hipStream_t stream) {
   if (d.M <= 0 || d.N <= 0) return hipErrorInvalidValue;
   if (plan.tail_n0 > 0) {
@@ -138,6 +146,12 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
     return gemm_run(dt, pt, scratch, stream);
   }
   if (plan.splits > 1 && scratch == nullptr) return hipErrorInvalidValue;
+  if (d.fuse_t) {
+    const bool ok = d.LA != nullptr && d.nseg == 2 && d.K[1] >= 1 && d.K[1] <= kFuseMaxR && d.K[0] >= 1 && !d.a_strided &&
+                    !d.b_kcontig && plan.splits == 1 && d.D == nullptr && d.Bscale == nullptr && d.drop_thr == 0 &&
+                    plan.cfg != CFG_MC3 && plan.cfg != CFG_MC4;
+    if (!ok) return hipErrorInvalidValue;
+  }
   int cfg = plan.cfg;
   if (d.Bscale != nullptr && cfg != CFG_BIG && cfg != CFG_MID && cfg != CFG_MC3) return hipErrorInvalidValue;  // see gemm_plan_int4
   if (d.Bscale != nullptr && d.a_strided) return hipErrorInvalidValue;
@@ -182,6 +196,10 @@ hipError_t gemm_run(const GemmDesc& d, const GemmPlan& plan, float* scratch, hip
   a.drop_thr = d.drop_thr;
   a.drop_key = d.drop_key;
   a.drop_cpr = d.drop_cpr;
+  a.LA = d.fuse_t ? d.LA : nullptr;
+  a.ldla = d.ldla;
+  a.R = d.fuse_t ? (int)d.K[1] : 0;
+  a.t_alpha = d.t_alpha;
   dim3 grid((unsigned)(plan.nbm * plan.nbn), (unsigned)plan.splits, 1);
   const int al = d.a_strided ? 1 : 0, bl = d.b_kcontig ? 1 : 0;
   hipError_t e;

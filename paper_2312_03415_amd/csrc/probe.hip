@@ -1,6 +1,8 @@
-// Matrix-core ceiling probe: a loop of independent bf16 MFMAs with nothing else going on, fed with
-// zeros or with random operands.  MI355X runs under a power limit, so the sustained MFMA rate
-// depends on how many operand bits toggle; kernels that multiply N(0,1)-like data cannot reach what
+// Matrix-core ceiling probe: a loop of bf16 MFMAs (16x16x32, the product the matrix-core GEMM is built
+// from) with nothing else going on: one wave per SIMD, an 8 x 8 block of accumulators per wave, operands
+// held in registers, every MFMA written out so that no loop arithmetic sits between them.  Fed with zeros
+// or with operands drawn roughly from N(0, 1).  MI355X runs under a power limit, so the sustained MFMA
+// rate depends on how many operand bits toggle; kernels that multiply N(0,1)-like data cannot reach what
 // the same loop reaches on zeros.  bench.py reports both figures next to the datasheet peak.
 #include <hip/hip_runtime.h>
 
@@ -9,39 +11,35 @@
 
 namespace rl {
 
-__global__ __launch_bounds__(512) void mfma_probe_kernel(float* out, int iters, int random_data) {
-  constexpr int NA = 4, NB = 2;
-  i32x4 a[NA], b[NB];
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters, int random_data) {
+  i32x4 a[8], b[8];
   unsigned h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
-  auto next16 = [&]() -> unsigned {  // a bf16 with random sign, exponent in [2^-2, 2^1], random mantissa
-    h ^= h << 13; h ^= h >> 17; h ^= h << 5;
-    const unsigned sign = (h >> 3) & 0x8000u, expo = (125u + ((h >> 9) & 3u)) << 7, man = (h >> 20) & 0x7Fu;
-    return random_data ? (sign | expo | man) : 0u;
+  auto next16 = [&]() -> unsigned {  // a bf16 close to N(0, 1): twelve uniforms summed, minus six
+    float s = -6.f;
+    for (int k = 0; k < 12; ++k) {
+      h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+      s += (float)(h >> 8) * (1.0f / 16777216.0f);
+    }
+    return random_data ? (__builtin_bit_cast(unsigned, s) >> 16) : 0u;
   };
-  for (int i = 0; i < NA; ++i)
+  for (int i = 0; i < 8; ++i)
     for (int e = 0; e < 4; ++e) a[i][e] = (int)(next16() | (next16() << 16));
-  for (int i = 0; i < NB; ++i)
+  for (int i = 0; i < 8; ++i)
     for (int e = 0; e < 4; ++e) b[i][e] = (int)(next16() | (next16() << 16));
-  f32x16 acc[NA][NB];
-  for (int i = 0; i < NA; ++i)
-    for (int j = 0; j < NB; ++j)
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  f32x4 acc[8][8];
+  for (int i = 0; i < 8; ++i)
+    for (int j = 0; j < 8; ++j)
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < NA; ++i)
-#pragma unroll
-      for (int j = 0; j < NB; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]),
-                                                            __builtin_bit_cast(bf16x8, b[j]), acc[i][j], 0, 0, 0);
-    if (random_data) {  // keep the operands changing, as a K loop does
-#pragma unroll
-      for (int i = 0; i < NA; ++i) a[i][it & 3] ^= 0x00400040;
-    }
+    for (int q = 0; q < 64; ++q)  // one operand held for eight products, the other changing: the GEMM's order
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[q >> 3][q & 7]) : "v"(a[q >> 3]), "v"(b[q & 7]));
   }
+  asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");  // the last MFMAs finish before their results are read
   float s = 0.f;
-  for (int i = 0; i < NA; ++i)
-    for (int j = 0; j < NB; ++j)
-      for (int v = 0; v < 16; ++v) s += acc[i][j][v];
+  for (int i = 0; i < 8; ++i)
+    for (int j = 0; j < 8; ++j)
+      for (int v = 0; v < 4; ++v) s += acc[i][j][v];
   out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
@@ -50,7 +48,7 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(float* out, int iters, 
 extern "C" int runlora_probe_mfma(void* scratch, size_t scratch_bytes, int random_data, void* stream,
                                   double* tflops) {
   if (!scratch || !tflops) return RL_ERR_NULL;
-  const int blocks = 256, threads = 512, iters = 3000, reps = 5;
+  const int blocks = 256, threads = 256, iters = 4000, reps = 5;
   if (scratch_bytes < (size_t)blocks * threads * sizeof(float)) return RL_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipEvent_t e0, e1;
@@ -67,7 +65,7 @@ extern "C" int runlora_probe_mfma(void* scratch, size_t scratch_bytes, int rando
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   if (e != hipSuccess || ms <= 0.f) return RL_ERR_HIP;
-  const double flops = (double)blocks * (threads / 64) * iters * 8.0 * 2.0 * 32 * 32 * 16 * reps;
+  const double flops = (double)blocks * (threads / 64) * iters * 64.0 * 2.0 * 16 * 16 * 32 * reps;
   *tflops = flops / (ms * 1e-3) / 1e12;
   return RL_OK;
 }

@@ -82,6 +82,29 @@ struct Builder {
     out->steps.push_back(s);
   }
 
+  // Y = X W + (s X A) B (+ bias) in one launch of the tile GEMM's one-pass build: X is read once, T = s X A lives
+  // in the kernel only
+  void fused_forward(const char* what, Mat X, Mat W, Mat A, Mat B, Mat Y, const void* bias) {
+    Step s;
+    s.what = what;
+    GemmDesc& d = s.d;
+    d.dtype = L.dtype;
+    d.bias = bias;
+    d.M = L.n;
+    d.N = L.o;
+    d.nseg = 2;
+    d.A[0] = X.ptr; d.lda[0] = X.ld; d.B[0] = W.ptr; d.ldb[0] = W.ld; d.K[0] = L.i;
+    d.A[1] = nullptr; d.lda[1] = 0; d.B[1] = B.ptr; d.ldb[1] = B.ld; d.K[1] = L.r;
+    d.C = const_cast<void*>(Y.ptr);
+    d.ldc = Y.ld;
+    d.LA = A.ptr;
+    d.ldla = A.ld;
+    d.t_alpha = scale();
+    d.fuse_t = true;
+    s.plan = gemm_plan_fused(L.dtype, L.n, L.o, L.i, L.r);
+    out->steps.push_back(s);
+  }
+
   // M = W + A B: the bandwidth-bound merge kernel when it applies (16-bit, r <= 128), else the tile
   // GEMM with W as the addend
   void merge(const char* what, Mat A, Mat B, Mat W, Mat M) {
@@ -223,6 +246,12 @@ bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void*
       b.gemm("Y += T B", 0, 0, n, o, r, op.T, op.B, op.Y, &op.Y);
       break;
     }
+    case 3:  // forward1 in one pass over X; where that build does not apply, forward1's two launches
+      if (r <= kFuseMaxR && !L.w_int4 && !L.drop_thr) {
+        b.fused_forward("Y = X [W|A] ; Y += T B", op.X, op.W, op.A, op.B, op.Y, op.bias);
+        break;
+      }
+      [[fallthrough]];
     case 1: {  // forward1: (XW) + ((XA)B), the sum folded into one contraction over [X|T]
       Mat T = b.scratch(n, r);
       b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T, true, true});

@@ -16,7 +16,8 @@ int64_t table1_flops(int is_bwd, int v, int64_t n, int64_t i, int64_t o, int64_t
   if (!is_bwd) {
     switch (v) {
       case 0:
-      case 1: return 2 * n * (i * o + r * i + o * r);
+      case 1:
+      case 3: return 2 * n * (i * o + r * i + o * r);  // (3: forward1's graph; its kernel's repeated X A is not counted)
       case 2: return 2 * (i * o * r + n * o * i);
       default: return -1;
     }
@@ -71,7 +72,16 @@ static double gemm_time_us(const GemmDesc& d, const GemmPlan& p) {
   const bool addend = has_d && p.splits == 1;
   // int4 B on the matrix-core kernel: the dequantisation behind the MFMAs costs ~20 % per K tile
   // (measured on the 5120 x 13824 layer)
-  const double q = (d.b_int4 && p.cfg == CFG_MC3) ? 1.2 : 1.0;
+  double q = (d.b_int4 && p.cfg == CFG_MC3) ? 1.2 : 1.0;
+  if (d.fuse_t) {
+    // one-pass forward: next to its TM x TN blocks of 32 x 32 per K step a wave multiplies ceil(TM / WN) blocks of
+    // T = X A (+1/8 of the MFMA work on the 256x256 tile, +1/4 on 128x128, +1/2 on 128x64 and 64x128) and stages a
+    // slice of A per K tile.  Measured against the K-concatenated launch on the same tile with the contraction
+    // whole: 1.25-1.35 (256x256), 1.35-1.63 (128x128), 1.64 (128x64, 64x128); the 32-wide tiles (T as wide as the
+    // output) are taken at 2.
+    static const double ratio[6] = {1.32, 1.62, 2.0, 1.66, 2.0, 1.66};
+    if (p.cfg >= 0 && p.cfg < 6) q *= ratio[p.cfg];
+  }
   double us = rounds * (ktiles * tm.tk_us[lay] * share * q + (addend ? tm.tfix_d_us : tm.tfix_us));
   if (p.splits > 1)
     us += (double)d.M * d.N * (4.0 * (p.splits + 1) + (has_d ? e : 0.0) + e) / (mc.reduce_tbps * 1e12) * 1e6 + mc.reduce_fix_us + mc.launch_us;
@@ -144,7 +154,7 @@ extern "C" double runlora_model_time_us(int is_bwd, int variant, int64_t n, int6
                                         int dtype) {
   int dt = to_internal_dtype(dtype);
   if (dt < 0 || n < 1 || i < 1 || o < 1 || r < 1) return -1.0;
-  if (variant < 0 || variant > (is_bwd ? 8 : 2)) return -1.0;
+  if (variant < 0 || variant > (is_bwd ? 8 : 3)) return -1.0;
   LayerDims L{n, i, o, r, dt};
   L.w_int4 = dtype == RL_INT4_G64;  // priced with the int4 route's plans; merged graphs then return -1
   return model_time_us(is_bwd, variant, L);
@@ -159,7 +169,8 @@ extern "C" int runlora_select_by(int criterion, int64_t n, int64_t i, int64_t o,
   if (criterion < 0 || criterion > 2) return RL_ERR_VARIANT;
   const bool int4 = (dtype == RL_INT4_G64);
   // an int4 W has no dense buffer to merge AB into: forward1 and backward1..3 only
-  const int fmax = int4 ? 1 : 2, bmax = int4 ? 3 : 5;
+  // (forward 3 is forward1's graph in one kernel: a candidate under the time criteria only, where it applies)
+  const int fmax = int4 ? 1 : (criterion == 0 ? 2 : 3), bmax = int4 ? 3 : 5;
   LayerDims L{n, i, o, r, dt};
   L.w_int4 = int4;
   int bf = 1, bb = 1;
@@ -209,7 +220,7 @@ extern "C" int runlora_select(int64_t n, int64_t i, int64_t o, int64_t r, int dt
   int rc = runlora_select_by(criterion, n, i, o, r, dtype, fwd, bwd);
   if (rc != RL_OK) return rc;
   // RUNLORA_FORCE_FWD / RUNLORA_FORCE_BWD pin one side of the pair (debugging: run a whole model in one graph)
-  const int ff = env_variant("RUNLORA_FORCE_FWD", RL_FWD2), fb = env_variant("RUNLORA_FORCE_BWD", RL_BWD8);
+  const int ff = env_variant("RUNLORA_FORCE_FWD", RL_FWD3), fb = env_variant("RUNLORA_FORCE_BWD", RL_BWD8);
   if (ff == -2 || fb == -2) return RL_ERR_VARIANT;
   if (ff >= 0) *fwd = ff;
   if (fb >= 0) *bwd = fb;

@@ -34,8 +34,9 @@ def test_flops_match_table1(table1):
         for v in range(1, 9):
             assert rl.runlora_flops(1, v, n, i, o, r) == table1[f"backward{v}"](n, i, o, r)
         assert rl.runlora_flops(0, 0, n, i, o, r) == table1["forward1"](n, i, o, r)
+        assert rl.runlora_flops(0, 3, n, i, o, r) == table1["forward1"](n, i, o, r)   # forward1's graph in one kernel
         assert rl.runlora_flops(1, 0, n, i, o, r) == table1["backward1"](n, i, o, r) - 2 * n * i * r
-    assert rl.runlora_flops(0, 3, 1, 1, 1, 1) == -1 and rl.runlora_flops(1, 9, 1, 1, 1, 1) == -1
+    assert rl.runlora_flops(0, 4, 1, 1, 1, 1) == -1 and rl.runlora_flops(1, 9, 1, 1, 1, 1) == -1
 
 
 def test_flop_criterion_closed_forms(table1):
@@ -72,7 +73,7 @@ def test_select_time_model_returns_legal_pairs():
     for n in (128, 1024, 8192, 16384):
         for r in (8, 64, 256):
             f, b = rl.runlora_select(n, 4096, 4096, r, rl.RL_F16)
-            assert (f in (1, 2) and b in (1, 2, 3, 4, 5)) or (f, b) == (0, 0)
+            assert (f in (1, 2, 3) and b in (1, 2, 3, 4, 5)) or (f, b) == (0, 0)
             assert rl.runlora_model_time_us(0, f, n, 4096, 4096, r, rl.RL_F16) > 0
     assert rl.runlora_model_time_us(0, 7, 128, 64, 64, 8, rl.RL_F16) < 0
     assert rl.runlora_model_time_us(1, 8, 128, 64, 64, 8, rl.RL_F16) > 0      # items 6-8 are modelled too
@@ -316,7 +317,7 @@ def test_vera_calls_reject_bad_arguments_before_touching_the_gpu():
     d, b = 0x20000000, 0x20001000
     need = rl.runlora_vera_workspace_bytes(1, 1, n, i, o, r, dt)
     assert need == 2 * ((r * o * 2 + 255) // 256 * 256) + rl.runlora_workspace_bytes(1, 1, n, i, o, r, dt)
-    assert rl.runlora_vera_workspace_bytes(3, 1, n, i, o, r, dt) == 0 and rl.runlora_vera_workspace_bytes(-1, -1, n, i, o, r, dt) == 0
+    assert rl.runlora_vera_workspace_bytes(4, 1, n, i, o, r, dt) == 0 and rl.runlora_vera_workspace_bytes(-1, -1, n, i, o, r, dt) == 0
     ws = rl.rl_opts_t(None, 0x70000000, need)
 
     def fwd(variant, a=a, d=d, b=b, opts=ws):
@@ -376,7 +377,7 @@ def test_dora_calls_reject_bad_arguments_before_touching_the_gpu():
                                       br(rl.rl_saved_t()), c, br(opts) if opts else None)
 
     assert fwd(0) == rl.RL_ERR_UNSUPPORTED and fwd(1) == rl.RL_ERR_UNSUPPORTED
-    assert fwd(3) == rl.RL_ERR_VARIANT
+    assert fwd(3) == rl.RL_ERR_UNSUPPORTED and fwd(4) == rl.RL_ERR_VARIANT
     assert fwd(2, m=None) == rl.RL_ERR_NULL and fwd(2, c=None) == rl.RL_ERR_NULL
     assert fwd(2, m=m + 4) == rl.RL_ERR_ALIGN and fwd(2, c=c + 4) == rl.RL_ERR_ALIGN
     assert fwd(2, opts=None) == rl.RL_ERR_WORKSPACE

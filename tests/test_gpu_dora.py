@@ -137,12 +137,12 @@ def test_dora_refusals():
     c = torch.zeros((L.o,), dtype=torch.float32, device="cuda")
     ws = torch.empty(rl.runlora_dora_workspace_bytes(2, 5, L.n, L.i, L.o, L.r, code) + 4096, dtype=torch.uint8, device="cuda")
     saved = rl.new_saved(torch.empty((L.n, L.r), dtype=torch.bfloat16, device="cuda"))
-    for fwd in (0, 1):
+    for fwd in (0, 1, 3):
         with pytest.raises(rl.RunLoRAError) as e:
             rl.runlora_dora_forward(fwd, dev["X"], dev["W"], dev["A"], dev["B"], vec["m"][0], Y, saved, c, ws)
         assert e.value.code == rl.RL_ERR_UNSUPPORTED
     with pytest.raises(rl.RunLoRAError) as e:
-        rl.runlora_dora_forward(3, dev["X"], dev["W"], dev["A"], dev["B"], vec["m"][0], Y, saved, c, ws)
+        rl.runlora_dora_forward(4, dev["X"], dev["W"], dev["A"], dev["B"], vec["m"][0], Y, saved, c, ws)
     assert e.value.code == rl.RL_ERR_VARIANT
     saved = rl.new_saved(None)
     rl.runlora_dora_forward(2, dev["X"], dev["W"], dev["A"], dev["B"], vec["m"][0], Y, saved, c, ws)

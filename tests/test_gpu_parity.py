@@ -77,7 +77,7 @@ def test_degenerate_shapes(shape):
     """One token, smallest legal dims, rank equal to a dimension."""
     n, i, o, r = shape
     L = synth.Layer("degenerate", n, i, o, r, "bf16", 5)
-    check(L, [(1, 1), (2, 5), (0, 0), (1, 4), (2, 3), (1, 2)])
+    check(L, [(1, 1), (2, 5), (0, 0), (1, 4), (2, 3), (1, 2), (3, 1)])
 
 
 def test_zero_B_gives_zero_dA_and_plain_linear():
