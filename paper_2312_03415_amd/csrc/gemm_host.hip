@@ -12,6 +12,23 @@ static const int kTileBM[CFG_COUNT] = {256, 128, 128, 128, 32, 64, 256, 256};
 static const int kTileBN[CFG_COUNT] = {256, 128, 32, 64, 128, 128, 256, 256};
 static const int kTileBK16[CFG_COUNT] = {64, 64, 64, 64, 64, 64, 32, 64};  // K tile, 16-bit types
 
+// Slices of a contraction of length K for `tiles` output tiles of the matrix-core kernel (one 256x256 workgroup per
+// compute unit).  In units of a whole tile's time (0.024 us per k): s slices take ceil(tiles * s / 256) rounds of 1 / s
+// each; the reduce pass reads s fp32 partials per output at ~5.5 TB/s (2 tiles s / K) and is a launch of ~5 us (200 / K).
+// 96 tiles at K = 4096 run best in two slices (192 work items, one round of half tiles), not in the three that fill 256
+// slots and spill 32 items into a second round.
+static int pick_splits(int64_t tiles, int64_t K, int smin) {
+  int best = smin;
+  double best_cost = 1e30;
+  const double k = (double)(K > 0 ? K : 1);
+  for (int s = smin; s <= 8; ++s) {
+    const double rounds = (double)((tiles * s + 255) / 256);
+    const double cost = rounds / s + (s > 1 ? 2.0 * (double)tiles * s / k + 200.0 / k : 0.0);
+    if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
+  }
+  return best;
+}
+
 GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int force_cfg,
                    int force_splits, bool b_int4) {
   GemmPlan p;
@@ -54,7 +71,7 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
   if (force_splits > 0) {
     splits = force_splits;
   } else if (cfg == CFG_MC3 || cfg == CFG_MC4 || cfg == CFG_BIG) {
-    if (tiles < 160 && (int64_t)ktiles * p.bk >= 1024) splits = (int)((256 + tiles - 1) / tiles);
+    if (tiles < 160 && (int64_t)ktiles * p.bk >= 1024) splits = pick_splits(tiles, (int64_t)ktiles * p.bk, 1);
   } else if (tiles < 256 && ktiles >= 8) {
     // fill the chip (aim at ~512 workgroups) but keep >= 4 K tiles per slice
     int64_t want = (512 + tiles - 1) / tiles;
@@ -89,14 +106,11 @@ GemmPlan gemm_plan(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1, int 
 }
 
 GemmPlan gemm_tail_plan(const GemmPlan& main, int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1) {
-  // same kernel as the main launch, the contraction split so that (tiles x slices) is about one
-  // round of workgroups
+  // same kernel as the main launch with the contraction split (pick_splits)
   const int64_t nt = N - main.tail_n0;
   const int64_t tiles = (int64_t)main.nbm * ((nt + main.bn - 1) / main.bn);
-  int64_t splits = (256 + tiles - 1) / tiles;
-  if (splits < 2) splits = 2;
-  if (splits > 8) splits = 8;
-  return gemm_plan(dtype, M, nt, K0, K1, main.cfg, (int)splits);
+  const int best = pick_splits(tiles, K0 + K1, 2);
+  return gemm_plan(dtype, M, nt, K0, K1, main.cfg, best);
 }
 
 GemmPlan gemm_plan_int4(int dtype, int64_t M, int64_t N, int64_t K0, int64_t K1) {
