@@ -1,6 +1,8 @@
 // Matrix-core kernel for the large contractions of the LoRA layer (X W, dY W^T, X^T dY and their
 // K-concatenated forms [X|T][W;B], [dY|Z1][W^T;A^T]; Eq. 1 / Eq. 3 and Algorithms 1-5 of arxiv
 // 2312.03415) in bf16 / fp16 on gfx950.  Same contract as gemm_kernel (gemm_engine.hpp).
+// Dense products run on its successor with a K tile of 64 (gemm_mc64.hpp), which includes this file for the helpers
+// they share; this kernel remains the route of an int4 frozen weight (BQ) and tile id 6 of runlora_gemm.
 //
 // Shape of the kernel
 //  - 256x256 output tile per workgroup, 4 wavefronts (one per SIMD), each owning a 128x128 sub-tile:

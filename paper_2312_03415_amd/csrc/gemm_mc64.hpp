@@ -3,10 +3,10 @@
 // in bf16 / fp16 on gfx950.  Same contract as gemm_mc_kernel (gemm_mc.hpp), which it replaces wherever it applies.
 //
 // Why a second kernel.  Counters and a bare-MFMA probe name two costs of gemm_mc_kernel on this power-limited chip:
-//  - v_mfma_f32_32x32x16 sustains 1.38 PFLOP/s on random bf16 operands in a loop of nothing but MFMAs, v_mfma_f32_16x16x32
-//    1.64 (2.19 / 2.38 on zeros): the 16x16 form reads and writes a quarter of the accumulator registers per
-//    instruction and adds 32 products into each, so it moves fewer register bytes and does half as many fp32
-//    accumulator updates per FLOP.
+//  - back-to-back v_mfma_f32_16x16x32 (one wave per SIMD, operands in registers, N(0,1)-like data) sustain 1.8-1.9
+//    PFLOP/s, v_mfma_f32_32x32x16 about a sixth less in the same loop (2.4 on zeros either way): the 16x16 form reads
+//    and writes a quarter of the accumulator registers per instruction and adds 32 products into each, so it moves
+//    fewer register bytes and does half as many fp32 accumulator updates per FLOP.
 //  - With a K tile of 32 a row of a K-contiguous operand tile is 64 bytes: half a 128-byte cache line per request to
 //    L2 (33.7 M requests for 8192 x 4096 x 4096 where the bytes need 16.8 M), and one workgroup barrier, one wait and
 //    one step of the load cursor per 32 MFMAs' worth of work.
