@@ -146,6 +146,19 @@ def test_workspace_bytes_cover_intermediates():
 
 # ---- argument validation: fake (never dereferenced) device addresses ----------------------------
 
+def test_split_contractions_are_sized_by_whole_rounds():
+    """The fp32 partials in the workspace tell how a large product is split.  4096 -> 11008 at 8192 tokens: 32 x 43
+    tiles of 256 x 256; 40 tile columns are five whole rounds of 256 compute units, the 96 tiles of the last three
+    columns run in two K slices (192 work items in one round; three slices would spill into a second round).
+    8192 -> 2048 at 4096 tokens: 128 tiles, the contraction in two."""
+    n, i, o, r = 8192, 4096, 11008, 32
+    assert rl.runlora_workspace_bytes(1, -1, n, i, o, r, rl.RL_BF16) == n * r * 2 + 2 * n * 768 * 4
+    n, i, o, r = 4096, 8192, 2048, 16
+    assert rl.runlora_workspace_bytes(1, -1, n, i, o, r, rl.RL_BF16) == n * r * 2 + 2 * n * o * 4
+    # a contraction too short to pay for the partials' round trip stays whole
+    assert rl.runlora_workspace_bytes(1, -1, 4096, 512, 2048, 16, rl.RL_BF16) == 4096 * 16 * 2
+
+
 def T(ptr, rows, cols, dtype=rl.RL_BF16, ld=None):
     return rl.rl_tensor_t(ptr, rows, cols, cols if ld is None else ld, dtype, None, 0)
 
