@@ -60,6 +60,8 @@ def parse():
     ap.add_argument("--no-extra-ranks", action="store_true", help="llama7b: skip the extra timings of the block at ranks 8 and 128")
     ap.add_argument("--sets", type=int, default=4, help="rotating input/output sets (together beyond the 256 MB Infinity Cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--keep-t", action="store_true",
+                    help="forward1 keeps T = XA for the backward (n*r elements per layer; selection criterion 3)")
     ap.add_argument("--keep-merged", action="store_true",
                     help="let forward2 keep W + AB for backward4/5 (i*o elements held per layer; pairs chosen for that)")
     ap.add_argument("--dropout", type=float, default=0.0,
@@ -172,7 +174,7 @@ def main():
                 fwd, bwd = (int(v) for v in args.pair.split(","))
             else:
                 fwd, bwd = rl.runlora_select(L.n, L.i, L.o, L.r, rl.RL_INT4_G64 if int4 else code,
-                                             criterion=2 if args.keep_merged else None)
+                                             criterion=2 if args.keep_merged else (3 if args.keep_t else None))
             wd = rl.RL_INT4_G64 if int4 else None
             ws_bytes = max(rl.runlora_workspace_bytes(fwd, bwd, L.n, L.i, L.o, L.r, code, wd),
                            rl.runlora_workspace_bytes(0, 0, L.n, L.i, L.o, L.r, code, wd))
@@ -191,7 +193,8 @@ def main():
         for st in (state if only is None else [only]):
             t = st["sets"][k % args.sets]
             fwd, bwd = (0, 0) if default_chain else st["pair"]
-            saved = rl.new_saved(t["T"] if fwd == 0 else None, t["M"] if fwd == 2 and bwd in rl.BWD_MERGED else None)
+            keep_t = fwd == 0 or (args.keep_t and fwd in (1, 3) and bwd in (1, 5, 6, 7))
+            saved = rl.new_saved(t["T"] if keep_t else None, t["M"] if fwd == 2 and bwd in rl.BWD_MERGED else None)
             if args.dora and not default_chain:
                 rl.runlora_dora_forward(fwd, t["X"], t["W"], t["A"], t["B"], t["m"], t["Y"], saved, t["c"], st["ws"])
                 rl.runlora_dora_backward(bwd, t["dY"], saved, t["W"], t["A"], t["B"], t["m"], t["c"], t["Y"], t["dX"], t["dA"],
@@ -355,7 +358,7 @@ def main():
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": wl_name, "layers": [dict(name=L.name, n=L.n, d_in=L.i, d_out=L.o, r=L.r) for L in layers],
                    "pairs": {st["L"].name: list(st["pair"]) for st in state}, "input_sets": args.sets,
-                   "keep_merged": bool(args.keep_merged), "lora_dropout": args.dropout,
+                   "keep_merged": bool(args.keep_merged), "keep_t": bool(args.keep_t), "lora_dropout": args.dropout,
                    "adapter": "vera" if args.vera else ("dora" if args.dora else "lora")},
         "ms_per_step_default_chain": round(sec_def * 1e3, 4),
         "speedup_over_default_chain": round(sec_def / sec_sel, 4),

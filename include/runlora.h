@@ -133,8 +133,12 @@ typedef struct {
  * fills the rest; runlora_backward reads it.  X is borrowed: the caller keeps the buffer alive and
  * unchanged until the backward has run.
  *   T  caller-provided [n,r] buffer (ldt elements per row, same dtype as X).  Set T/ldt BEFORE
- *      calling runlora_forward(RL_FWD_DEFAULT, ...), which fills it with s XA; other variants
- *      ignore it and set it to NULL.
+ *      calling runlora_forward(RL_FWD_DEFAULT, ...), which fills it with s XA (required).  Optional
+ *      for RL_FWD1 (and RL_FWD3, which then runs as RL_FWD1): s XA is written there instead of into
+ *      the workspace and left for the backward, and RL_BWD1 / 5 / 6 / 7 read it instead of forming
+ *      X A again (one pass over X saved, n*r elements held meanwhile: the memory Section 2 says the
+ *      RunLoRA forwards do not spend, r/i of X).  A T left by RL_FWD_DEFAULT serves them as well.
+ *      NULL: nothing is kept.  RL_FWD2 ignores it and sets it to NULL.
  *   M  optional caller-provided [i,o] buffer (ldm elements per row, same dtype as X).  Set M/ldm
  *      BEFORE calling runlora_forward(RL_FWD2, ...): W + s AB is then formed there instead of in
  *      the workspace and left for the backward, and RL_BWD4 / 5 / 7 / 8 read it instead of forming
@@ -301,7 +305,9 @@ int runlora_select(int64_t n_tokens, int64_t d_in, int64_t d_out, int64_t r, int
 
 /* Same, with the criterion explicit: 0 = Table 1 FLOPs (ties -> lower id), 1 = time model,
  * 2 = time model for a caller that lets forward2 keep W + AB for the backward (rl_saved_t.M):
- * pairs of forward2 with backward4 / 5 are then priced without the second W + AB pass. */
+ * pairs of forward2 with backward4 / 5 are then priced without the second W + AB pass;
+ * 3 = time model for a caller that lets forward1 keep T = XA (rl_saved_t.T): forward1 with
+ * backward1 / 5 is then priced without the second X A pass. */
 int runlora_select_by(int criterion, int64_t n_tokens, int64_t d_in, int64_t d_out, int64_t r,
                       int dtype, int* fwd_variant, int* bwd_variant);
 
@@ -319,8 +325,10 @@ double runlora_model_time_us(int is_bwd, int variant, int64_t n, int64_t i, int6
 
 /*
  * Bytes a forward variant keeps for its backward besides X itself: n*r elements for the default
- * chain's T = XA, nothing for forward1 / forward2 (the memory saving of Section 2), plus i*o
- * elements if forward2 is asked to keep W + AB (keep_merged != 0).  0 for an unknown variant.
+ * chain's T = XA, nothing for forward1 / forward2 (the memory saving of Section 2), plus what the
+ * caller asks to be kept (keep_merged is a bit set): bit 0, i*o elements if forward2 keeps W + AB
+ * (rl_saved_t.M); bit 1, n*r elements if forward1 / forward 3 keeps T = XA (rl_saved_t.T).
+ * 0 for an unknown variant.
  */
 size_t runlora_saved_bytes(int fwd, int64_t n, int64_t i, int64_t o, int64_t r, int dtype, int keep_merged);
 

@@ -368,9 +368,9 @@ def runlora_workspace_bytes(fwd, bwd, n, i, o, r, dtype, w_dtype=None):
     return int(lib().runlora_workspace_bytes_w(fwd, bwd, n, i, o, r, dtype, w_dtype))
 
 
-def runlora_saved_bytes(fwd, n, i, o, r, dtype, keep_merged=False):
+def runlora_saved_bytes(fwd, n, i, o, r, dtype, keep_merged=False, keep_t=False):
     """Bytes forward graph `fwd` keeps for the backward besides X."""
-    return int(lib().runlora_saved_bytes(fwd, n, i, o, r, dtype, int(bool(keep_merged))))
+    return int(lib().runlora_saved_bytes(fwd, n, i, o, r, dtype, int(bool(keep_merged)) | (2 if keep_t else 0)))
 
 
 def runlora_gemm(A, B, C, a_strided=False, b_kcontig=False, A2=None, B2=None, D=None, tile_cfg=-1, splits=0,

@@ -311,7 +311,9 @@ int forward_impl(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const 
     op.M.ld = saved->ldm;
     op.keep_M = true;
   }
-  if (variant == RL_FWD_DEFAULT) {
+  // forward1 (also asked for as forward 3) keeps T = s XA for the backward when the caller hands it a buffer
+  const bool keep_T = (variant == RL_FWD1 || variant == RL_FWD3) && saved->T != nullptr;
+  if (variant == RL_FWD_DEFAULT || keep_T) {
     if (!saved->T) return RL_ERR_NULL;
     const int64_t q = dtype == RL_F32 ? 4 : 8;
     if (saved->ldt < r) return RL_ERR_SHAPE;
@@ -322,6 +324,7 @@ int forward_impl(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const 
       return RL_ERR_ALIAS;
     op.T.ptr = saved->T;
     op.T.ld = saved->ldt;
+    op.keep_T = keep_T;
   }
   Schedule sch;
   char* ws = opts ? static_cast<char*>(opts->workspace) : nullptr;
@@ -357,7 +360,7 @@ int forward_impl(int variant, const rl_tensor_t* X, const rl_tensor_t* W, const 
   saved->scale = scale;
   saved->dropout_thr = L.drop_thr;
   saved->dropout_seed = L.drop_thr ? opts->dropout_seed : 0u;
-  if (variant != RL_FWD_DEFAULT) { saved->T = nullptr; saved->ldt = 0; }
+  if (variant != RL_FWD_DEFAULT && !keep_T) { saved->T = nullptr; saved->ldt = 0; }
   if (variant != RL_FWD2) { saved->M = nullptr; saved->ldm = 0; }
   return RL_OK;
 }
@@ -406,6 +409,13 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
     if (saved->fwd_variant != RL_FWD_DEFAULT || !saved->T || saved->ldt < r) return RL_ERR_SAVED_MISMATCH;
     if ((reinterpret_cast<uintptr_t>(saved->T) & 15) != 0 || saved->ldt % q != 0) return RL_ERR_ALIGN;
   }
+  // T = s XA kept by the default chain's forward or by forward1 serves the graphs that would form X A again
+  const bool use_T = (variant == RL_BWD1 || variant == RL_BWD5 || variant == RL_BWD6 || variant == RL_BWD7) && saved->T != nullptr &&
+                     (saved->fwd_variant == RL_FWD_DEFAULT || saved->fwd_variant == RL_FWD1 || saved->fwd_variant == RL_FWD3);
+  if (use_T) {
+    if (saved->ldt < r) return RL_ERR_SAVED_MISMATCH;
+    if ((reinterpret_cast<uintptr_t>(saved->T) & 15) != 0 || saved->ldt % q != 0) return RL_ERR_ALIGN;
+  }
   // W + s AB kept by forward2 serves the graphs that would form it again
   const bool merged_bwd = variant == RL_BWD4 || variant == RL_BWD5 || variant == RL_BWD7 || variant == RL_BWD8;
   const bool use_M = merged_bwd && saved->fwd_variant == RL_FWD2 && saved->M != nullptr;
@@ -417,7 +427,7 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   Range in[7] = {range_of(dY->data, n, dY->ld, o, esz), range_of(saved->X, n, saved->ldx, i, esz),
                  weight_range(W, i, o, esz, w_int4), range_of(A->data, i, A->ld, r, esz),
                  range_of(B->data, r, B->ld, o, esz),
-                 (variant == RL_BWD_DEFAULT) ? range_of(saved->T, n, saved->ldt, r, esz) : Range{nullptr, nullptr},
+                 (variant == RL_BWD_DEFAULT || use_T) ? range_of(saved->T, n, saved->ldt, r, esz) : Range{nullptr, nullptr},
                  use_M ? range_of(saved->M, i, saved->ldm, o, esz) : Range{nullptr, nullptr}};
   Range outr[3];
   int nout = 0;
@@ -441,6 +451,7 @@ extern "C" int runlora_backward(int variant, const rl_tensor_t* dY, const rl_sav
   }
   BwdOperands op;
   if (use_M) { op.M.ptr = saved->M; op.M.ld = saved->ldm; op.have_M = true; }
+  op.have_T = use_T;
   op.dY = mat(dY); op.W = weight_mat(W, o, w_int4); op.A = mat(A); op.B = mat(B);
   op.X.ptr = saved->X; op.X.ld = saved->ldx;
   op.T.ptr = saved->T; op.T.ld = saved->ldt;
@@ -749,9 +760,9 @@ extern "C" size_t runlora_saved_bytes(int fwd, int64_t n, int64_t i, int64_t o, 
   const size_t e = dtype_size(dt);
   switch (fwd) {
     case RL_FWD_DEFAULT: return (size_t)n * (size_t)r * e;  // T = XA
-    case RL_FWD1: return 0;
-    case RL_FWD3: return 0;
-    case RL_FWD2: return keep_merged ? (size_t)i * (size_t)o * e : 0;
+    case RL_FWD1:
+    case RL_FWD3: return (keep_merged & 2) ? (size_t)n * (size_t)r * e : 0;  // T = XA kept on request
+    case RL_FWD2: return (keep_merged & 1) ? (size_t)i * (size_t)o * e : 0;
     default: return 0;
   }
 }

@@ -247,13 +247,13 @@ bool build_forward(int variant, const LayerDims& L, const FwdOperands& op, void*
       break;
     }
     case 3:  // forward1 in one pass over X; where that build does not apply, forward1's two launches
-      if (r <= kFuseMaxR && !L.w_int4 && !L.drop_thr) {
+      if (r <= kFuseMaxR && !L.w_int4 && !L.drop_thr && !op.keep_T) {
         b.fused_forward("Y = X [W|A] ; Y += T B", op.X, op.W, op.A, op.B, op.Y, op.bias);
         break;
       }
       [[fallthrough]];
     case 1: {  // forward1: (XW) + ((XA)B), the sum folded into one contraction over [X|T]
-      Mat T = b.scratch(n, r);
+      Mat T = op.keep_T ? op.T : b.scratch(n, r);
       b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T, true, true});
       b.gemm("Y = [X|T] [W;B]", 0, 0, n, o, i, op.X, op.W, op.Y, nullptr, r, &T, &op.B, true, 1.f, op.bias);
       break;
@@ -294,8 +294,8 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
       break;
     }
     case 1: {  // Algorithm 1
-      Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r);
-      rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA || dX, dB, dA, dB);
+      Mat Z1 = b.scratch(n, r), Z2 = op.have_T ? op.T : b.scratch(n, r);
+      rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA || dX, dB && !op.have_T, dA, dB);
       if (dX && L.drop_thr) {  // the mask sits between the two products: no concatenated contraction
         b.gemm("dX = dY W^T", 0, 1, n, i, o, op.dY, op.W, op.dX, nullptr, 0, nullptr, nullptr, true);
         b.gemm("dX += Z1 A^T", 0, 1, n, i, r, Z1, op.A, op.dX, &op.dX, 0, nullptr, nullptr, false, 1.f, nullptr, true);
@@ -335,20 +335,21 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     }
     case 5: {  // Algorithm 5
       if (L.w_int4) return false;
-      Mat Z1 = b.scratch(n, r), Z2 = b.scratch(n, r), Z3 = op.have_M ? op.M : b.scratch(i, o);
+      Mat Z1 = b.scratch(n, r), Z2 = op.have_T ? op.T : b.scratch(n, r), Z3 = op.have_M ? op.M : b.scratch(i, o);
       if (dX && !op.have_M) b.merge("Z3 = W + A B", op.A, op.B, op.W, Z3);
-      rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA, dB, dA, dB);
+      rank_r_pass(b, op, n, i, o, r, Z1, Z2, dA, dB && !op.have_T, dA, dB);
       if (dX) b.gemm("dX = dY Z3^T", 0, 1, n, i, o, op.dY, Z3, op.dX);
       break;
     }
     // Items 6-8 of the list of eight bracketings in Section 2 (the paper drops them because Table 1
     // never ranks them first; they are built from the same launches as Algorithms 1-5)
     case 6: {  // dA = (X^T dY) B^T, dB = (A^T X^T) dY, dX = dY W^T + (dY B^T) A^T
-      Mat Z1 = b.scratch(n, r), T = b.scratch(n, r), Z2 = b.scratch(i, o);
+      Mat Z1 = b.scratch(n, r), T = op.have_T ? op.T : b.scratch(n, r), Z2 = b.scratch(i, o);
       const Builder::Sk z1{0, 1, n, r, o, op.dY, op.B, Z1, true}, t{0, 0, n, r, i, op.X, op.A, T, true};
-      if (dX && dB) b.skinny2("Z1 = dY B^T ; T = X A", "Z1 = dY B^T", z1, "T = X A", t);
+      const bool need_T = dB && !op.have_T;
+      if (dX && need_T) b.skinny2("Z1 = dY B^T ; T = X A", "Z1 = dY B^T", z1, "T = X A", t);
       else if (dX) b.skinny("Z1 = dY B^T", z1);
-      else if (dB) b.skinny("T = X A", t);
+      else if (need_T) b.skinny("T = X A", t);
       if (dA) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
       if (dA) b.skinny("dA = Z2 B^T", {0, 1, i, r, o, Z2, op.B, op.dA, true});
       if (dB) b.skinny("dB = T^T dY", {1, 0, r, o, n, T, op.dY, op.dB});
@@ -357,9 +358,9 @@ bool build_backward(int variant, const LayerDims& L, const BwdOperands& op, void
     }
     case 7: {  // dA = (X^T dY) B^T, dB = (A^T X^T) dY, dX = dY (W^T + B^T A^T)
       if (L.w_int4) return false;
-      Mat T = b.scratch(n, r), Z2 = b.scratch(i, o), M = op.have_M ? op.M : b.scratch(i, o);
+      Mat T = op.have_T ? op.T : b.scratch(n, r), Z2 = b.scratch(i, o), M = op.have_M ? op.M : b.scratch(i, o);
       if (dX && !op.have_M) b.merge("M = W + A B", op.A, op.B, op.W, M);
-      if (dB) b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T, true});
+      if (dB && !op.have_T) b.skinny("T = X A", {0, 0, n, r, i, op.X, op.A, T, true});
       if (dA) b.gemm("Z2 = X^T dY", 1, 0, i, o, n, op.X, op.dY, Z2);
       if (dA) b.skinny("dA = Z2 B^T", {0, 1, i, r, o, Z2, op.B, op.dA, true});
       if (dB) b.skinny("dB = T^T dY", {1, 0, r, o, n, T, op.dY, op.dB});

@@ -56,6 +56,7 @@ struct Schedule {
 
 struct FwdOperands {
   Mat X, W, A, B, Y, T;  // T: caller's buffer for the default chain (kept for the backward)
+  bool keep_T = false;   // forward1: write T = s XA into T (caller's buffer) and leave it for the backward
   const void* bias = nullptr;  // frozen bias of the base layer [o], added by the GEMM that writes Y
   Mat M;                       // forward2 with keep_M: W + s AB goes here (caller's buffer) and stays
   bool keep_M = false;
@@ -65,6 +66,8 @@ struct BwdOperands {
   bool want_dX = true, want_dA = true, want_dB = true;
   Mat M;                // have_M: W + s AB as forward2 left it; the merged graphs read it instead of
   bool have_M = false;  // forming it again
+  bool have_T = false;  // T = s XA as the default chain's forward or forward1 left it: the graphs that would form
+                        // X A again (Z2 of Algorithms 1 and 5, T of items 6 and 7) read it instead
 };
 
 // ws_base may be null (sizing / modelling).  Returns false for an unknown variant.

@@ -114,8 +114,9 @@ static double step_time_us(const Step& s) {
   return gemm_time_us(s.d, s.plan);
 }
 
-// have_M: the backward finds W + AB kept by forward2 and does not form it again
-double model_time_us(int is_bwd, int variant, const LayerDims& L, bool have_M = false) {
+// have_M: the backward finds W + AB kept by forward2 and does not form it again; have_T: it finds T = XA kept by
+// forward1 (keep_T on the forward side changes nothing: the same launch writes T elsewhere)
+double model_time_us(int is_bwd, int variant, const LayerDims& L, bool have_M = false, bool have_T = false) {
   Schedule sch;
   bool ok;
   if (!is_bwd) {
@@ -124,6 +125,7 @@ double model_time_us(int is_bwd, int variant, const LayerDims& L, bool have_M = 
   } else {
     BwdOperands op;
     op.have_M = have_M;
+    op.have_T = have_T;
     ok = build_backward(variant, L, op, nullptr, &sch);
   }
   if (!ok) return -1.0;
@@ -166,7 +168,7 @@ extern "C" int runlora_select_by(int criterion, int64_t n, int64_t i, int64_t o,
   if (n < 1 || i < 1 || o < 1 || r < 1) return RL_ERR_SHAPE;
   int dt = to_internal_dtype(dtype);
   if (dt < 0) return RL_ERR_DTYPE;
-  if (criterion < 0 || criterion > 2) return RL_ERR_VARIANT;
+  if (criterion < 0 || criterion > 3) return RL_ERR_VARIANT;
   const bool int4 = (dtype == RL_INT4_G64);
   // an int4 W has no dense buffer to merge AB into: forward1 and backward1..3 only
   // (forward 3 is forward1's graph in one kernel: a candidate under the time criteria only, where it applies)
@@ -195,6 +197,15 @@ extern "C" int runlora_select_by(int criterion, int64_t n, int64_t i, int64_t o,
       for (int v = 4; v <= 5; ++v) {
         const double c = f2 + model_time_us(1, v, L, true);
         if (c < cf + cb) { cf = f2; cb = c - f2; bf = 2; bb = v; }
+      }
+    }
+    // Criterion 3, for callers that let forward1 keep T = XA (n r elements): forward1 paired with the backwards that
+    // would form X A again (Algorithms 1 and 5) is priced without that pass; forward2 computes no T, so its pairs stay
+    if (criterion == 3) {
+      const double f1 = model_time_us(0, 1, L);
+      for (int v = 1; v <= bmax; v += 4) {  // Algorithms 1 and 5
+        const double c = f1 + model_time_us(1, v, L, false, true);
+        if (c < cf + cb) { cf = f1; cb = c - f1; bf = 1; bb = v; }
       }
     }
     const double c0 = model_time_us(0, 0, L) + model_time_us(1, 0, L);

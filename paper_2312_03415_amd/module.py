@@ -35,13 +35,14 @@ class RunLoRAFunction(torch.autograd.Function):
     """y = x W + bias + scale (x A) B with W and bias frozen; gradients for x, A and B (Eq. 1, Eq. 3).
 
     pair = (forward variant, backward variant) as runlora_select returns them; keep_merged lets
-    forward2 hold W + scale AB for a merged backward (i*o elements kept until the backward ran);
+    forward2 hold W + scale AB for a merged backward (i*o elements kept until the backward ran), keep_t
+    lets forward1 hold scale XA for the backwards that would form it again (n*r elements);
     dropout = (p, seed) or None: LoRA dropout on the adapter's input (mask defined in runlora.h; the
     backward regenerates it from the seed the forward recorded).
     """
 
     @staticmethod
-    def forward(ctx, x, W, A, B, bias, scale, pair, keep_merged, dropout=None):
+    def forward(ctx, x, W, A, B, bias, scale, pair, keep_merged, dropout=None, keep_t=False):
         fwd, bwd = pair
         i, o = W.shape
         r = A.shape[1]
@@ -51,7 +52,8 @@ class RunLoRAFunction(torch.autograd.Function):
         n = x2.shape[0]
         code = rl.dtype_code(x.dtype)
         y = torch.empty((n, o), dtype=x.dtype, device=x.device)
-        T = torch.empty((n, r), dtype=x.dtype, device=x.device) if fwd == rl.FWD_DEFAULT else None
+        keeps_t = fwd == rl.FWD_DEFAULT or (keep_t and fwd in (rl.FWD1, rl.FWD3) and bwd in (1, 5, 6, 7))
+        T = torch.empty((n, r), dtype=x.dtype, device=x.device) if keeps_t else None
         M = None
         if keep_merged and fwd == rl.FWD2 and bwd in rl.BWD_MERGED:
             M = torch.empty((i, o), dtype=x.dtype, device=x.device)
@@ -84,7 +86,7 @@ class RunLoRAFunction(torch.autograd.Function):
         rl.runlora_backward(ctx.bwd, dy2, ctx.saved, W, A, B, dx, dA, dB, workspace=ws)
         if dx is not None:
             dx = dx.view(ctx.x_shape)
-        return dx, None, dA, dB, None, None, None, None, None
+        return dx, None, dA, dB, None, None, None, None, None, None
 
 
 class RunLoRALinear(nn.Module):
@@ -92,10 +94,10 @@ class RunLoRALinear(nn.Module):
     optional frozen bias, trainable A [d_in, r] and B [r, d_out], scale = alpha / r.
 
     The (forward, backward) pair is chosen per token count by runlora_select the first time that
-    count is seen (criterion 2 when keep_merged), or fixed with pair=(f, b).
+    count is seen (criterion 2 when keep_merged, 3 when keep_t), or fixed with pair=(f, b).
     """
 
-    def __init__(self, weight, r, alpha=None, bias=None, pair=None, keep_merged=False, dropout=0.0):
+    def __init__(self, weight, r, alpha=None, bias=None, pair=None, keep_merged=False, dropout=0.0, keep_t=False):
         super().__init__()
         d_in, d_out = weight.shape
         self.d_in, self.d_out, self.r = d_in, d_out, r
@@ -107,6 +109,7 @@ class RunLoRALinear(nn.Module):
         self.lora_B = nn.Parameter(torch.zeros(r, d_out, dtype=weight.dtype, device=weight.device))
         self.pair = pair
         self.keep_merged = keep_merged
+        self.keep_t = keep_t
         self.dropout = float(dropout)  # LoRA dropout probability, applied in training mode only
         self.last_dropout_seed = None  # seed of the most recent training-mode forward (for reproducing its mask)
         self._pairs = {}
@@ -124,7 +127,7 @@ class RunLoRALinear(nn.Module):
         p = self._pairs.get(n_tokens)
         if p is None:
             code = rl.dtype_code(self.weight.dtype)
-            p = rl.runlora_select(n_tokens, self.d_in, self.d_out, self.r, code, criterion=2 if self.keep_merged else None)
+            p = rl.runlora_select(n_tokens, self.d_in, self.d_out, self.r, code, criterion=2 if self.keep_merged else (3 if self.keep_t else None))
             self._pairs[n_tokens] = p
         return p
 
@@ -136,9 +139,9 @@ class RunLoRALinear(nn.Module):
             self.last_dropout_seed = int(torch.randint(0, 2 ** 31 - 1, (1,)).item())
             pair = self.pair if self.pair in ((0, 0), (0, 1), (1, 1)) else (1, 1)
             return RunLoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.bias, self.scale, pair, False,
-                                         (self.dropout, self.last_dropout_seed))
+                                         (self.dropout, self.last_dropout_seed), self.keep_t)
         return RunLoRAFunction.apply(x, self.weight, self.lora_A, self.lora_B, self.bias, self.scale,
-                                     self.pair_for(n), self.keep_merged)
+                                     self.pair_for(n), self.keep_merged, None, self.keep_t)
 
     def extra_repr(self):
         return f"d_in={self.d_in}, d_out={self.d_out}, r={self.r}, scale={self.scale:g}, bias={self.bias is not None}"

@@ -113,10 +113,24 @@ def test_select_with_kept_merged_weight():
             f2, b2 = rl.runlora_select(n, i, o, r, rl.RL_BF16, criterion=2)
             assert (f2, b2) == (f1, b1) or (f2 == 2 and b2 in (4, 5)), (n, i, o, r)
     f, b = ctypes.c_int(), ctypes.c_int()
-    assert rl.lib().runlora_select_by(3, 8, 8, 8, 8, rl.RL_F16, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_VARIANT
+    assert rl.lib().runlora_select_by(4, 8, 8, 8, 8, rl.RL_F16, ctypes.byref(f), ctypes.byref(b)) == rl.RL_ERR_VARIANT
     # an int4 W has no merged graphs whatever the criterion
     f2, b2 = rl.runlora_select(16384, 4096, 4096, 64, rl.RL_INT4_G64, criterion=2)
     assert f2 in (0, 1) and b2 in (0, 1, 2, 3)
+
+
+def test_select_with_kept_T():
+    """Criterion 3 prices forward1 + backward1/5 without the second X A pass: it may only move the choice towards
+    such a pair, and the model must see the saving."""
+    for n in (128, 1024, 8192, 16384):
+        for i, o, r in ((4096, 4096, 32), (4096, 11008, 32), (11008, 4096, 128), (4096, 4096, 1024)):
+            p1 = rl.runlora_select(n, i, o, r, rl.RL_BF16, criterion=1)
+            p3 = rl.runlora_select(n, i, o, r, rl.RL_BF16, criterion=3)
+            assert p3 == p1 or (p3[0] == 1 and p3[1] in (1, 5)), (n, i, o, r)
+    # at the Llama shapes the kept T decides between forward1 and forward2, which the plain model prices alike
+    assert rl.runlora_select(8192, 4096, 4096, 32, rl.RL_BF16, criterion=3) == (1, 1)
+    assert rl.runlora_select(8192, 11008, 4096, 32, rl.RL_BF16, criterion=3) == (1, 1)
+    assert rl.runlora_select(4096, 5120, 13824, 64, rl.RL_INT4_G64, criterion=3) == (1, 1)
 
 
 def test_saved_bytes_is_the_memory_claim_of_section2():
@@ -130,6 +144,11 @@ def test_saved_bytes_is_the_memory_claim_of_section2():
     assert rl.runlora_saved_bytes(2, n, i, o, r, rl.RL_BF16, keep_merged=True) == i * o * 2
     assert rl.runlora_saved_bytes(1, n, i, o, r, rl.RL_BF16, keep_merged=True) == 0
     assert rl.runlora_saved_bytes(5, n, i, o, r, rl.RL_BF16) == 0
+    # forward1 (also as forward 3) asked to keep XA holds what the default chain holds
+    assert rl.runlora_saved_bytes(1, n, i, o, r, rl.RL_BF16, keep_t=True) == n * r * 2
+    assert rl.runlora_saved_bytes(3, n, i, o, r, rl.RL_BF16, keep_t=True) == n * r * 2
+    assert rl.runlora_saved_bytes(2, n, i, o, r, rl.RL_BF16, keep_t=True) == 0
+    assert rl.runlora_saved_bytes(2, n, i, o, r, rl.RL_BF16, keep_merged=True, keep_t=True) == i * o * 2
 
 
 def test_workspace_bytes_cover_intermediates():

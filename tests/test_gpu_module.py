@@ -14,7 +14,7 @@ from paper_2312_03415_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-def make_layer(d_in, d_out, r, dtype, alpha, with_bias, pair=None, keep_merged=False, seed=41):
+def make_layer(d_in, d_out, r, dtype, alpha, with_bias, pair=None, keep_merged=False, seed=41, keep_t=False):
     from paper_2312_03415_amd.module import RunLoRALinear
     import torch
     st = {"W": synth.store(synth.normal(seed, 2, (d_in, d_out), 1.0 / d_in), dtype),
@@ -23,7 +23,7 @@ def make_layer(d_in, d_out, r, dtype, alpha, with_bias, pair=None, keep_merged=F
           "bias": synth.store(synth.normal(seed, 9, (d_out,)), dtype)}
     host = {k: synth.widen(v, dtype) for k, v in st.items()}
     layer = RunLoRALinear(to_device(st["W"], dtype), r, alpha, to_device(st["bias"], dtype) if with_bias else None,
-                          pair=pair, keep_merged=keep_merged)
+                          pair=pair, keep_merged=keep_merged, keep_t=keep_t)
     with torch.no_grad():
         layer.lora_A.copy_(to_device(st["A"], dtype))
         layer.lora_B.copy_(to_device(st["B"], dtype))
@@ -32,11 +32,12 @@ def make_layer(d_in, d_out, r, dtype, alpha, with_bias, pair=None, keep_merged=F
     return layer, host
 
 
-@pytest.mark.parametrize("dtype,pair", [("bf16", None), ("bf16", (0, 0)), ("f16", (2, 5)), ("f32", (1, 3)), ("bf16", (2, 4))])
+@pytest.mark.parametrize("dtype,pair", [("bf16", None), ("bf16", (0, 0)), ("f16", (2, 5)), ("f32", (1, 3)), ("bf16", (2, 4)), ("bf16", (1, 1)),
+                                        ("f16", (3, 5))])
 def test_layer_matches_oracle(dtype, pair):
     import torch
     b, s, d_in, d_out, r, alpha = 3, 50, 264, 136, 8, 20.0
-    layer, host = make_layer(d_in, d_out, r, dtype, alpha, True, pair, keep_merged=pair in ((2, 5), (2, 4)))
+    layer, host = make_layer(d_in, d_out, r, dtype, alpha, True, pair, keep_merged=pair in ((2, 5), (2, 4)), keep_t=pair in ((1, 1), (3, 5)))
     xs = synth.store(synth.normal(42, 1, (b * s, d_in)), dtype)
     gs = synth.store(synth.normal(42, 5, (b * s, d_out)), dtype)
     x = to_device(xs, dtype).view(b, s, d_in).requires_grad_(True)
@@ -89,8 +90,9 @@ def test_memory_kept_between_forward_and_backward():
     code = rl.RL_BF16
     xs = to_device(synth.store(synth.normal(61, 1, (n, d_in)), "bf16"), "bf16").requires_grad_(True)
     held = {}
-    for name, pair, keep in (("default", (0, 0), False), ("fwd1", (1, 1), False), ("fwd2", (2, 5), False), ("fwd2+M", (2, 5), True)):
-        layer, _ = make_layer(d_in, d_out, r, "bf16", None, False, pair, keep)
+    for name, pair, keep in (("default", (0, 0), False), ("fwd1", (1, 1), False), ("fwd2", (2, 5), False), ("fwd2+M", (2, 5), True),
+                             ("fwd1+T", (1, 1), "t")):
+        layer, _ = make_layer(d_in, d_out, r, "bf16", None, False, pair, keep is True, keep_t=keep == "t")
         layer(xs).sum().backward()      # warm: workspace and autograd buffers exist
         layer.zero_grad(); xs.grad = None
         torch.cuda.synchronize()
@@ -103,6 +105,7 @@ def test_memory_kept_between_forward_and_backward():
     assert held["fwd1"] == 0 and held["fwd2"] == 0
     assert held["default"] == rl.runlora_saved_bytes(0, n, d_in, d_out, r, code) == n * r * 2
     assert held["fwd2+M"] == rl.runlora_saved_bytes(2, n, d_in, d_out, r, code, keep_merged=True) == d_in * d_out * 2
+    assert held["fwd1+T"] == rl.runlora_saved_bytes(1, n, d_in, d_out, r, code, keep_t=True) == n * r * 2
 
 
 def test_wrap_linears_replaces_and_freezes():

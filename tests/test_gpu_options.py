@@ -108,6 +108,54 @@ def test_forward2_keeps_merged_weight_for_the_backward(dtype):
     assert s1.M is None
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_forward1_keeps_XA_for_the_backward(dtype):
+    """rl_saved_t.T given to forward1 (or forward 3): T = s XA stays there and backward 1 / 5 / 6 / 7 read it
+    instead of forming X A again; a T left by the default chain's forward serves them as well.  Results against the
+    oracle; the kept T against s X A; the backward needs less workspace work (one launch fewer in its record)."""
+    import torch
+    L = synth.Layer("keepT", 333, 264, 392, 24, dtype, 41)
+    dev, host = layer_on_device(L)
+    td, code = torch_dtype(dtype), rl.dtype_from_name(dtype)
+    scale = 0.5
+    want = scaled_reference(host, scale, np.zeros(L.o))
+    T_want = scale * (host["X"] @ host["A"])
+    for fwd in (1, 3, 0):
+        for bwd in (1, 5, 6, 7):
+            print(f"case kept T dtype={dtype} fwd={fwd} bwd={bwd}", flush=True)
+            T = torch.full((L.n, L.r), float("nan"), dtype=td, device="cuda")
+            Y = torch.full((L.n, L.o), float("nan"), dtype=td, device="cuda")
+            gX, gA, gB = (torch.full(s, float("nan"), dtype=td, device="cuda") for s in ((L.n, L.i), (L.i, L.r), (L.r, L.o)))
+            ws = rl.new_workspace(fwd, bwd, L.n, L.i, L.o, L.r, code)
+            saved = rl.new_saved(T)
+            rl.runlora_forward(fwd, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=ws, scale=scale)
+            assert saved.T == T.data_ptr() and saved.fwd_variant == fwd
+            assert relerr(to_f64(T), T_want) < TOL[dtype]
+            ws.fill_(0xFF)                      # the backward must not expect anything of the forward's scratch
+            rl.runlora_profile_enable(32)
+            rl.runlora_backward(bwd, dev["dY"], saved, dev["W"], dev["A"], dev["B"], gX, gA, gB, workspace=ws)
+            torch.cuda.synchronize()
+            kept = [r["what"] for r in rl.runlora_profile_collect(32)]
+            rl.runlora_profile_disable()
+            assert not any("X A" in w for w in kept), kept
+            for k, g in (("Y", Y), ("dX", gX), ("dA", gA), ("dB", gB)):
+                assert relerr(to_f64(g), want[k]) < TOL[dtype], (fwd, bwd, k)
+    # without a buffer nothing is kept and the backward forms X A itself
+    ws = rl.new_workspace(1, 1, L.n, L.i, L.o, L.r, code)
+    saved = rl.new_saved()
+    rl.runlora_forward(1, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=ws, scale=scale)
+    assert not saved.T
+    rl.runlora_profile_enable(32)
+    rl.runlora_backward(1, dev["dY"], saved, dev["W"], dev["A"], dev["B"], gX, gA, gB, workspace=ws)
+    torch.cuda.synchronize()
+    assert any("X A" in r["what"] for r in rl.runlora_profile_collect(32))
+    rl.runlora_profile_disable()
+    # forward2 computes no T: the buffer is ignored
+    saved = rl.new_saved(T)
+    rl.runlora_forward(2, dev["X"], dev["W"], dev["A"], dev["B"], Y, saved, workspace=rl.new_workspace(2, 1, L.n, L.i, L.o, L.r, code), scale=scale)
+    assert not saved.T
+
+
 @pytest.mark.parametrize("cfg,splits,dtype", [(7, 1, "bf16"), (7, 3, "bf16"), (1, 1, "f16"), (0, 2, "f32"), (3, 1, "f32")])
 def test_gemm_alpha_and_bias(cfg, splits, dtype):
     """C = alpha (A B) + D + bias through each engine's epilogue and through the split-K reduce."""
