@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import TOL, relerr, to_device, to_f64, torch_dtype
+from helpers import elem_excess, TOL, relerr, to_device, to_f64, torch_dtype
 from paper_2312_03415_amd import binding as rl
 from paper_2312_03415_amd import synth
 
@@ -142,6 +142,40 @@ def test_gemm_strided_rows_and_aliased_addend():
     torch.cuda.synchronize()
     assert relerr(to_f64(C), want) < TOL[dtype]
     assert np.array_equal(to_f64(Cbuf[:, N:]), Cbh[:, N:])      # padding columns untouched
+
+
+@pytest.mark.parametrize("cfg", [6, 7])
+@pytest.mark.parametrize("layout", list(LAYOUTS))
+def test_matrix_core_kernels_with_padded_leading_dimensions(layout, cfg):
+    """Every operand a view into a wider buffer (row length < leading dimension, each padded differently), two K
+    segments, ragged M / N and K tails: the kernels' address arithmetic must use the strides, and the padding
+    columns of the output must stay untouched.  Whole-tile shape as well (the builds with the short epilogues)."""
+    import torch
+    dtype = "bf16"
+    a_str, b_kc = LAYOUTS[layout]
+    for M, N, K, K2 in ((520, 392, 200, 24), (512, 256, 192, 0)):
+        print(f"case padded ld cfg={cfg} layout={layout} M={M} N={N} K={K} K2={K2}", flush=True)
+        Abuf, Abh = make(11, 1, (K, M + 40) if a_str else (M, K + 24), dtype)
+        Bbuf, Bbh = make(11, 2, (N, K + 8) if b_kc else (K, N + 16), dtype, 1.0 / K)
+        A, Ah = (Abuf[:, :M], Abh[:, :M].copy()) if a_str else (Abuf[:, :K], Abh[:, :K].copy())
+        B, Bh = (Bbuf[:, :K], Bbh[:, :K].copy()) if b_kc else (Bbuf[:, :N], Bbh[:, :N].copy())
+        want = oracle.matmul(Ah, Bh, ta=a_str, tb=b_kc)
+        A2 = B2 = None
+        if K2 and not a_str:
+            A2buf, A2h = make(11, 4, (M, K2 + 8), dtype)
+            B2buf, B2h = make(11, 5, (N, K2 + 16) if b_kc else (K2, N + 8), dtype, 1.0 / K2)
+            A2 = A2buf[:, :K2]
+            B2, B2hv = (B2buf[:, :K2], B2h[:, :K2].copy()) if b_kc else (B2buf[:, :N], B2h[:, :N].copy())
+            want = want + oracle.matmul(A2h[:, :K2].copy(), B2hv, tb=b_kc)
+        Cbuf = torch.full((M, N + 32), 3.0, dtype=torch_dtype(dtype), device="cuda")
+        C = Cbuf[:, :N]
+        for splits in (1, 2):
+            C.fill_(float("nan"))
+            rl.runlora_gemm(A, B, C, a_strided=a_str, b_kcontig=b_kc, A2=A2, B2=B2, tile_cfg=cfg, splits=splits)
+            torch.cuda.synchronize()
+            assert relerr(to_f64(C), want) < TOL[dtype], (M, N, splits)
+            assert elem_excess(to_f64(C), want, dtype) <= 1.0, (M, N, splits)
+            assert torch.all(Cbuf[:, N:] == 3.0)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
